@@ -1,0 +1,322 @@
+"""Pins of the oracle's encoder (Algorithm 1, Section II-B): units worked by hand,
+a re-derivation from torch's CPU bfloat16 arithmetic plus brute-force nearest
+searches, the invariants the algorithm implies, canonical round trips, special
+inputs, and the MSE ratios printed in Section III-A."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_11287_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ helpers
+
+def nibbles(codes):
+    c = np.asarray(codes, dtype=np.uint8)
+    out = np.empty(c.shape[:-1] + (c.shape[-1] * 2,), np.uint8)
+    out[..., 0::2] = c & 0xF
+    out[..., 1::2] = c >> 4
+    return out
+
+
+def bf(values):
+    """float list -> BF16 patterns via torch (exact for the short values used here)."""
+    return synth.bits(torch.tensor(np.asarray(values, dtype=np.float64)).to(torch.bfloat16))
+
+
+def random_units(rng, n, kind):
+    if kind == "gauss":
+        x = rng.standard_normal((n, 64))
+    elif kind == "outlier":
+        x = rng.standard_normal((n, 64))
+        x[rng.random((n, 64)) < 0.02] *= 64
+    elif kind == "wide":
+        x = rng.standard_normal((n, 64)) * np.exp(rng.uniform(-3, 3, (n, 64)))
+    elif kind == "scales":
+        x = rng.standard_normal((n, 64)) * 2.0 ** rng.integers(-60, 24, (n, 1))
+    elif kind == "short":  # few significant bits: ties everywhere
+        x = rng.integers(-64, 65, (n, 64)) / 8.0
+    elif kind == "sparse":
+        x = rng.standard_normal((n, 64)) * (rng.random((n, 64)) < 0.1)
+    else:
+        raise ValueError(kind)
+    return synth.bits(torch.from_numpy(x).to(torch.bfloat16))
+
+
+KINDS = ["gauss", "outlier", "wide", "scales", "short", "sparse"]
+
+
+# ------------------------------------------------------------------ hand-worked units
+
+def load_units():
+    units, cur = {}, None
+    for raw in open(os.path.join(GOLD, "handworked_units.txt")):
+        t = raw.split("#")[0].split()
+        if not t:
+            continue
+        if t[0] == "unit":
+            cur = units.setdefault(t[1], {"x": {}, "meta": {}, "code": {"rne": {}, "rha": {}}, "dec": {"rne": {}}})
+        elif t[0] == "x":
+            cur["x"][int(t[1])] = float(t[2])
+        elif t[0] == "meta":
+            cur["meta"][t[1]] = int(t[2], 16)
+        elif t[0] == "code":
+            cur["code"][t[1]][int(t[2])] = int(t[3], 16)
+        elif t[0] == "dec":
+            cur["dec"][t[1]][int(t[2])] = float(t[3])
+    return units
+
+
+@pytest.mark.parametrize("name", ["seven", "ten"])
+def test_handworked_units(oracle, name):
+    u = load_units()[name]
+    x = np.zeros(64)
+    for i, v in u["x"].items():
+        x[i] = v
+    xb = bf(x)
+    assert (synth.from_bits(xb).double().numpy() == x).all(), "inputs are exact in BF16"
+    for mode_name, mode in (("rne", oracle.ROUND_RNE), ("rha", oracle.ROUND_RHA)):
+        codes, meta = oracle.encode_unit(xb, mode)
+        assert meta == u["meta"][mode_name], hex(meta)
+        want = np.zeros(64, np.uint8)
+        for i, c in u["code"][mode_name].items():
+            want[i] = c
+        assert (nibbles(codes) == want).all()
+    codes, meta = oracle.encode_unit(xb)
+    y = oracle.decode_unit(codes, meta)
+    f = oracle.bf16_bits_to_f64(y)
+    for i, v in u["dec"]["rne"].items():
+        assert f[i] == v and np.signbit(f[i]) == np.signbit(v)
+
+
+# ------------------------------------------------------------------ re-derivation
+
+E6M2_TABLE = [Fraction(4 + (b & 3), 4) * Fraction(2) ** ((b >> 2) - 48) for b in range(255)]
+S1P2_GRID = np.arange(8) / 4.0
+
+
+def rederive_unit(xb):
+    """Algorithm 1 again, from torch bfloat16 products and nearest searches."""
+    x = synth.from_bits(xb)
+    a = x.abs()
+    vmax = a.max()
+    inv7 = torch.tensor(1.0 / 7.0, dtype=torch.float64).to(torch.bfloat16)
+    sf = Fraction(float(vmax * inv7))                      # product rounded to BF16 by torch
+    if sf <= E6M2_TABLE[0]:
+        byte = 0
+    elif sf >= Fraction(7, 4) * 2 ** 15:
+        byte = 254
+    else:
+        d = [abs(t - sf) for t in E6M2_TABLE]
+        best = min(d)
+        cands = [b for b in range(255) if d[b] == best]
+        byte = cands[0] if len(cands) == 1 else [b for b in cands if b % 2 == 0][0]
+    rec = torch.tensor(float(1 / E6M2_TABLE[byte]), dtype=torch.float64).to(torch.bfloat16)
+    p = (a * rec).double().numpy()                         # 64 products rounded to BF16 by torch
+    e8 = [int(p[8 * j:8 * j + 8].max() >= 4.0) for j in range(8)]
+    e16 = [int(p[4 * k:4 * k + 4].max() * 2.0 ** -e8[k // 2] >= 2.0) for k in range(16)]
+    codes = np.zeros(64, np.uint8)
+    for i in range(64):
+        s = p[i] * 2.0 ** -(e8[i // 8] + e16[i // 4])
+        d = np.abs(S1P2_GRID - s)
+        cands = np.flatnonzero(d == d.min())
+        m = cands[0] if len(cands) == 1 else [c for c in cands if c % 2 == 0][0]
+        codes[i] = (8 if (xb[i] >> 15) else 0) | int(m)
+    meta = byte | (sum(b << j for j, b in enumerate(e8)) << 8) | (sum(b << k for k, b in enumerate(e16)) << 16)
+    return codes, meta
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_encoder_matches_rederivation(oracle, kind):
+    rng = np.random.default_rng(100 + KINDS.index(kind))
+    xs = random_units(rng, 120, kind)
+    for xb in xs:
+        codes, meta = oracle.encode_unit(xb)
+        wc, wm = rederive_unit(xb)
+        assert meta == wm, (hex(meta), hex(wm))
+        assert (nibbles(codes) == wc).all()
+
+
+# ------------------------------------------------------------------ invariants
+
+@pytest.mark.parametrize("kind", ["gauss", "outlier", "wide", "short"])
+def test_invariants(oracle, kind):
+    rng = np.random.default_rng(11)
+    xs = random_units(rng, 200, kind)
+    for xb in xs:
+        codes, meta = oracle.encode_unit(xb)
+        nib = nibbles(codes)
+        x = oracle.bf16_bits_to_f64(xb)
+        if not x.any():
+            continue
+        e8 = [(meta >> (8 + j)) & 1 for j in range(8)]
+        e16 = [(meta >> (16 + k)) & 1 for k in range(16)]
+        # the peak element sits at the top of the intra-group range
+        i = int(np.abs(x).argmax())
+        assert e8[i // 8] == 1 and e16[i // 4] == 1 and (nib[i] & 7) in (6, 7)
+        # a set level-2 bit needs a set level-3 bit under it; a set level-3 bit needs an element >= 1
+        for j in range(8):
+            if e8[j]:
+                assert e16[2 * j] or e16[2 * j + 1]
+        for k in range(16):
+            if e16[k]:
+                assert (nib[4 * k:4 * k + 4] & 7).max() >= 4
+        # error bound: half a step of the element's own scale (+ one BF16 rounding of the product)
+        y = oracle.bf16_bits_to_f64(oracle.decode_unit(codes, meta))
+        s = oracle.e6m2_to_f64(meta & 0xFF)
+        step = np.array([0.25 * s * 2.0 ** (e8[t // 8] + e16[t // 4]) for t in range(64)])
+        unclamped = (nib & 7) < 7
+        assert (np.abs(y - x)[unclamped] <= (0.5 * step + np.abs(x) * 2.0 ** -6)[unclamped]).all()
+        # negation flips sign bits only
+        c2, m2 = oracle.encode_unit(xb ^ 0x8000)
+        assert m2 == meta and (nibbles(c2) == (nib ^ 8)).all()
+        # a power-of-two rescale moves only the E6M2 exponent
+        for n in (-9, 5):
+            xs2 = synth.bits(torch.from_numpy(x * 2.0 ** n).to(torch.bfloat16))
+            c3, m3 = oracle.encode_unit(xs2)
+            assert (nibbles(c3) == nib).all() and m3 == meta + (n << 2)
+        # permuting elements inside one group of four permutes its codes only
+        k = int(rng.integers(0, 16))
+        perm = np.arange(64)
+        perm[4 * k:4 * k + 4] = 4 * k + rng.permutation(4)
+        c4, m4 = oracle.encode_unit(xb[perm])
+        assert m4 == meta and (nibbles(c4) == nib[perm]).all()
+
+
+def test_monotone_in_one_position(oracle):
+    """With the rest of the unit fixed (and the peak elsewhere), a larger input never decodes smaller."""
+    rng = np.random.default_rng(12)
+    base = rng.standard_normal(64)
+    base[0] = 9.0  # fixes the metadata
+    vals = np.sort(rng.uniform(-2.5, 2.5, 300))
+    prev = -np.inf
+    for v in vals:
+        x = base.copy()
+        x[5] = v
+        codes, meta = oracle.encode_unit(bf(x))
+        y = oracle.bf16_bits_to_f64(oracle.decode_unit(codes, meta))[5]
+        assert y >= prev
+        prev = y
+
+
+# ------------------------------------------------------------------ round trips
+
+def canonical_units(rng, n):
+    """Units already on a HiF4 grid in canonical form: the peak element is 7 * scale
+    (code 7 under two set micro-exponents), every set level-3 bit has a code >= 4 below
+    it, every set level-2 bit has a set level-3 bit below it."""
+    out = []
+    while len(out) < n:
+        nib = rng.integers(0, 16, 64).astype(np.uint8)
+        e16 = rng.integers(0, 2, 16)
+        e8 = rng.integers(0, 2, 8)
+        for k in range(16):
+            if e16[k] and (nib[4 * k:4 * k + 4] & 7).max() < 4:
+                nib[4 * k + rng.integers(0, 4)] |= 4
+        for j in range(8):
+            if e8[j] and not (e16[2 * j] or e16[2 * j + 1]):
+                e16[2 * j] = 1
+                nib[8 * j] |= 4
+        j = int(rng.integers(0, 8))
+        e8[j] = 1
+        e16[2 * j] = 1
+        nib[8 * j] |= 7
+        byte = int(rng.integers(0, 255))
+        meta = byte | (sum(int(b) << t for t, b in enumerate(e8)) << 8) | (sum(int(b) << t for t, b in enumerate(e16)) << 16)
+        out.append(((nib[0::2] | (nib[1::2] << 4)).astype(np.uint8), meta))
+    return out
+
+
+def test_round_trip_on_canonical_units(oracle):
+    rng = np.random.default_rng(13)
+    for codes, meta in canonical_units(rng, 400):
+        y = oracle.decode_unit(codes, meta)
+        c2, m2 = oracle.encode_unit(y)
+        assert m2 == meta and (c2 == codes).all()
+        assert (oracle.decode_unit(c2, m2) == y).all()
+
+
+def test_reencoding_is_not_idempotent_in_general(oracle):
+    """A unit whose peak decodes below 7 * scale can move when encoded again (7.9375 -> 7.5 -> 7.0):
+    the round trip above is a property of canonical units only."""
+    x = np.zeros(64)
+    x[0] = 7.9375
+    c1, m1 = oracle.encode_unit(bf(x))
+    y1 = oracle.decode_unit(c1, m1)
+    assert oracle.bf16_bits_to_f64(y1)[0] == 7.5
+    c2, m2 = oracle.encode_unit(y1)
+    assert oracle.bf16_bits_to_f64(oracle.decode_unit(c2, m2))[0] == 7.0
+
+
+# ------------------------------------------------------------------ special inputs
+
+def test_special_inputs(oracle):
+    z = np.zeros(64, np.uint16)
+    codes, meta = oracle.encode_unit(z)
+    assert meta == 0 and not codes.any()
+    assert not oracle.decode_unit(codes, meta).any()
+    # minus zero keeps its sign
+    z2 = z.copy()
+    z2[3] = 0x8000
+    codes, meta = oracle.encode_unit(z2)
+    assert nibbles(codes)[3] == 8 and oracle.decode_unit(codes, meta)[3] == 0x8000
+    # NaN or Inf anywhere -> the NaN unit
+    for special in (0x7FC0, 0xFFC1, 0x7F80, 0xFF80):
+        x = bf(np.linspace(-3, 3, 64))
+        x[17] = special
+        codes, meta = oracle.encode_unit(x)
+        assert meta == 0xFF and not codes.any()
+        assert np.isnan(oracle.bf16_bits_to_f64(oracle.decode_unit(codes, meta))).all()
+    # beyond the format's range: the scale saturates at its largest finite code, elements clamp
+    x = np.full(64, 1.0)
+    x[0], x[1], x[2] = 3.0e38, -2.0e30, 344064.0
+    codes, meta = oracle.encode_unit(bf(x))
+    nib = nibbles(codes)
+    assert meta & 0xFF == 0xFE and nib[0] == 7 and nib[1] == 0xF and nib[2] == 7
+    y = oracle.bf16_bits_to_f64(oracle.decode_unit(codes, meta))
+    assert y[0] == 344064.0 and y[1] == -344064.0 and y[2] == 344064.0
+    # below the format's range: the scale stops at its least code, small values flush to signed zero
+    x = np.full(64, 2.0 ** -60)
+    x[0], x[1], x[2] = 2.0 ** -50, -(2.0 ** -52), 2.0 ** -130
+    codes, meta = oracle.encode_unit(bf(x))
+    nib = nibbles(codes)
+    assert meta == 0 and nib[0] == 1 and nib[1] == 8 and nib[2] == 0 and not (nib[3:] & 7).any()
+
+
+def test_matrix_wrappers_follow_units(oracle):
+    rng = np.random.default_rng(14)
+    x = random_units(rng, 6, "outlier").reshape(2, 192)
+    big = np.zeros((2, 200), np.uint16)
+    big[:, :192] = x
+    codes, meta = oracle.quantize(big[:, :192])  # strided rows
+    for r in range(2):
+        for u in range(3):
+            c, m = oracle.encode_unit(x[r, 64 * u:64 * u + 64])
+            assert m == meta[r, u] and (c == codes[r, 32 * u:32 * u + 32]).all()
+    with pytest.raises(ValueError):
+        oracle.quantize(np.zeros((2, 100), np.uint16))
+
+
+# ------------------------------------------------------------------ Section III-A
+
+@pytest.mark.parametrize("x", [4, 11])
+def test_mse_ratios_of_section_3a(oracle, x):
+    """HiF4 : NVFP4 (with per-tensor scaling) : MXFP4 = 1 : 1.32 : 1.89 on Gaussian matrices."""
+    from oracle import bfp4_comparators as cmp
+    X = synth.gaussian_sweep(x)
+    xb = synth.bits(synth.to_bf16(X))
+    Xb = oracle.bf16_bits_to_f64(xb)
+    codes, meta = oracle.quantize(xb)
+    mse_h = np.mean((X - oracle.bf16_bits_to_f64(oracle.dequantize(codes, meta))) ** 2)
+    mse_nv = np.mean((X - cmp.nvfp4_fake_quant(Xb, pts=True)) ** 2)
+    mse_mx = np.mean((X - cmp.mxfp4_fake_quant(Xb)) ** 2)
+    assert abs(mse_nv / mse_h - 1.32) < 0.03, mse_nv / mse_h
+    assert abs(mse_mx / mse_h - 1.89) < 0.03, mse_mx / mse_h
+    # in range, the direct cast of NVFP4 agrees with the scaled one
+    mse_nv_direct = np.mean((X - cmp.nvfp4_fake_quant(Xb)) ** 2)
+    assert abs(mse_nv_direct / mse_nv - 1.0) < 0.02
