@@ -1,0 +1,140 @@
+/*
+ * libhif4 — HiFloat4 (HiF4) block floating point on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer below is a DEVICE pointer owned by the caller unless it
+ * says "host".  The library allocates nothing and keeps no state between calls;
+ * each call validates its arguments on the host, enqueues its kernels on the
+ * caller's stream (a hipStream_t passed as void*, NULL = the default stream) and
+ * returns without synchronising.  Return value: HIF4_OK or a negative error code;
+ * nothing is enqueued when an error is returned, except HIF4_ERR_DEVICE, which
+ * reports a launch failure.
+ *
+ * The format (paper: "HiFloat4 Format for Language Model Inference", Section II-A):
+ * one unit = 64 consecutive values along the reduction axis K, stored as 64 4-bit
+ * S1P2 elements plus 32 bits of scaling metadata (E6M2, E1_8, E1_16) = 36 bytes,
+ * 4.5 bits per value.  Element i (0-based) of a unit has the value (Eq. 2)
+ *     E6M2 * 2^(E1_8[i/8] + E1_16[i/4]) * S1P2[i],      all 64 NaN if E6M2 is NaN.
+ *
+ * Packed layout (version 1; the paper's figure fixing the bit order is not part of
+ * its text, so this is the library's own, documented choice) — two planes:
+ *   codes : uint8  [rows][K/2]   element 2t in the low nibble of byte t, element 2t+1
+ *                                in the high nibble; nibble = sign<<3 | integer bit<<2
+ *                                | two fraction bits (sign-magnitude, +-0 both exist).
+ *   meta  : uint32 [rows][K/64]  bits  7:0  E6M2 byte, exponent field (bias 48) in bits
+ *                                           7:2, mantissa in bits 1:0, 0xFF = NaN;
+ *                                bits 15:8  E1_8,  bit j  scales elements 8j..8j+7 by 2;
+ *                                bits 31:16 E1_16, bit k  scales elements 4k..4k+3 by 2.
+ * Rows of both planes are dense (no padding).  BF16 matrices are row-major with K
+ * contiguous and a row stride (ldx, ldy, lda) given in elements.
+ */
+#ifndef HIF4_H
+#define HIF4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HIF4_VERSION 1
+#define HIF4_UNIT 64 /* group size (Table 2) */
+
+enum {
+    HIF4_OK = 0,
+    HIF4_ERR_NULL = -1,        /* a required pointer is NULL */
+    HIF4_ERR_SHAPE = -2,       /* negative size, K not a multiple of 64, leading dimension < K, sizes over 2^31 units per row */
+    HIF4_ERR_ALIGN = -3,       /* BF16 matrices: base and row stride 16-byte aligned; codes 16-byte; meta 4-byte */
+    HIF4_ERR_UNSUPPORTED = -4, /* an enum value this build does not implement */
+    HIF4_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than hif4_gemm_workspace_bytes() */
+    HIF4_ERR_DEVICE = -6       /* the HIP runtime reported an error at launch */
+};
+
+/* Rounding used by every rounding step of the conversion (Section II-B, last
+ * paragraph: round-half-to-even or round-half-away-from-zero). */
+enum { HIF4_ROUND_RNE = 0, HIF4_ROUND_RHA = 1 };
+
+/* What the A operand of a GEMM is. */
+enum {
+    HIF4_A_BF16_QUANTIZE = 0, /* BF16 activations, converted to HiF4 inside the call (W4A4)     */
+    HIF4_A_HIF4 = 1,          /* already packed: a = codes plane, a_meta = meta plane (W4A4)      */
+    HIF4_A_BF16_KEEP = 2      /* BF16 activations used as they are (HiF4-weight-only GEMM)        */
+};
+
+enum { HIF4_OUT_BF16 = 0, HIF4_OUT_F32 = 1 };
+
+/*
+ * BF16 -> HiF4: Algorithm 1 (Section II-B) on every unit of a rows x K matrix.
+ *   stage 1  peak magnitudes 64 -> 16 -> 8 -> 1;
+ *   stage 2  SF = Vmax * (1/7)_BF16, E6M2 = BF16_to_E6M2(SF), its reciprocal by table,
+ *            E1_8[j]  = (V8[j]  * REC >= 4),  E1_16[k] = (V16[k] * REC * 2^-E1_8[k/2] >= 2);
+ *   stage 3  each element * REC * 2^-(E1_8 + E1_16), rounded to a multiple of 0.25 and
+ *            clamped to +-1.75 with its sign kept.
+ * Every product is rounded to BF16 before it is compared or converted.  E6M2 saturates
+ * at its least (0x00) and greatest finite (0xFE) codes.  A unit holding a NaN or an
+ * infinity becomes the NaN unit (meta 0x000000FF, codes 0).  The sign bit of every
+ * element, zero included, is the sign bit of its input.
+ *   x      in   BF16 [rows][ldx], ldx >= K, read only
+ *   codes  out  uint8 [rows][K/2]
+ *   meta   out  uint32 [rows][K/64]
+ * rows == 0 or K == 0 is a no-op.  x must not overlap the outputs.
+ */
+int hif4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
+                  uint8_t *codes, uint32_t *meta, int round_mode, void *stream);
+
+/*
+ * HiF4 -> BF16: Eq. 2 (Section II-A) on every unit.  Every finite HiF4 value has at
+ * most six significant bits and lies in [2^-50, 2^18 * 1.3125], so the result is
+ * exact.  NaN units give the quiet NaN 0x7FC0 in all 64 places; zero elements keep
+ * their sign.
+ *   y  out  BF16 [rows][ldy], ldy >= K
+ */
+int hif4_dequantize(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K,
+                    void *y_bf16, int64_t ldy, void *stream);
+
+/*
+ * C[M][N] = A[M][K] * W[N][K]^T with W in HiF4 (units along K) and fp32 accumulation.
+ * Between two HiF4 operands each 64-wide K step is the unit dot product of Eq. 4
+ * (Section III-B); with a_kind == HIF4_A_BF16_KEEP, A enters the products as BF16.
+ *   a          in   BF16 [M][lda] (kinds 0 and 2) or codes uint8 [M][K/2] (kind 1; lda ignored)
+ *   a_meta     in   uint32 [M][K/64] for kind 1, NULL otherwise
+ *   w_codes    in   uint8 [N][K/2];  w_meta in uint32 [N][K/64]
+ *   c          out  BF16 or fp32 [M][ldc] per out_dtype, ldc >= N
+ *   workspace       device scratch of at least hif4_gemm_workspace_bytes(a_kind, M, K)
+ *                   bytes, 16-byte aligned (holds the packed A for kind 0; may be NULL
+ *                   when that size is 0)
+ * M == 0 or N == 0 is a no-op; K == 0 writes zeros.
+ */
+int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
+              const uint8_t *w_codes, const uint32_t *w_meta,
+              int64_t M, int64_t N, int64_t K,
+              void *c, int64_t ldc, int out_dtype,
+              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Grouped (mixture-of-experts) GEMM: the rows of A are sorted by expert; expert e owns
+ * rows offs[e] .. offs[e+1]-1 and multiplies them by its own weights
+ * W[e] (w_codes [E][N][K/2], w_meta [E][N][K/64]).  offs is a DEVICE int32[E+1] array,
+ * non-decreasing, offs[0] == 0, offs[E] == total_rows; it is read by the kernels only,
+ * so no host synchronisation happens.  Experts with no rows are skipped.  Other
+ * arguments as hif4_gemm with M = total_rows.
+ */
+int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
+                      const uint8_t *w_codes, const uint32_t *w_meta,
+                      const int32_t *offs, int E, int64_t total_rows, int64_t N, int64_t K,
+                      void *c, int64_t ldc, int out_dtype,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scratch bytes hif4_gemm / hif4_grouped_gemm need for M (or total_rows) rows of A. Host function. */
+size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K);
+
+/* Static host string naming a status code. */
+const char *hif4_status_string(int status);
+
+/* HIF4_VERSION of the built library (also the version of the packed layout). */
+int hif4_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIF4_H */

@@ -1,0 +1,130 @@
+// C ABI of libhif4: host-side argument validation, then kernel launches on the
+// caller's stream.  See include/hif4.h for the contract of every entry point.
+#include "hif4_common.h"
+
+namespace hif4 {
+int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
+                  hipStream_t stream);
+int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, int64_t ldy,
+                  hipStream_t stream);
+int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
+                const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
+                int64_t ldc, int out_dtype, void *workspace, hipStream_t stream);
+} // namespace hif4
+
+namespace {
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Limits that keep every index computation inside the kernels in range.
+constexpr int64_t MAX_DIM = (int64_t)1 << 31;
+
+int check_matrix_shape(int64_t rows, int64_t K, int64_t ld)
+{
+    if (rows < 0 || K < 0 || K % HIF4_UNIT != 0 || ld < K) return HIF4_ERR_SHAPE;
+    if (rows >= MAX_DIM || K >= MAX_DIM || ld >= MAX_DIM) return HIF4_ERR_SHAPE;
+    return HIF4_OK;
+}
+
+int check_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
+               const uint32_t *w_meta, int64_t M, int64_t N, int64_t K, const void *c, int64_t ldc, int out_dtype,
+               const void *workspace, size_t workspace_bytes)
+{
+    if (a_kind != HIF4_A_BF16_QUANTIZE && a_kind != HIF4_A_HIF4 && a_kind != HIF4_A_BF16_KEEP) return HIF4_ERR_UNSUPPORTED;
+    if (out_dtype != HIF4_OUT_BF16 && out_dtype != HIF4_OUT_F32) return HIF4_ERR_UNSUPPORTED;
+    if (M < 0 || N < 0 || K < 0 || K % HIF4_UNIT != 0 || ldc < N) return HIF4_ERR_SHAPE;
+    if (M >= MAX_DIM || N >= MAX_DIM || K >= MAX_DIM || ldc >= MAX_DIM) return HIF4_ERR_SHAPE;
+    if (a_kind != HIF4_A_HIF4 && (lda < K || lda >= MAX_DIM)) return HIF4_ERR_SHAPE;
+    if (M == 0 || N == 0) return HIF4_OK;
+    if (!c) return HIF4_ERR_NULL;
+    if (K > 0) {
+        if (!a || !w_codes || !w_meta) return HIF4_ERR_NULL;
+        if (a_kind == HIF4_A_HIF4 && !a_meta) return HIF4_ERR_NULL;
+    }
+    if (!aligned(a, 16) || !aligned(w_codes, 16) || !aligned(w_meta, 4) || !aligned(a_meta, 4)) return HIF4_ERR_ALIGN;
+    if (a_kind != HIF4_A_HIF4 && (lda % 8) != 0) return HIF4_ERR_ALIGN;
+    if (!aligned(c, out_dtype == HIF4_OUT_BF16 ? 2 : 4)) return HIF4_ERR_ALIGN;
+    const size_t need = hif4_gemm_workspace_bytes(a_kind, M, K);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return HIF4_ERR_WORKSPACE;
+        if (!aligned(workspace, 16)) return HIF4_ERR_ALIGN;
+    }
+    return HIF4_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int hif4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta,
+                  int round_mode, void *stream)
+{
+    if (round_mode != HIF4_ROUND_RNE && round_mode != HIF4_ROUND_RHA) return HIF4_ERR_UNSUPPORTED;
+    if (int rc = check_matrix_shape(rows, K, ldx)) return rc;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    if (!x_bf16 || !codes || !meta) return HIF4_ERR_NULL;
+    if (!aligned(x_bf16, 16) || (ldx % 8) != 0 || !aligned(codes, 16) || !aligned(meta, 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_encode(x_bf16, rows, K, ldx, codes, meta, round_mode, static_cast<hipStream_t>(stream));
+}
+
+int hif4_dequantize(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y_bf16, int64_t ldy,
+                    void *stream)
+{
+    if (int rc = check_matrix_shape(rows, K, ldy)) return rc;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    if (!y_bf16 || !codes || !meta) return HIF4_ERR_NULL;
+    if (!aligned(y_bf16, 16) || (ldy % 8) != 0 || !aligned(codes, 16) || !aligned(meta, 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_decode(codes, meta, rows, K, y_bf16, ldy, static_cast<hipStream_t>(stream));
+}
+
+size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K)
+{
+    if (a_kind != HIF4_A_BF16_QUANTIZE || M_or_total_rows <= 0 || K <= 0 || K % HIF4_UNIT != 0) return 0;
+    // packed A: codes plane (rounded up to 16 bytes) followed by the meta plane
+    const size_t codes = (size_t)M_or_total_rows * (size_t)K / 2;
+    const size_t meta = (size_t)M_or_total_rows * (size_t)(K / HIF4_UNIT) * sizeof(uint32_t);
+    return ((codes + 15) & ~(size_t)15) + meta;
+}
+
+int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
+              const uint32_t *w_meta, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype,
+              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, workspace, workspace_bytes))
+        return rc;
+    if (M == 0 || N == 0) return HIF4_OK;
+    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, nullptr, 1, M, N, K, c, ldc, out_dtype, workspace,
+                             static_cast<hipStream_t>(stream));
+}
+
+int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
+                      const uint32_t *w_meta, const int32_t *offs, int E, int64_t total_rows, int64_t N, int64_t K,
+                      void *c, int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (E < 0) return HIF4_ERR_SHAPE;
+    if (int rc = check_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, total_rows, N, K, c, ldc, out_dtype, workspace, workspace_bytes))
+        return rc;
+    if (total_rows == 0 || N == 0 || E == 0) return HIF4_OK;
+    if (!offs) return HIF4_ERR_NULL;
+    if (!aligned(offs, 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, offs, E, total_rows, N, K, c, ldc, out_dtype,
+                             workspace, static_cast<hipStream_t>(stream));
+}
+
+const char *hif4_status_string(int status)
+{
+    switch (status) {
+    case HIF4_OK: return "ok";
+    case HIF4_ERR_NULL: return "null pointer";
+    case HIF4_ERR_SHAPE: return "bad shape (negative, K not a multiple of 64, leading dimension too small, or too large)";
+    case HIF4_ERR_ALIGN: return "misaligned pointer or leading dimension";
+    case HIF4_ERR_UNSUPPORTED: return "unsupported enum value";
+    case HIF4_ERR_WORKSPACE: return "workspace missing or too small";
+    case HIF4_ERR_DEVICE: return "HIP launch error";
+    default: return "unknown status";
+    }
+}
+
+int hif4_version(void) { return HIF4_VERSION; }
+
+} // extern "C"

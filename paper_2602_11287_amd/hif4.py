@@ -1,0 +1,159 @@
+"""Thin Python binding of the libhif4 C ABI (see include/hif4.h).
+
+Argument marshalling only: every step of the HiF4 path runs in the HIP kernels of
+``libhif4.so``.  PyTorch supplies device memory and the current stream.  There is
+no CPU fallback: if the shared library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhif4.so")
+
+HIF4_OK = 0
+HIF4_ERR_NULL, HIF4_ERR_SHAPE, HIF4_ERR_ALIGN = -1, -2, -3
+HIF4_ERR_UNSUPPORTED, HIF4_ERR_WORKSPACE, HIF4_ERR_DEVICE = -4, -5, -6
+HIF4_ROUND_RNE, HIF4_ROUND_RHA = 0, 1
+HIF4_A_BF16_QUANTIZE, HIF4_A_HIF4, HIF4_A_BF16_KEEP = 0, 1, 2
+HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
+
+EXPORTS = ["hif4_quantize", "hif4_dequantize", "hif4_gemm", "hif4_grouped_gemm",
+           "hif4_gemm_workspace_bytes", "hif4_status_string", "hif4_version"]
+
+
+class Hif4Error(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {hif4_status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load():
+    """Load libhif4.so (built in-tree by paper_2602_11287_amd/build.py); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+        L.hif4_quantize.restype = i32
+        L.hif4_quantize.argtypes = [vp, i64, i64, i64, vp, vp, i32, vp]
+        L.hif4_dequantize.restype = i32
+        L.hif4_dequantize.argtypes = [vp, vp, i64, i64, vp, i64, vp]
+        L.hif4_gemm.restype = i32
+        L.hif4_gemm.argtypes = [i32, vp, vp, i64, vp, vp, i64, i64, i64, vp, i64, i32, vp, sz, vp]
+        L.hif4_grouped_gemm.restype = i32
+        L.hif4_grouped_gemm.argtypes = [i32, vp, vp, i64, vp, vp, vp, i32, i64, i64, i64, vp, i64, i32, vp, sz, vp]
+        L.hif4_gemm_workspace_bytes.restype = sz
+        L.hif4_gemm_workspace_bytes.argtypes = [i32, i64, i64]
+        L.hif4_status_string.restype = C.c_char_p
+        L.hif4_status_string.argtypes = [i32]
+        L.hif4_version.restype = i32
+        L.hif4_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(status, where):
+    if status != HIF4_OK:
+        raise Hif4Error(status, where)
+
+
+def hif4_version():
+    return load().hif4_version()
+
+
+def hif4_status_string(status):
+    return load().hif4_status_string(int(status)).decode()
+
+
+def hif4_gemm_workspace_bytes(a_kind, rows, K):
+    return int(load().hif4_gemm_workspace_bytes(int(a_kind), int(rows), int(K)))
+
+
+def hif4_quantize(x, codes=None, meta=None, round_mode=HIF4_ROUND_RNE, stream=None):
+    """x: CUDA bfloat16 [rows, K] (rows may be strided) -> (codes uint8 [rows, K/2], meta int32 [rows, K/64])."""
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
+    rows, K = x.shape
+    if codes is None:
+        codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    if meta is None:
+        meta = torch.empty((rows, K // 64), dtype=torch.int32, device=x.device)
+    ldx = x.stride(0) if rows > 1 else max(x.stride(0), K)
+    _check(load().hif4_quantize(_ptr(x), rows, K, ldx, _ptr(codes), _ptr(meta), round_mode, _stream(stream)),
+           "hif4_quantize")
+    return codes, meta
+
+
+def hif4_dequantize(codes, meta, y=None, stream=None):
+    """codes uint8 [rows, K/2], meta int32 [rows, K/64] -> CUDA bfloat16 [rows, K]."""
+    assert codes.is_cuda and codes.dtype == torch.uint8 and codes.is_contiguous()
+    assert meta.dtype == torch.int32 and meta.is_contiguous()
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    if y is None:
+        y = torch.empty((rows, K), dtype=torch.bfloat16, device=codes.device)
+    ldy = y.stride(0) if rows > 1 else max(y.stride(0), K)
+    _check(load().hif4_dequantize(_ptr(codes), _ptr(meta), rows, K, _ptr(y), ldy, _stream(stream)), "hif4_dequantize")
+    return y
+
+
+def _gemm_common(a_kind, a, a_meta, w_codes, M, K):
+    assert w_codes.dtype == torch.uint8 and w_codes.is_contiguous() and w_codes.shape[-1] * 2 == K
+    if a_kind == HIF4_A_HIF4:
+        assert a.dtype == torch.uint8 and a.is_contiguous() and a_meta is not None
+        return K
+    assert a.dtype == torch.bfloat16 and a.stride(1) == 1
+    return a.stride(0) if M > 1 else max(a.stride(0), K)
+
+
+def hif4_gemm(a_kind, a, a_meta, w_codes, w_meta, out_dtype=HIF4_OUT_BF16, c=None, workspace=None, stream=None):
+    """C[M, N] = A[M, K] @ W[N, K]^T, W (and for W4A4 also A) in HiF4; fp32 accumulation."""
+    M = a.shape[0]
+    K = a.shape[1] * 2 if a_kind == HIF4_A_HIF4 else a.shape[1]
+    N = w_codes.shape[0]
+    lda = _gemm_common(a_kind, a, a_meta, w_codes, M, K)
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16 if out_dtype == HIF4_OUT_BF16 else torch.float32, device=a.device)
+    need = hif4_gemm_workspace_bytes(a_kind, M, K)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ldc = c.stride(0) if M > 1 else max(c.stride(0), N)
+    _check(load().hif4_gemm(a_kind, _ptr(a), _ptr(a_meta), lda, _ptr(w_codes), _ptr(w_meta), M, N, K, _ptr(c), ldc,
+                            out_dtype, _ptr(workspace), wsz, _stream(stream)), "hif4_gemm")
+    return c
+
+
+def hif4_grouped_gemm(a_kind, a, a_meta, w_codes, w_meta, offs, out_dtype=HIF4_OUT_BF16, c=None, workspace=None,
+                      stream=None):
+    """Rows of A sorted by expert; expert e owns rows offs[e]..offs[e+1]-1 and weights w_codes[e] ([E, N, K/2])."""
+    M = a.shape[0]
+    K = a.shape[1] * 2 if a_kind == HIF4_A_HIF4 else a.shape[1]
+    E, N = w_codes.shape[0], w_codes.shape[1]
+    assert offs.dtype == torch.int32 and offs.is_cuda and offs.numel() == E + 1
+    lda = _gemm_common(a_kind, a, a_meta, w_codes, M, K)
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16 if out_dtype == HIF4_OUT_BF16 else torch.float32, device=a.device)
+    need = hif4_gemm_workspace_bytes(a_kind, M, K)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ldc = c.stride(0) if M > 1 else max(c.stride(0), N)
+    _check(load().hif4_grouped_gemm(a_kind, _ptr(a), _ptr(a_meta), lda, _ptr(w_codes), _ptr(w_meta), _ptr(offs), E, M,
+                                    N, K, _ptr(c), ldc, out_dtype, _ptr(workspace), wsz, _stream(stream)),
+           "hif4_grouped_gemm")
+    return c

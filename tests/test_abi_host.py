@@ -1,0 +1,108 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2602_11287_amd import build, hif4
+    if build.stale():
+        build.build()
+    return hif4.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "hif4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hif4_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2602_11287_amd import hif4
+    names = declared_functions()
+    assert sorted(hif4.EXPORTS) == names
+    for n in names:
+        assert hasattr(lib, n), n
+        assert hasattr(hif4, n), f"binding lacks {n}"
+
+
+def test_version_and_status_strings(lib):
+    from paper_2602_11287_amd import hif4
+    assert hif4.hif4_version() == 1
+    for s in range(0, -7, -1):
+        assert hif4.hif4_status_string(s) != "unknown status"
+    assert hif4.hif4_status_string(-99) == "unknown status"
+
+
+def test_quantize_argument_errors(lib):
+    from paper_2602_11287_amd import hif4 as h
+    q = lib.hif4_quantize
+    p = 0x1000  # never dereferenced: every call below fails validation or is a no-op
+    assert q(p, 4, 100, 100, p, p, 0, None) == h.HIF4_ERR_SHAPE      # K not a multiple of 64
+    assert q(p, -1, 128, 128, p, p, 0, None) == h.HIF4_ERR_SHAPE
+    assert q(p, 4, 128, 64, p, p, 0, None) == h.HIF4_ERR_SHAPE       # ldx < K
+    assert q(p, 4, 128, 128, p, p, 7, None) == h.HIF4_ERR_UNSUPPORTED
+    assert q(None, 4, 128, 128, p, p, 0, None) == h.HIF4_ERR_NULL
+    assert q(p, 4, 128, 128, None, p, 0, None) == h.HIF4_ERR_NULL
+    assert q(p + 2, 4, 128, 128, p, p, 0, None) == h.HIF4_ERR_ALIGN
+    assert q(p, 4, 128, 132, p, p, 0, None) == h.HIF4_ERR_ALIGN      # row stride not 16-byte
+    assert q(p, 4, 128, 128, p, p + 1, 0, None) == h.HIF4_ERR_ALIGN
+    assert q(None, 0, 128, 128, None, None, 0, None) == h.HIF4_OK    # empty: no-op
+    assert q(None, 5, 0, 0, None, None, 0, None) == h.HIF4_OK
+
+
+def test_dequantize_argument_errors(lib):
+    from paper_2602_11287_amd import hif4 as h
+    d = lib.hif4_dequantize
+    p = 0x1000
+    assert d(p, p, 4, 96, p, 96, None) == h.HIF4_ERR_SHAPE
+    assert d(p, p, 4, 128, p, 64, None) == h.HIF4_ERR_SHAPE
+    assert d(p, None, 4, 128, p, 128, None) == h.HIF4_ERR_NULL
+    assert d(p, p, 4, 128, p + 4, 128, None) == h.HIF4_ERR_ALIGN
+    assert d(None, None, 0, 128, None, 128, None) == h.HIF4_OK
+
+
+def test_gemm_argument_errors(lib):
+    from paper_2602_11287_amd import hif4 as h
+    g, gg = lib.hif4_gemm, lib.hif4_grouped_gemm
+    p = 0x1000
+    ok = dict(a_kind=h.HIF4_A_HIF4, a=p, a_meta=p, lda=256, w=p, wm=p, M=8, N=16, K=256, c=p, ldc=16, out=1, ws=None, wsz=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return g(a["a_kind"], a["a"], a["a_meta"], a["lda"], a["w"], a["wm"], a["M"], a["N"], a["K"], a["c"], a["ldc"],
+                 a["out"], a["ws"], a["wsz"], None)
+
+    assert call(a_kind=9) == h.HIF4_ERR_UNSUPPORTED
+    assert call(out=5) == h.HIF4_ERR_UNSUPPORTED
+    assert call(K=100) == h.HIF4_ERR_SHAPE
+    assert call(ldc=8) == h.HIF4_ERR_SHAPE
+    assert call(a_kind=h.HIF4_A_BF16_KEEP, lda=128) == h.HIF4_ERR_SHAPE
+    assert call(a_meta=None) == h.HIF4_ERR_NULL
+    assert call(w=None) == h.HIF4_ERR_NULL
+    assert call(c=None) == h.HIF4_ERR_NULL
+    assert call(w=p + 4) == h.HIF4_ERR_ALIGN
+    assert call(M=0) == h.HIF4_OK and call(N=0) == h.HIF4_OK
+    # quantise-inside-the-call needs a workspace of the advertised size
+    need = lib.hif4_gemm_workspace_bytes(h.HIF4_A_BF16_QUANTIZE, 8, 256)
+    assert need == 8 * 128 + 8 * 4 * 4
+    assert lib.hif4_gemm_workspace_bytes(h.HIF4_A_HIF4, 8, 256) == 0
+    assert lib.hif4_gemm_workspace_bytes(h.HIF4_A_BF16_KEEP, 8, 256) == 0
+    assert call(a_kind=h.HIF4_A_BF16_QUANTIZE, a_meta=None) == h.HIF4_ERR_WORKSPACE
+    assert call(a_kind=h.HIF4_A_BF16_QUANTIZE, a_meta=None, ws=p, wsz=need - 1) == h.HIF4_ERR_WORKSPACE
+    # grouped: offsets are required once there is work
+    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, 4, 8, 16, 256, p, 16, 1, None, 0, None) == h.HIF4_ERR_NULL
+    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, -1, 8, 16, 256, p, 16, 1, None, 0, None) == h.HIF4_ERR_SHAPE
+    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, 0, 8, 16, 256, p, 16, 1, None, 0, None) == h.HIF4_OK
+
+
+def test_product_path_has_no_cpu_fallback():
+    """The binding imports neither the oracle nor any CPU implementation."""
+    src = open(os.path.join(ROOT, "paper_2602_11287_amd", "hif4.py")).read()
+    assert "oracle" not in src.replace("no CPU fallback", "")
