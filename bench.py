@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the libhif4 hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one pass of the HiF4 hot path over one batch of seeded synthetic input
+already resident in HBM: hif4_quantize (Algorithm 1) then hif4_dequantize (Eq. 2)
+over a batch of 64 distinct 1024 x 4096 BF16 activation matrices (512 MiB, so the
+traffic really comes from HBM and not from the 256 MB last-level cache), followed,
+once per step as well, by the GEMM legs that consume HiF4 units.  The headline
+value is the encode+decode throughput in GB/s at 164 algorithmic bytes per unit and
+direction; the GEMM legs report TFLOP/s at 2*M*N*K.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense BF16 MFMA, published
+BYTES_PER_UNIT = 164          # 128 B of BF16 + 36 B of packed unit, either direction
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-gemm", action="store_true", help="time the encode/decode legs only")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain device copy of the 512 MiB batch (known size) for counter scaling")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2602_11287_amd import build as lib_build
+    from paper_2602_11287_amd import hif4, synth
+
+    if not os.path.exists(hif4.LIB_PATH):
+        lib_build.build()
+    hif4.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- workload: 64 distinct copies of the 1024 x 4096 activation matrix ----------
+    copies, rows1, K = 64, 1024, 4096
+    base = synth.activation_with_outliers(rows=rows1, K=K)            # the seeded CPU tensor (also the oracle's input)
+    x = torch.empty((copies * rows1, K), dtype=torch.bfloat16, device=dev)
+    g = torch.Generator(device=dev).manual_seed(synth.BASE_SEED)
+    x[:rows1] = base.to(dev)
+    for c in range(1, copies):                                        # other copies: same recipe, device-side draws
+        blk = torch.randn((rows1, K), generator=g, device=dev, dtype=torch.float32)
+        blk[torch.rand((rows1, K), generator=g, device=dev) < 0.001] *= 64.0
+        x[c * rows1:(c + 1) * rows1] = blk.to(torch.bfloat16)
+    rows = copies * rows1
+    units = rows * K // 64
+    codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=dev)
+    meta = torch.empty((rows, K // 64), dtype=torch.int32, device=dev)
+    y = torch.empty_like(x)
+
+    def step():
+        hif4.hif4_quantize(x, codes, meta)
+        hif4.hif4_dequantize(codes, meta, y)
+
+    if args.pmc_calibration:
+        y.copy_(x)  # reads rows*K*2 bytes, writes as many: the yardstick for FETCH_SIZE / WRITE_SIZE
+        torch.cuda.synchronize()
+
+    def timed(fn, n):
+        """Average duration of n back-to-back calls of fn on the current stream, by HIP events."""
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step_ms = timed(step, args.steps)                       # the timed region: exactly K steps
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # per-kernel launch durations for the roofline entries, same launches, same stream
+    enc_ms = timed(lambda: hif4.hif4_quantize(x, codes, meta), args.steps)
+    dec_ms = timed(lambda: hif4.hif4_dequantize(codes, meta, y), args.steps)
+    bytes_dir = units * BYTES_PER_UNIT
+    enc_gbps = bytes_dir / enc_ms / 1e6
+    dec_gbps = bytes_dir / dec_ms / 1e6
+    value = 2 * bytes_dir / step_ms / 1e6
+
+    # correctness of what was just timed: first copy against the oracle is done by the tests;
+    # here only a cheap device-side sanity check that decode(encode(x)) is close to x
+    err = (y[:rows1].float() - x[:rows1].float()).pow(2).sum().item()
+    ref = x[:rows1].float().pow(2).sum().item()
+    sqnr_db = 10.0 * np.log10(ref / err)
+
+    dom = ("hif4::encode_kernel", enc_ms, enc_gbps) if enc_ms >= dec_ms else ("hif4::decode_kernel", dec_ms, dec_gbps)
+    out = {
+        "metric": "HiF4 encode/decode GB/s (% HBM peak)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "encode+decode round trip of 64 distinct 1024x4096 bf16 activation matrices "
+                               "(N(0,1), 0.1% entries x64), 512 MiB resident in HBM, units along K",
+                   "rows": rows, "K": K, "units": units, "bytes_per_unit_per_direction": BYTES_PER_UNIT},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 1),
+        "legs": {
+            "encode": {"ms": round(enc_ms, 4), "GBps": round(enc_gbps, 1), "pct_hbm_peak": round(100 * enc_gbps / HBM_PEAK_GBPS, 1)},
+            "decode": {"ms": round(dec_ms, 4), "GBps": round(dec_gbps, 1), "pct_hbm_peak": round(100 * dec_gbps / HBM_PEAK_GBPS, 1)},
+            "host_wall_ms_per_step": round(wall_ms, 4),
+            "sqnr_db_first_copy": round(float(sqnr_db), 2),
+        },
+        "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[2], 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(dom[2] / HBM_PEAK_GBPS, 4), "traffic": None},
+    }
+
+    if not args.no_gemm:
+        try:
+            from paper_2602_11287_amd import bench_gemm
+            out["legs"].update(bench_gemm.run(hif4, synth, dev, args.steps, args.warmup, MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBPS))
+        except ImportError:
+            pass
+
+    if not args.no_cpu_baseline:
+        import oracle
+        xb = synth.bits(base)
+        oracle.quantize(xb[:64])  # warm
+        reps, spent = 0, 0.0
+        while spent < 10.0 and reps < 8:
+            t = time.perf_counter()
+            wc, wm = oracle.quantize(xb)
+            oracle.dequantize(wc, wm)
+            spent += time.perf_counter() - t
+            reps += 1
+        cpu_gbps = reps * 2 * (rows1 * K // 64) * BYTES_PER_UNIT / spent / 1e9
+        out["cpu_baseline"] = {"value": round(cpu_gbps, 4), "unit": "GB/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"{reps} x encode+decode of one 1024x4096 matrix (65536 units), OpenMP over rows"}
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

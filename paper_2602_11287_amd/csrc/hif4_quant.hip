@@ -53,53 +53,55 @@ __device__ __forceinline__ float e6m2_reciprocal(uint32_t e6)
     return u2f((expf << 23) | (mant << 16));
 }
 
-// Scaled magnitude (BF16 value held in the top half of an fp32 pattern, sign
-// cleared) -> S1P2 magnitude 0..7 after division by 2^sh.
-//   clampc = pattern of 1.75 * 2^sh, scale = 2^-sh (RNE) or 2^(2-sh) (RHA).
-template <int MODE>
-__device__ __forceinline__ uint32_t s1p2_magnitude(uint32_t abits, uint32_t clampc, float scale)
-{
-    float t = u2f(umin(abits, clampc)); // positive patterns order like integers
-    if (MODE == HIF4_ROUND_RNE) {
-        // 1.5 * 2^21 has an ulp of 0.25: the add rounds to the S1P2 grid, ties to even
-        return f2u(__builtin_fmaf(t, scale, 3145728.0f)) & 7u;
-    }
-    return (uint32_t)__builtin_fmaf(t, scale, 0.5f); // truncation of x*4 + 0.5
-}
-
 // ------------------------------------------------------------------ encoder
 
-template <int LPU, int MODE, bool CONTIG>
-__global__ __launch_bounds__(256) void encode_kernel(const uint16_t *__restrict__ x, int64_t units, int64_t upr,
-                                                     int64_t ldx, uint32_t *__restrict__ codes,
-                                                     uint32_t *__restrict__ meta)
+template <bool NT>
+__device__ __forceinline__ uint4 load16(const void *p)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 *q = static_cast<const u32x4 *>(p);
+    u32x4 v = NT ? __builtin_nontemporal_load(q) : *q;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <bool NT>
+__device__ __forceinline__ void store16(void *p, uint4 v)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 t = { v.x, v.y, v.z, v.w };
+    if (NT) __builtin_nontemporal_store(t, static_cast<u32x4 *>(p));
+    else *static_cast<u32x4 *>(p) = t;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store4(uint32_t *p, uint32_t v)
+{
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// Algorithm 1 for the share of one unit that this lane holds (NCH chunks of 8 elements,
+// chunk c being group-of-8 number c*LPU + l of the unit).  Returns the packed codes of
+// the lane's chunks and the complete metadata word.
+template <int LPU, int MODE>
+__device__ __forceinline__ uint32_t encode_share(const uint4 (&w)[8 / LPU], int l, uint32_t (&out)[8 / LPU])
 {
     constexpr int NCH = 8 / LPU; // chunks of 8 elements per lane
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t unit_raw = tid / LPU;
-    const int l = (int)(tid % LPU);
-    const bool live = unit_raw < units;
-    const int64_t unit = live ? unit_raw : units - 1; // dead lanes redo the last unit, store nothing
-
-    const uint16_t *src;
-    if (CONTIG) {
-        src = x + unit * 64;
-    } else {
-        const int64_t row = unit / upr;
-        src = x + row * ldx + (unit - row * upr) * 64;
-    }
-
-    uint4 w[NCH];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) w[c] = *reinterpret_cast<const uint4 *>(src + 8 * (c * LPU + l));
 
     // Stage 1: peak magnitudes as BF16 patterns (they order like unsigned integers).
+    uint32_t am[NCH][4]; // |x| pairs, reused by stage 3
     uint32_t v16a[NCH], v16b[NCH], v8[NCH];
     uint32_t vmax = 0;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const uint32_t m01 = pk_max_u16(w[c].x & 0x7FFF7FFFu, w[c].y & 0x7FFF7FFFu);
-        const uint32_t m23 = pk_max_u16(w[c].z & 0x7FFF7FFFu, w[c].w & 0x7FFF7FFFu);
+        am[c][0] = w[c].x & 0x7FFF7FFFu;
+        am[c][1] = w[c].y & 0x7FFF7FFFu;
+        am[c][2] = w[c].z & 0x7FFF7FFFu;
+        am[c][3] = w[c].w & 0x7FFF7FFFu;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(am[c][t])); // keep the masked value, do not re-derive it
+        const uint32_t m01 = pk_max_u16(am[c][0], am[c][1]);
+        const uint32_t m23 = pk_max_u16(am[c][2], am[c][3]);
         v16a[c] = umax(m01 & 0xFFFFu, m01 >> 16);
         v16b[c] = umax(m23 & 0xFFFFu, m23 >> 16);
         v8[c] = umax(v16a[c], v16b[c]);
@@ -115,45 +117,70 @@ __global__ __launch_bounds__(256) void encode_kernel(const uint16_t *__restrict_
     const uint32_t e6 = bf16_to_e6m2<MODE>(sfb);
     const float rec = e6m2_reciprocal(e6);
 
+    // BF16(V * REC) >= 4 holds exactly when V >= 4 * E6M2 (the product 4 * E6M2 * REC is at or
+    // above the rounding boundary 4 - 2^-7 for each of the four table entries, the BF16 just
+    // below 4 * E6M2 falls under it, and rounding is monotone), likewise for 2: the
+    // multiply-compare steps become integer compares of BF16 patterns.
+    const uint32_t S = (e6 << 5) + (79u << 7); // BF16 pattern of the E6M2 value
+    const uint32_t thr2 = S + 0x80u, thr4 = S + 0x100u;
+
+    // Rebias constants for the three possible divisors 2^0, 2^1, 2^2 (see stage 3 below).
+    constexpr uint32_t RB0 = 0x38003800u, RBSTEP = 0x00800080u;
+
     uint32_t mbits = 0; // this lane's share of E1_8 (bits 8..15) and E1_16 (bits 16..31)
-    uint32_t out[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int j = c * LPU + l; // index of this group of 8 inside the unit
-        const uint32_t p8 = round_bf16<MODE>(u2f(v8[c] << 16) * rec);
-        const uint32_t pa = round_bf16<MODE>(u2f(v16a[c] << 16) * rec);
-        const uint32_t pb = round_bf16<MODE>(u2f(v16b[c] << 16) * rec);
-        const uint32_t e8 = p8 >= 0x4080u ? 1u : 0u;                         // >= 4
-        const uint32_t e16a = (int)pa - (int)(e8 << 7) >= 0x4000 ? 1u : 0u;  // * 2^-E1_8 >= 2
-        const uint32_t e16b = (int)pb - (int)(e8 << 7) >= 0x4000 ? 1u : 0u;
-        mbits |= (e8 << (8 + j)) | (e16a << (16 + 2 * j)) | (e16b << (17 + 2 * j));
+        const bool b8 = v8[c] >= thr4;
+        const uint32_t thr16 = b8 ? thr4 : thr2; // V16 * REC * 2^-E1_8 >= 2
+        const bool ba = v16a[c] >= thr16, bb = v16b[c] >= thr16;
+        mbits |= ((b8 ? 1u : 0u) << (8 + j)) | (((ba ? 1u : 0u) | (bb ? 2u : 0u)) << (16 + 2 * j));
 
-        // Stage 3: scale, round to BF16, divide by 2^(E1_8+E1_16), round to S1P2.
-        const uint32_t sha = e8 + e16a, shb = e8 + e16b;
-        const uint32_t base = MODE == HIF4_ROUND_RNE ? 0x3F800000u : 0x40800000u; // 1 or 4
-        const uint32_t ca = 0x3FE00000u + (sha << 23), cb = 0x3FE00000u + (shb << 23);
-        const float sa = u2f(base - (sha << 23)), sb = u2f(base - (shb << 23));
-        const uint32_t ww[4] = { w[c].x, w[c].y, w[c].z, w[c].w };
-        uint32_t mag[2]; // byte t of mag[h] = magnitude of element 4h + t
+        // Stage 3: scale, round to BF16, divide by 2^(E1_8+E1_16), clamp, round to S1P2.
+        // Magnitudes only: the sign bits are copied from the inputs further down.
+        uint32_t mag0, mag1; // byte t of mag0 = magnitude of element t, of mag1 = element 4 + t
+        if (MODE == HIF4_ROUND_RNE) {
+            // Packed fp16 arithmetic, two elements per instruction.  A BF16 magnitude p (8
+            // significant bits) divided by 2^sh and clamped to 1.75 is exact in fp16: subtract
+            // (112 + sh) << 7 from the pattern with saturation (exponent rebias 127 -> 15 and the
+            // division; patterns below 2^(sh-14) become 0 or tiny, far under the first rounding
+            // boundary 0.125), clamp to the rebiased 1.75, move the 7 mantissa bits up by 3.
+            // 384 = 1.5 * 2^8 has an fp16 ulp of 0.25: adding it rounds to the S1P2 grid with
+            // ties to even and leaves the count of quarter steps in the low mantissa bits.
+            const uint32_t rb_lo = b8 ? RB0 + RBSTEP : RB0, rb_hi = b8 ? RB0 + 2 * RBSTEP : RB0 + RBSTEP;
+            const uint32_t rba = ba ? rb_hi : rb_lo, rbb = bb ? rb_hi : rb_lo;
+            uint32_t r[4];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t cc = h ? cb : ca;
-            const float ss = h ? sb : sa;
-            uint32_t acc = 0;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const uint32_t d = ww[2 * h + t];
-                const uint32_t P = round_bf16_pair<MODE>(u2f(d << 16) * rec, u2f(d & 0xFFFF0000u) * rec);
-                const uint32_t m_lo = s1p2_magnitude<MODE>((P << 16) & 0x7FFFFFFFu, cc, ss);
-                const uint32_t m_hi = s1p2_magnitude<MODE>(P & 0x7FFF0000u, cc, ss);
-                acc |= (m_lo | (m_hi << 8)) << (16 * t);
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t a = am[c][t];
+                const uint32_t P = round_bf16_pair<MODE>(u2f(a << 16) * rec, u2f(a & 0xFFFF0000u) * rec);
+                const uint32_t H = pk_shl3_u16(pk_min_u16(pk_sub_sat_u16(P, t < 2 ? rba : rbb), 0x07E007E0u));
+                r[t] = pk_add_f16(H, 0x5E005E00u);
             }
-            mag[h] = acc;
+            mag0 = __builtin_amdgcn_perm(r[1], r[0], 0x06040200u);
+            mag1 = __builtin_amdgcn_perm(r[3], r[2], 0x06040200u);
+        } else {
+            const uint32_t sha = (b8 ? 1u : 0u) + (ba ? 1u : 0u), shb = (b8 ? 1u : 0u) + (bb ? 1u : 0u);
+            const uint32_t ca = (0x3FE0u + (sha << 7)) * 0x00010001u; // BF16 pair of 1.75 * 2^sh
+            const uint32_t cb = (0x3FE0u + (shb << 7)) * 0x00010001u;
+            const float sa = u2f(0x40800000u - (sha << 23)), sb = u2f(0x40800000u - (shb << 23)); // 2^(2-sh)
+            uint32_t r[8];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t a = am[c][t];
+                const uint32_t P = round_bf16_pair<MODE>(u2f(a << 16) * rec, u2f(a & 0xFFFF0000u) * rec);
+                const uint32_t Pc = pk_min_u16(P, t < 2 ? ca : cb); // patterns order like integers
+                // truncation of t * 4 + 0.5 rounds half away from zero
+                r[2 * t] = (uint32_t)__builtin_fmaf(u2f(Pc << 16), t < 2 ? sa : sb, 0.5f);
+                r[2 * t + 1] = (uint32_t)__builtin_fmaf(u2f(Pc & 0xFFFF0000u), t < 2 ? sa : sb, 0.5f);
+            }
+            mag0 = __builtin_amdgcn_perm(r[1], r[0], 0x0C0C0400u) | __builtin_amdgcn_perm(r[3], r[2], 0x04000C0Cu);
+            mag1 = __builtin_amdgcn_perm(r[5], r[4], 0x0C0C0400u) | __builtin_amdgcn_perm(r[7], r[6], 0x04000C0Cu);
         }
+        const uint32_t ww[4] = { w[c].x, w[c].y, w[c].z, w[c].w };
         // sign bits: top bit of each BF16 -> bit 3 of the element's byte
-        const uint32_t s0 = (__builtin_amdgcn_perm(ww[1], ww[0], 0x07050301u) >> 4) & 0x08080808u;
-        const uint32_t s1 = (__builtin_amdgcn_perm(ww[3], ww[2], 0x07050301u) >> 4) & 0x08080808u;
-        const uint32_t b0 = mag[0] | s0, b1 = mag[1] | s1;
+        const uint32_t b0 = ((__builtin_amdgcn_perm(ww[1], ww[0], 0x07050301u) >> 4) & 0x08080808u) | mag0;
+        const uint32_t b1 = ((__builtin_amdgcn_perm(ww[3], ww[2], 0x07050301u) >> 4) & 0x08080808u) | mag1;
         // bytes -> nibbles: byte0|byte1<<4 lands in byte 0, byte2|byte3<<4 in byte 2
         const uint32_t n0 = b0 | (b0 >> 4), n1 = b1 | (b1 >> 4);
         out[c] = special ? 0u : __builtin_amdgcn_perm(n1, n0, 0x06040200u);
@@ -164,90 +191,160 @@ __global__ __launch_bounds__(256) void encode_kernel(const uint16_t *__restrict_
     if (LPU >= 4) mbits |= dpp<DPP_XOR2>(mbits);
     if (LPU >= 8) mbits |= dpp<DPP_HALF_MIRROR>(mbits);
 
-    if (live) {
+    return special ? 0x000000FFu : (mbits | e6);
+}
+
+// Thread block b encodes units [b * UPB, (b+1) * UPB), UPB = UPT * 256 / LPU; a thread's
+// t-th unit is UPB*b + t*(256/LPU) + threadIdx/LPU, so that every load and store
+// instruction of a wave touches one contiguous range.
+template <int LPU, int MODE, bool CONTIG, int UPT, bool NT>
+__global__ __launch_bounds__(256) void encode_kernel(const uint16_t *__restrict__ x, int64_t units, int64_t upr,
+                                                     int64_t ldx, uint32_t *__restrict__ codes,
+                                                     uint32_t *__restrict__ meta)
+{
+    constexpr int NCH = 8 / LPU;
+    constexpr int UPS = 256 / LPU; // units per block per slice
+    const int l = (int)(threadIdx.x % LPU);
+    const int64_t first = (int64_t)blockIdx.x * (UPS * UPT) + threadIdx.x / LPU;
+
+    uint4 w[UPT][NCH];
+    int64_t unit[UPT];
+    bool live[UPT];
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) codes[unit * 8 + c * LPU + l] = out[c];
-        if (l == 0) meta[unit] = special ? 0x000000FFu : (mbits | e6);
+    for (int t = 0; t < UPT; ++t) {
+        const int64_t u = first + (int64_t)t * UPS;
+        live[t] = u < units;
+        unit[t] = live[t] ? u : units - 1; // dead lanes redo the last unit and store nothing
+        const uint16_t *src;
+        if (CONTIG) {
+            src = x + unit[t] * 64;
+        } else {
+            const int64_t row = unit[t] / upr;
+            src = x + row * ldx + (unit[t] - row * upr) * 64;
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) w[t][c] = load16<NT>(src + 8 * (c * LPU + l));
+    }
+#pragma unroll
+    for (int t = 0; t < UPT; ++t) {
+        uint32_t out[NCH];
+        const uint32_t m = encode_share<LPU, MODE>(w[t], l, out);
+        if (live[t]) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) store4<NT>(codes + unit[t] * 8 + c * LPU + l, out[c]);
+            if (l == 0) store4<NT>(meta + unit[t], m);
+        }
     }
 }
 
 // ------------------------------------------------------------------ decoder
 
-// One lane decodes 8 consecutive elements: a dword of codes -> 16 bytes of BF16.
-template <bool CONTIG>
+// Eq. 2 for 8 consecutive elements: group-of-8 number j of a unit with metadata m,
+// codes dword c -> 16 bytes of BF16.
+__device__ __forceinline__ uint4 decode_chunk(uint32_t c, uint32_t m, int j)
+{
+    if ((m & 0xFFu) == 0xFFu) return make_uint4(0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u);
+    // value = (4 + M) * mag * 2^(E - 48 - 4 + E1_8 + E1_16): at most 6 significant bits, exact
+    const uint32_t e8 = (m >> (8 + j)) & 1u;
+    const uint32_t e16a = (m >> (16 + 2 * j)) & 1u, e16b = (m >> (17 + 2 * j)) & 1u;
+    const uint32_t ebase = ((m >> 2) & 0x3Fu) + (127u - 52u) + e8;
+    const float sig = (float)(4u + (m & 3u));
+    const float sa = sig * u2f((ebase + e16a) << 23), sb = sig * u2f((ebase + e16b) << 23);
+    const uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u; // magnitudes of even / odd elements
+    float f[8];
+    f[0] = (float)(lo & 0xFFu) * sa;
+    f[1] = (float)(hi & 0xFFu) * sa;
+    f[2] = (float)((lo >> 8) & 0xFFu) * sa;
+    f[3] = (float)((hi >> 8) & 0xFFu) * sa;
+    f[4] = (float)((lo >> 16) & 0xFFu) * sb;
+    f[5] = (float)((hi >> 16) & 0xFFu) * sb;
+    f[6] = (float)(lo >> 24) * sb;
+    f[7] = (float)(hi >> 24) * sb;
+    uint32_t r[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        // exact values: their BF16 form is the top half of the fp32 pattern
+        const uint32_t pair = __builtin_amdgcn_perm(f2u(f[2 * t + 1]), f2u(f[2 * t]), 0x07060302u);
+        // sign of element 2t sits at bit 8t+3, of element 2t+1 at bit 8t+7
+        const uint32_t cs = c >> (8 * t);
+        const uint32_t sg = ((cs << 12) & 0x8000u) | ((cs << 24) & 0x80000000u);
+        r[t] = pair | sg;
+    }
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+// One lane decodes CPT chunks of 8 elements; block b owns chunks [b*256*CPT, (b+1)*256*CPT).
+template <bool CONTIG, int CPT, bool NT>
 __global__ __launch_bounds__(256) void decode_kernel(const uint32_t *__restrict__ codes,
                                                      const uint32_t *__restrict__ meta, int64_t chunks, int64_t upr,
                                                      int64_t ldy, uint16_t *__restrict__ y)
 {
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid >= chunks) return;
-    const int64_t unit = tid >> 3;
-    const int j = (int)(tid & 7);
-    const uint32_t c = codes[tid];
-    const uint32_t m = meta[unit];
-
-    uint16_t *dst;
-    if (CONTIG) {
-        dst = y + tid * 8;
-    } else {
-        const int64_t row = unit / upr;
-        dst = y + row * ldy + (unit - row * upr) * 64 + j * 8;
-    }
-
-    uint4 o;
-    if ((m & 0xFFu) == 0xFFu) {
-        o = make_uint4(0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u);
-    } else {
-        // value = (4 + M) * m * 2^(E - 48 - 4 + E1_8 + E1_16): at most 6 significant bits, exact
-        const uint32_t e8 = (m >> (8 + j)) & 1u;
-        const uint32_t e16a = (m >> (16 + 2 * j)) & 1u, e16b = (m >> (17 + 2 * j)) & 1u;
-        const uint32_t ebase = ((m >> 2) & 0x3Fu) + (127u - 52u) + e8;
-        const float sig = (float)(4u + (m & 3u));
-        const float sa = sig * u2f((ebase + e16a) << 23), sb = sig * u2f((ebase + e16b) << 23);
-        const uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u; // magnitudes of even / odd elements
-        float f[8];
-        f[0] = (float)(lo & 0xFFu) * sa;
-        f[1] = (float)(hi & 0xFFu) * sa;
-        f[2] = (float)((lo >> 8) & 0xFFu) * sa;
-        f[3] = (float)((hi >> 8) & 0xFFu) * sa;
-        f[4] = (float)((lo >> 16) & 0xFFu) * sb;
-        f[5] = (float)((hi >> 16) & 0xFFu) * sb;
-        f[6] = (float)(lo >> 24) * sb;
-        f[7] = (float)(hi >> 24) * sb;
-        uint32_t r[4];
+    const int64_t first = (int64_t)blockIdx.x * (256 * CPT) + threadIdx.x;
+    uint32_t c[CPT], m[CPT];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            // exact values: their BF16 form is the top half of the fp32 pattern
-            const uint32_t pair = __builtin_amdgcn_perm(f2u(f[2 * t + 1]), f2u(f[2 * t]), 0x07060302u);
-            // sign of element 2t sits at bit 8t+3, of element 2t+1 at bit 8t+7
-            const uint32_t cs = c >> (8 * t);
-            const uint32_t sg = ((cs << 12) & 0x8000u) | ((cs << 24) & 0x80000000u);
-            r[t] = pair | sg;
-        }
-        o = make_uint4(r[0], r[1], r[2], r[3]);
+    for (int t = 0; t < CPT; ++t) {
+        const int64_t id = first + t * 256;
+        const int64_t idc = id < chunks ? id : chunks - 1;
+        c[t] = NT ? __builtin_nontemporal_load(codes + idc) : codes[idc];
+        m[t] = meta[idc >> 3];
     }
-    *reinterpret_cast<uint4 *>(dst) = o;
+#pragma unroll
+    for (int t = 0; t < CPT; ++t) {
+        const int64_t id = first + t * 256;
+        if (id >= chunks) continue;
+        const int64_t unit = id >> 3;
+        const int j = (int)(id & 7);
+        uint16_t *dst;
+        if (CONTIG) {
+            dst = y + id * 8;
+        } else {
+            const int64_t row = unit / upr;
+            dst = y + row * ldy + (unit - row * upr) * 64 + j * 8;
+        }
+        store16<NT>(dst, decode_chunk(c[t], m[t], j));
+    }
 }
 
 // ------------------------------------------------------------------ launchers
+
+// Launch shapes measured on MI355X at 512 MiB of BF16: 4 lanes per unit and one unit
+// slice per thread for the encoder (the kernel is VALU-limited, fewer lanes per unit
+// amortise the per-unit scalar work); 4 chunks per thread and streaming stores for the
+// decoder (write-dominated).
+#ifndef HIF4_ENC_LPU
+#define HIF4_ENC_LPU 4
+#endif
+#ifndef HIF4_ENC_UPT
+#define HIF4_ENC_UPT 1
+#endif
+#ifndef HIF4_ENC_NT
+#define HIF4_ENC_NT false
+#endif
+#ifndef HIF4_DEC_CPT
+#define HIF4_DEC_CPT 4
+#endif
+#ifndef HIF4_DEC_NT
+#define HIF4_DEC_NT true
+#endif
 
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream)
 {
     const int64_t upr = K / 64, units = rows * upr;
     if (units == 0) return HIF4_OK;
-    constexpr int LPU = 8;
-    const int64_t threads = units * LPU;
-    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    constexpr int LPU = HIF4_ENC_LPU, UPT = HIF4_ENC_UPT;
+    constexpr bool NT = HIF4_ENC_NT;
+    constexpr int64_t UPB = (256 / LPU) * UPT; // units per block
+    const dim3 grid((unsigned)((units + UPB - 1) / UPB)), block(256);
     const uint16_t *xs = static_cast<const uint16_t *>(x);
     uint32_t *cd = reinterpret_cast<uint32_t *>(codes);
     const bool contig = ldx == K;
     if (mode == HIF4_ROUND_RNE) {
-        if (contig) hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RNE, true>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
-        else hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RNE, false>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
+        if (contig) hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RNE, true, UPT, NT>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
+        else hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RNE, false, UPT, NT>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
     } else {
-        if (contig) hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RHA, true>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
-        else hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RHA, false>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
+        if (contig) hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RHA, true, UPT, NT>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
+        else hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RHA, false, UPT, NT>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
     }
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
@@ -257,11 +354,13 @@ int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int6
 {
     const int64_t upr = K / 64, chunks = rows * upr * 8;
     if (chunks == 0) return HIF4_OK;
-    const dim3 grid((unsigned)((chunks + 255) / 256)), block(256);
+    constexpr int CPT = HIF4_DEC_CPT;
+    constexpr bool NT = HIF4_DEC_NT;
+    const dim3 grid((unsigned)((chunks + 256 * CPT - 1) / (256 * CPT))), block(256);
     const uint32_t *cd = reinterpret_cast<const uint32_t *>(codes);
     uint16_t *ys = static_cast<uint16_t *>(y);
-    if (ldy == K) hipLaunchKernelGGL((decode_kernel<true>), grid, block, 0, stream, cd, meta, chunks, upr, ldy, ys);
-    else hipLaunchKernelGGL((decode_kernel<false>), grid, block, 0, stream, cd, meta, chunks, upr, ldy, ys);
+    if (ldy == K) hipLaunchKernelGGL((decode_kernel<true, CPT, NT>), grid, block, 0, stream, cd, meta, chunks, upr, ldy, ys);
+    else hipLaunchKernelGGL((decode_kernel<false, CPT, NT>), grid, block, 0, stream, cd, meta, chunks, upr, ldy, ys);
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 
