@@ -17,9 +17,14 @@
  *
  * Packed layout (version 1; the paper's figure fixing the bit order is not part of
  * its text, so this is the library's own, documented choice) — two planes:
- *   codes : uint8  [rows][K/2]   element 2t in the low nibble of byte t, element 2t+1
- *                                in the high nibble; nibble = sign<<3 | integer bit<<2
- *                                | two fraction bits (sign-magnitude, +-0 both exist).
+ *   codes : uint8  [rows][K/2]   32 bytes per unit, 4 bytes per group of 8 elements (one
+ *                                level-2 domain).  Inside group j, byte 4j+t (t = 0..3)
+ *                                holds element 8j+t in its low nibble and element 8j+4+t
+ *                                in its high nibble: the four low nibbles are one level-3
+ *                                group, the four high nibbles the next, so that one mask
+ *                                separates the two groups of a 32-bit word.
+ *                                nibble = sign<<3 | integer bit<<2 | two fraction bits
+ *                                (sign-magnitude, +-0 both exist).
  *   meta  : uint32 [rows][K/64]  bits  7:0  E6M2 byte, exponent field (bias 48) in bits
  *                                           7:2, mantissa in bits 1:0, 0xFF = NaN;
  *                                bits 15:8  E1_8,  bit j  scales elements 8j..8j+7 by 2;

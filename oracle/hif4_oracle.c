@@ -23,9 +23,12 @@
  * to nearest, the sign of zero copying the input sign.
  *
  * Packed layout used on both sides of the boundary:
- *   codes[row][K/2] : element 2t in the low nibble of byte t, 2t+1 in the high
- *                     nibble; nibble = sign(bit3) | integer bit(bit2) | 2 fraction
- *                     bits (S1P2, sign-magnitude).
+ *   codes[row][K/2] : 32 bytes per unit, 4 bytes per group of 8 elements; inside
+ *                     group j, byte 4j+t (t = 0..3) holds element 8j+t in its low
+ *                     nibble and element 8j+4+t in its high nibble, so the low
+ *                     nibbles of the 4 bytes are one level-3 group and the high
+ *                     nibbles the next.  nibble = sign(bit3) | integer bit(bit2) |
+ *                     2 fraction bits (S1P2, sign-magnitude).
  *   meta[row][K/64] : u32, bits 7:0 E6M2 byte (eeeeee_mm), bits 15:8 E1_8 (bit j
  *                     <-> elements 8j..8j+7), bits 31:16 E1_16 (bit k <-> elements
  *                     4k..4k+3).
@@ -37,6 +40,10 @@
 #ifdef _OPENMP
 #include <omp.h>
 #endif
+
+/* Where element i (0..63) of a unit lives in its 32 code bytes. */
+static int code_byte(int i) { return 4 * (i >> 3) + (i & 3); }
+static int code_shift(int i) { return ((i >> 2) & 1) * 4; }
 
 #define HIF4O_ROUND_RNE 0 /* round half to even            (Section II-B, last paragraph) */
 #define HIF4O_ROUND_RHA 1 /* round half away from zero     (same paragraph)               */
@@ -195,7 +202,7 @@ void hif4o_encode_unit(const uint16_t x[64], uint8_t codes[32], uint32_t *meta, 
         int shift = (int)((E1_8 >> (i >> 3)) & 1u) + (int)((E1_16 >> (i >> 2)) & 1u);
         s = ldexp(s, -shift); /* a power of two: no rounding where the result can matter */
         uint8_t c = hif4o_to_s1p2(s, (x[i] & 0x8000u) != 0, mode);
-        codes[i >> 1] |= (uint8_t)(c << ((i & 1) * 4));
+        codes[code_byte(i)] |= (uint8_t)(c << code_shift(i));
     }
     *meta = (E1_16 << 16) | (E1_8 << 8) | E6M2;
 }
@@ -209,7 +216,7 @@ double hif4o_decode_elem_f64(const uint8_t codes[32], uint32_t meta, int i)
     if (e6m2 == 0xFF) return NAN;
     int e8 = (int)((meta >> (8 + (i >> 3))) & 1u);
     int e16 = (int)((meta >> (16 + (i >> 2))) & 1u);
-    uint8_t c = (uint8_t)((codes[i >> 1] >> ((i & 1) * 4)) & 0xFu);
+    uint8_t c = (uint8_t)((codes[code_byte(i)] >> code_shift(i)) & 0xFu);
     double s1p2 = 0.25 * (double)(c & 7u);
     if (c & 8u) s1p2 = -s1p2; /* keeps -0.0 */
     return hif4o_e6m2_to_f64(e6m2) * ldexp(1.0, e8 + e16) * s1p2;
@@ -293,7 +300,7 @@ double hif4o_unit_dot(const uint8_t ca[32], uint32_t ma, const uint8_t cb[32], u
         for (int j = 2 * i; j < 2 * i + 2; ++j) {
             int64_t inner = 0;
             for (int k = 4 * j; k < 4 * j + 4; ++k) {
-                int a = (ca[k >> 1] >> ((k & 1) * 4)) & 0xF, b = (cb[k >> 1] >> ((k & 1) * 4)) & 0xF;
+                int a = (ca[code_byte(k)] >> code_shift(k)) & 0xF, b = (cb[code_byte(k)] >> code_shift(k)) & 0xF;
                 int sa = (a & 8) ? -(a & 7) : (a & 7), sb = (b & 8) ? -(b & 7) : (b & 7);
                 inner += sa * sb; /* in units of 1/16 */
             }

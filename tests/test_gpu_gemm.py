@@ -1,0 +1,185 @@
+"""GPU parity of hif4_gemm / hif4_grouped_gemm (through the C ABI) against the fp64 oracle
+on the same decoded operands: relative Frobenius error <= 1e-4 with fp32 output; BF16
+output within one BF16 ulp of the rounded oracle value."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_11287_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4  # relative Frobenius error against the fp64 oracle, fp32 output
+
+
+@pytest.fixture(scope="module")
+def h():
+    from paper_2602_11287_amd import hif4
+    hif4.load()
+    assert torch.cuda.is_available()
+    return hif4
+
+
+def dev_packed(codes, meta):
+    return torch.from_numpy(codes).cuda(), torch.from_numpy(meta.view(np.int32)).cuda()
+
+
+def rel_fro(got, want):
+    return float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300))
+
+
+def quantized_operands(oracle, M, N, K, seed, a_outliers=True):
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal((M, K))
+    if a_outliers:
+        a[rng.random((M, K)) < 0.002] *= 64
+    w = rng.standard_normal((N, K)) * 0.02 * np.exp(rng.uniform(np.log(0.5), np.log(2.0), (N, 1)))
+    ab = synth.bits(torch.from_numpy(a).to(torch.bfloat16))
+    wb = synth.bits(torch.from_numpy(w).to(torch.bfloat16))
+    ac, am = oracle.quantize(ab)
+    wc, wm = oracle.quantize(wb)
+    return ab, (ac, am), (wc, wm)
+
+
+SHAPES = [(1, 1, 64), (32, 32, 64), (256, 256, 64), (257, 255, 128), (333, 520, 1024), (5, 1000, 192), (600, 70, 320)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_w4a4_prepacked(h, oracle, M, N, K):
+    print(f"gemm parity M={M} N={N} K={K}", flush=True)
+    _, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 31 + M + N + K)
+    want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc, wm))
+    acd, amd = dev_packed(ac, am)
+    wcd, wmd = dev_packed(wc, wm)
+    c32 = h.hif4_gemm(h.HIF4_A_HIF4, acd, amd, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    c16 = h.hif4_gemm(h.HIF4_A_HIF4, acd, amd, wcd, wmd, out_dtype=h.HIF4_OUT_BF16)
+    c32b = h.hif4_gemm(h.HIF4_A_HIF4, acd, amd, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    got = c32.cpu().numpy().astype(np.float64)
+    assert rel_fro(got, want) <= TOL, rel_fro(got, want)
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max() + 1e-30
+    assert torch.equal(c32, c32b), "same launch twice gives the same bits"
+    # BF16 output: within one ulp of the oracle value rounded to BF16
+    wb = synth.bits(torch.from_numpy(want).to(torch.bfloat16)).astype(np.int32)
+    gb = synth.bits(c16.cpu()).astype(np.int32)
+    key = lambda b: np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    assert np.abs(key(gb) - key(wb)).max() <= 1
+
+
+def test_gemm_quantize_inside_call(h, oracle):
+    M, N, K = 300, 200, 512
+    ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 77)
+    want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc, wm))
+    wcd, wmd = dev_packed(wc, wm)
+    a = synth.from_bits(ab).cuda()
+    c = h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    # strided A and C
+    abuf = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    abuf[:, :K] = a
+    cbuf = torch.full((M, N + 9), -1.0, dtype=torch.float32, device="cuda")
+    h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, abuf[:, :K], None, wcd, wmd, out_dtype=h.HIF4_OUT_F32, c=cbuf[:, :N])
+    torch.cuda.synchronize()
+    assert rel_fro(c.cpu().numpy().astype(np.float64), want) <= TOL
+    assert torch.equal(cbuf[:, :N], c) and (cbuf[:, N:] == -1.0).all()
+
+
+def test_gemm_random_packed_wide_range_and_nan(h, oracle):
+    """Packed planes drawn directly: every metadata pattern, scales far apart, one NaN unit each side."""
+    rng = np.random.default_rng(5)
+    M, N, K = 70, 90, 256
+    ac = rng.integers(0, 256, (M, K // 2), dtype=np.uint8)
+    wc = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    am = (rng.integers(0, 2 ** 24, (M, K // 64)).astype(np.uint32) << 8) | rng.integers(100, 220, (M, K // 64)).astype(np.uint32)
+    wm = (rng.integers(0, 2 ** 24, (N, K // 64)).astype(np.uint32) << 8) | rng.integers(100, 220, (N, K // 64)).astype(np.uint32)
+    am[3, 1] |= 0xFF
+    wm[7, 2] |= 0xFF
+    want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc, wm))
+    c = h.hif4_gemm(h.HIF4_A_HIF4, *dev_packed(ac, am), *dev_packed(wc, wm), out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    got = c.cpu().numpy().astype(np.float64)
+    nan_want = np.isnan(want)
+    assert nan_want[3].all() and nan_want[:, 7].all() and nan_want.sum() == N + M - 1
+    assert (np.isnan(got) == nan_want).all()
+    ok = ~nan_want
+    assert np.linalg.norm(got[ok] - want[ok]) <= TOL * np.linalg.norm(want[ok])
+    # each row against its own norm as well: rows differ by many binades
+    for r in range(M):
+        if r != 3:
+            k = ok[r]
+            assert np.linalg.norm(got[r][k] - want[r][k]) <= TOL * np.linalg.norm(want[r][k])
+
+
+def test_gemm_extreme_scales(h, oracle):
+    """Largest and smallest finite units: no overflow to inf, no flush to zero."""
+    K = 64
+    codes = np.full((2, 32), 0x77, np.uint8)
+    hi = np.array([[0xFFFFFFFE]], np.uint32)
+    lo = np.array([[0x00000000]], np.uint32)
+    am = np.concatenate([hi, lo])
+    wm = np.concatenate([hi, lo])
+    want = oracle.gemm_f64(oracle.dequantize(codes, am), oracle.dequantize(codes, wm))
+    c = h.hif4_gemm(h.HIF4_A_HIF4, *dev_packed(codes, am), *dev_packed(codes, wm), out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    got = c.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all() and (got != 0).all()
+    assert np.abs(got / want - 1).max() < 1e-6
+
+
+def test_gemm_empty_and_k0(h):
+    wc = torch.zeros((8, 0), dtype=torch.uint8, device="cuda")
+    wm = torch.zeros((8, 0), dtype=torch.int32, device="cuda")
+    ac = torch.zeros((4, 0), dtype=torch.uint8, device="cuda")
+    am = torch.zeros((4, 0), dtype=torch.int32, device="cuda")
+    c = torch.full((4, 8), 3.0, dtype=torch.float32, device="cuda")
+    h.hif4_gemm(h.HIF4_A_HIF4, ac, am, wc, wm, out_dtype=h.HIF4_OUT_F32, c=c)
+    torch.cuda.synchronize()
+    assert (c == 0).all()
+    c0 = h.hif4_gemm(h.HIF4_A_HIF4, torch.zeros((0, 32), dtype=torch.uint8, device="cuda"),
+                     torch.zeros((0, 1), dtype=torch.int32, device="cuda"),
+                     torch.zeros((8, 32), dtype=torch.uint8, device="cuda"),
+                     torch.zeros((8, 1), dtype=torch.int32, device="cuda"))
+    assert c0.shape == (0, 8)
+
+
+@pytest.mark.parametrize("counts", [[0, 130, 1, 300, 77, 0], [5], [128, 128, 128], [0, 0, 257]])
+def test_grouped_gemm(h, oracle, counts):
+    E, N, K = len(counts), 300, 256
+    M = int(sum(counts))
+    offs = np.zeros(E + 1, np.int32)
+    offs[1:] = np.cumsum(counts)
+    rng = np.random.default_rng(E + M)
+    ab, (ac, am), _ = quantized_operands(oracle, M, 1, K, 900 + M)
+    w = rng.standard_normal((E * N, K)) * 0.02
+    wc, wm = oracle.quantize(synth.bits(torch.from_numpy(w).to(torch.bfloat16)))
+    adec, wdec = oracle.dequantize(ac, am), oracle.dequantize(wc, wm)
+    want = np.zeros((M, N))
+    for e in range(E):
+        if counts[e]:
+            want[offs[e]:offs[e + 1]] = oracle.gemm_f64(adec[offs[e]:offs[e + 1]], wdec[e * N:(e + 1) * N])
+    wcd, wmd = dev_packed(wc.reshape(E, N, K // 2), wm.reshape(E, N, K // 64))
+    od = torch.from_numpy(offs).cuda()
+    c = torch.full((M, N), 9.0, dtype=torch.float32, device="cuda")
+    h.hif4_grouped_gemm(h.HIF4_A_HIF4, *dev_packed(ac, am), wcd, wmd, od, out_dtype=h.HIF4_OUT_F32, c=c)
+    cq = h.hif4_grouped_gemm(h.HIF4_A_BF16_QUANTIZE, synth.from_bits(ab).cuda(), None, wcd, wmd, od, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    got = c.cpu().numpy().astype(np.float64)
+    assert rel_fro(got, want) <= TOL
+    assert torch.equal(c, cq)
+
+
+def test_gemm_prefill_shape_sampled(h, oracle):
+    """M=4096, N=11008, K=4096 (the W4A4 prefill configuration): a seeded sample of rows x columns."""
+    M, N, K = 4096, 11008, 4096
+    a = synth.activation_channel_outliers(M, K)
+    w = synth.weight_gaussian(N, K, 0.02, config=3)
+    wc, wm = oracle.quantize(synth.bits(w))
+    wcd, wmd = dev_packed(wc, wm)
+    c = h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, a.cuda(), None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    rows = np.sort(np.concatenate([rng.choice(M, 94, replace=False), [0, M - 1]]))
+    cols = np.sort(np.concatenate([rng.choice(N, 94, replace=False), [0, N - 1]]))
+    ac, am = oracle.quantize(synth.bits(a)[rows])
+    want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc[cols], wm[cols]))
+    got = c[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
+    assert rel_fro(got, want) <= TOL, rel_fro(got, want)

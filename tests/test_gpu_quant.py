@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 import torch
 
+from layout import nibbles_to_codes
 from paper_2602_11287_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -109,7 +110,7 @@ def test_decode_exhaustive(h, oracle):
     codes = np.zeros((rows, 16 * 32), np.uint8)
     for s in range(16):                                                       # rotate nibbles through positions
         nib = (np.arange(64) + s) % 16
-        codes[:, 32 * s:32 * s + 32] = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8)
+        codes[:, 32 * s:32 * s + 32] = nibbles_to_codes(nib)
     y = h.hif4_dequantize(torch.from_numpy(codes).cuda(), torch.from_numpy(meta.view(np.int32)).cuda())
     torch.cuda.synchronize()
     got = synth.bits(y.cpu())

@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 import torch
 
+from layout import codes_to_nibbles, nibbles_to_codes
 from paper_2602_11287_amd import synth
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
@@ -17,11 +18,7 @@ GOLD = os.path.join(os.path.dirname(__file__), "golden")
 # ------------------------------------------------------------------ helpers
 
 def nibbles(codes):
-    c = np.asarray(codes, dtype=np.uint8)
-    out = np.empty(c.shape[:-1] + (c.shape[-1] * 2,), np.uint8)
-    out[..., 0::2] = c & 0xF
-    out[..., 1::2] = c >> 4
-    return out
+    return codes_to_nibbles(codes)
 
 
 def bf(values):
@@ -228,7 +225,7 @@ def canonical_units(rng, n):
         nib[8 * j] |= 7
         byte = int(rng.integers(0, 255))
         meta = byte | (sum(int(b) << t for t, b in enumerate(e8)) << 8) | (sum(int(b) << t for t, b in enumerate(e16)) << 16)
-        out.append(((nib[0::2] | (nib[1::2] << 4)).astype(np.uint8), meta))
+        out.append((nibbles_to_codes(nib), meta))
     return out
 
 

@@ -7,6 +7,8 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
+from layout import nibbles_to_codes
+
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
@@ -25,7 +27,7 @@ P = paper_values()
 def unit(codes_nibbles, e6m2, e8=0, e16=0):
     """Build (codes[32], meta) from 64 nibbles using the documented layout."""
     n = np.asarray(codes_nibbles, dtype=np.uint8)
-    codes = (n[0::2] | (n[1::2] << 4)).astype(np.uint8)
+    codes = nibbles_to_codes(n)
     return codes, (e16 << 16) | (e8 << 8) | e6m2
 
 
@@ -117,11 +119,11 @@ def test_position_mapping_of_micro_exponents(oracle):
         want = np.ones(64)
         want[4 * k:4 * k + 4] = 2.0
         assert (f == want).all()
-    # nibble order: element 2t low nibble, 2t+1 high nibble
+    # nibble order: byte 4j+t = element 8j+t (low nibble) and element 8j+4+t (high nibble)
     codes = np.zeros(32, np.uint8)
     codes[5] = 0x73
     f = oracle.bf16_bits_to_f64(oracle.decode_unit(codes, 48 << 2))
-    assert f[10] == 0.75 and f[11] == 1.75 and f.sum() == 2.5
+    assert f[8 + 1] == 0.75 and f[8 + 4 + 1] == 1.75 and f.sum() == 2.5
 
 
 def test_bulk_decode_matches_elementwise(oracle):

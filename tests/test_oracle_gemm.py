@@ -3,6 +3,7 @@ fp64 dot of the decoded values; the matrix product reduces to numpy's matmul and
 units with unit scale and clear micro-exponents, to an exact integer product."""
 import numpy as np
 
+from layout import codes_to_nibbles
 from paper_2602_11287_amd import synth
 
 
@@ -58,8 +59,7 @@ def test_gemm_integer_special_case(oracle):
     got = oracle.gemm_f64(oracle.dequantize(ca, one[0]), oracle.dequantize(cw, one[1]))
 
     def quarters(c):
-        n = np.empty((c.shape[0], c.shape[1] * 2), np.int64)
-        n[:, 0::2], n[:, 1::2] = c & 0xF, c >> 4
+        n = codes_to_nibbles(c).astype(np.int64)
         return np.where(n & 8, -(n & 7), n & 7)
 
     want = quarters(ca) @ quarters(cw).T
