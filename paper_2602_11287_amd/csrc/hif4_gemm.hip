@@ -125,6 +125,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     constexpr int UPT = (BM + BN + NT - 1) / NT; // units per thread per K step
     const uint32_t *src_codes[UPT];
     const uint32_t *src_meta[UPT];
+    const uint16_t *src_bf16[UPT];
     int cell0[UPT];
     bool active[UPT];
 #pragma unroll
@@ -136,12 +137,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
             r = r < rows_end ? r : rows_end - 1; // rows past the edge repeat the last one; never stored
             src_codes[i] = g.a_codes + (int64_t)r * (g.K / 8);
             src_meta[i] = g.a_meta + (int64_t)r * upr;
+            src_bf16[i] = reinterpret_cast<const uint16_t *>(g.a_codes) + (int64_t)r * g.lda;
             cell0[i] = u;
         } else {
             int r = col0 + (u - BM);
             r = r < g.N ? r : g.N - 1;
             src_codes[i] = w_codes + (int64_t)r * (g.K / 8);
             src_meta[i] = w_meta + (int64_t)r * upr;
+            src_bf16[i] = nullptr;
             cell0[i] = 8 * BM + (u - BM);
         }
     }
@@ -155,23 +158,34 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    uint4 pc[UPT][2]; // packed codes of the next step
+    uint4 pc[UPT][A_BF16 ? 8 : 2]; // next step: packed codes of a unit, or 64 BF16 of a plain A row
     uint32_t pm[UPT];
 
     auto fetch = [&](int ks) {
 #pragma unroll
         for (int i = 0; i < UPT; ++i) {
             if (!active[i]) continue;
-            const uint4 *p = reinterpret_cast<const uint4 *>(src_codes[i] + ks * 8);
-            pc[i][0] = p[0];
-            pc[i][1] = p[1];
-            pm[i] = src_meta[i][ks];
+            if (A_BF16 && (tid + i * NT) < BM) {
+                const uint4 *p = reinterpret_cast<const uint4 *>(src_bf16[i] + (int64_t)ks * 64);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) pc[i][j] = p[j];
+            } else {
+                const uint4 *p = reinterpret_cast<const uint4 *>(src_codes[i] + ks * 8);
+                pc[i][0] = p[0];
+                pc[i][1] = p[1];
+                pm[i] = src_meta[i][ks];
+            }
         }
     };
     auto expand_to = [&](uint4 *buf) {
 #pragma unroll
         for (int i = 0; i < UPT; ++i) {
             if (!active[i]) continue;
+            if (A_BF16 && (tid + i * NT) < BM) { // plain BF16 activations: cells are straight copies
+#pragma unroll
+                for (int j = 0; j < 8; ++j) buf[cell0[i] + j * BM] = pc[i][j];
+                continue;
+            }
             const uint32_t sbase = unit_scale_bits(pm[i]);
             const uint32_t cw[8] = { pc[i][0].x, pc[i][0].y, pc[i][0].z, pc[i][0].w,
                                      pc[i][1].x, pc[i][1].y, pc[i][1].z, pc[i][1].w };
@@ -236,6 +250,90 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     }
 }
 
+// ------------------------------------------------------------------ skinny weight-only GEMM
+
+// C[M][N] = A[M][K] (BF16) * W[N][K]^T (HiF4) for M <= 16 * MB: bound by streaming W once
+// from HBM.  A workgroup owns 16 output columns; its 8 waves split K by pairs of units and
+// add their partial tiles through LDS.  v_mfma_f32_16x16x32_bf16: lane (n, q) = (lane % 16,
+// lane / 16) supplies 8 consecutive k of weight row n (one dword of codes, expanded in
+// registers, never through LDS) and of activation row n; for the pair of units (2p, 2p+1)
+// lane q loads the 16 code bytes [16 q, 16 q + 16) of the 64-byte pair, so a weight row's
+// bytes are read as one contiguous run.
+template <int MB, bool OUT_F32>
+__global__ __launch_bounds__(512) void gemm_skinny_kernel(const uint16_t *__restrict__ a, int64_t lda,
+                                                          const uint32_t *__restrict__ w_codes,
+                                                          const uint32_t *__restrict__ w_meta, void *c, int64_t ldc,
+                                                          int M, int N, int K)
+{
+    constexpr int KS = 8;
+    __shared__ float red[KS][MB][256];
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int n_l = lane % 16, q = lane / 16;
+    const int col = blockIdx.x * 16 + n_l;
+    const int colc = col < N ? col : N - 1;
+    const int upr = K / 64, npairs = (upr + 1) / 2;
+    const uint32_t *wrow = w_codes + (int64_t)colc * (K / 8);
+    const uint32_t *mrow = w_meta + (int64_t)colc * upr;
+
+    f32x4_t acc[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
+
+    for (int p = wave; p < npairs; p += KS) {
+        const int u = 2 * p + (q >> 1);
+        const bool valid = u < upr;
+        const int uc = valid ? u : upr - 1;
+        uint4 cw = *reinterpret_cast<const uint4 *>(wrow + uc * 8 + (q & 1) * 4);
+        uint32_t meta = mrow[uc];
+        if (!valid) { cw = make_uint4(0, 0, 0, 0); meta = 0; } // an odd unit count: the missing half adds zeros
+        const uint32_t sbase = unit_scale_bits(meta);
+        const uint32_t cwa[4] = { cw.x, cw.y, cw.z, cw.w };
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int j = 4 * (q & 1) + t;
+            const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, expand_chunk(cwa[t], meta, sbase, j));
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const int row = mb * 16 + n_l;
+                uint4 av = make_uint4(0, 0, 0, 0);
+                if (valid && row < M) av = *reinterpret_cast<const uint4 *>(a + (int64_t)row * lda + (int64_t)uc * 64 + j * 8);
+                acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), bfrag, acc[mb], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave][mb][r * 64 + lane] = acc[mb][r];
+    __syncthreads();
+    // thread -> (mb, r, lane): output row mb*16 + 4*(lane/16) + r, column lane%16
+    for (int idx = tid; idx < MB * 256; idx += 512) {
+        const int mb = idx / 256, rem = idx % 256, r = rem / 64, ln = rem % 64;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < KS; ++w) v += red[w][mb][rem];
+        const int row = mb * 16 + 4 * (ln / 16) + r, cc = blockIdx.x * 16 + (ln % 16);
+        if (row < M && cc < N) {
+            if (OUT_F32) static_cast<float *>(c)[(int64_t)row * ldc + cc] = v;
+            else static_cast<uint16_t *>(c)[(int64_t)row * ldc + cc] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
+        }
+    }
+}
+
+template <int MB>
+static int launch_skinny(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N,
+                         int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((N + 15) / 16)), block(512);
+    const uint16_t *ap = static_cast<const uint16_t *>(a);
+    const uint32_t *wc = reinterpret_cast<const uint32_t *>(w_codes);
+    if (out_dtype == HIF4_OUT_F32)
+        hipLaunchKernelGGL((gemm_skinny_kernel<MB, true>), grid, block, 0, stream, ap, lda, wc, w_meta, c, ldc, (int)M, (int)N, (int)K);
+    else
+        hipLaunchKernelGGL((gemm_skinny_kernel<MB, false>), grid, block, 0, stream, ap, lda, wc, w_meta, c, ldc, (int)M, (int)N, (int)K);
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
 __global__ void zero_kernel(void *c, int64_t M, int64_t N, int64_t ldc, int elem_bytes)
 {
     const int64_t col = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -251,19 +349,19 @@ __global__ void zero_kernel(void *c, int64_t M, int64_t N, int64_t ldc, int elem
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream);
 
-template <int BM, int BN, int WM, int WN, bool GROUPED>
+template <int BM, int BN, int WM, int WN, bool A_BF16, bool GROUPED>
 static int launch_tiles(const GemmArgs &g, int out_dtype, int m_tiles, hipStream_t stream)
 {
     constexpr size_t lds_bytes = 2 * 8 * (BM + BN) * sizeof(uint4);
     const dim3 grid((unsigned)((int64_t)m_tiles * g.tiles_n)), block(64 * WM * WN);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_kernel<BM, BN, WM, WN, false, true, GROUPED>;
+        auto k = gemm_kernel<BM, BN, WM, WN, A_BF16, true, GROUPED>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     } else {
-        auto k = gemm_kernel<BM, BN, WM, WN, false, false, GROUPED>;
+        auto k = gemm_kernel<BM, BN, WM, WN, A_BF16, false, GROUPED>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
@@ -275,14 +373,21 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
                 int64_t ldc, int out_dtype, void *workspace, hipStream_t stream)
 {
-    if (a_kind == HIF4_A_BF16_KEEP) return HIF4_ERR_UNSUPPORTED; // weight-only path: separate kernel, not built yet
     if (K == 0) { // empty sum: C = 0 (a fill kernel, so that the call can be captured in a graph)
         const dim3 grid((unsigned)((N + 255) / 256), (unsigned)(M < 65535 ? M : 65535)), block(256);
         hipLaunchKernelGGL(zero_kernel, grid, block, 0, stream, c, M, N, ldc, out_dtype == HIF4_OUT_F32 ? 4 : 2);
         return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
     }
+    if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64) { // decode-shaped: stream the weights once
+        if (M <= 16) return launch_skinny<1>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+        if (M <= 32) return launch_skinny<2>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+        return launch_skinny<4>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+    }
     GemmArgs g;
-    if (a_kind == HIF4_A_BF16_QUANTIZE) {
+    if (a_kind == HIF4_A_BF16_KEEP) {
+        g.a_codes = static_cast<const uint32_t *>(a); // BF16 rows, staged as they are
+        g.a_meta = nullptr;
+    } else if (a_kind == HIF4_A_BF16_QUANTIZE) {
         // quantise A into the workspace: codes plane, then the meta plane at the next 16-byte boundary
         uint8_t *codes = static_cast<uint8_t *>(workspace);
         const size_t cbytes = ((size_t)M * (size_t)K / 2 + 15) & ~(size_t)15;
@@ -308,12 +413,14 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         constexpr int BM = 128, BN = 256;
         g.tiles_n = (int)((N + BN - 1) / BN);
         const int m_tiles = (int)(M / BM) + E; // upper bound of sum_e ceil(rows_e / BM)
-        return launch_tiles<BM, BN, 2, 4, true>(g, out_dtype, m_tiles, stream);
+        if (a_kind == HIF4_A_BF16_KEEP) return launch_tiles<BM, BN, 2, 4, true, true>(g, out_dtype, m_tiles, stream);
+        return launch_tiles<BM, BN, 2, 4, false, true>(g, out_dtype, m_tiles, stream);
     }
     constexpr int BM = 256, BN = 256;
     g.tiles_n = (int)((N + BN - 1) / BN);
     const int m_tiles = (int)((M + BM - 1) / BM);
-    return launch_tiles<BM, BN, 2, 4, false>(g, out_dtype, m_tiles, stream);
+    if (a_kind == HIF4_A_BF16_KEEP) return launch_tiles<BM, BN, 2, 4, true, false>(g, out_dtype, m_tiles, stream);
+    return launch_tiles<BM, BN, 2, 4, false, false>(g, out_dtype, m_tiles, stream);
 }
 
 } // namespace hif4

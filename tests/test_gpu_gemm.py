@@ -183,3 +183,86 @@ def test_gemm_prefill_shape_sampled(h, oracle):
     want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc[cols], wm[cols]))
     got = c[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
     assert rel_fro(got, want) <= TOL, rel_fro(got, want)
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 256, 512), (1, 16, 64), (5, 100, 192), (16, 1000, 1088), (17, 48, 256),
+                                   (33, 130, 320), (64, 64, 128), (65, 300, 256), (300, 520, 448)])
+def test_gemm_weight_only(h, oracle, M, N, K):
+    """HiF4 weights, BF16 activations used as they are."""
+    print(f"weight-only parity M={M} N={N} K={K}", flush=True)
+    ab, _, (wc, wm) = quantized_operands(oracle, M, N, K, 500 + M + N + K)
+    want = oracle.gemm_f64(ab, oracle.dequantize(wc, wm))
+    a = synth.from_bits(ab).cuda()
+    wcd, wmd = dev_packed(wc, wm)
+    c32 = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    c16 = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_BF16)
+    torch.cuda.synchronize()
+    got = c32.cpu().numpy().astype(np.float64)
+    assert rel_fro(got, want) <= TOL, rel_fro(got, want)
+    wb = synth.bits(torch.from_numpy(want).to(torch.bfloat16)).astype(np.int32)
+    gb = synth.bits(c16.cpu()).astype(np.int32)
+    key = lambda b: np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    assert np.abs(key(gb) - key(wb)).max() <= 1
+
+
+def test_gemm_weight_only_decode_config(h, oracle):
+    """M=16, N=4096, K=4096: per-channel scaled weights, full output against the oracle."""
+    M, N, K = 16, 4096, 4096
+    w = synth.weight_gaussian(N, K, 0.02, config=2, channel_scale=True)
+    a = synth.activation_gaussian(M, K, config=2)
+    wc, wm = oracle.quantize(synth.bits(w))
+    want = oracle.gemm_f64(synth.bits(a), oracle.dequantize(wc, wm))
+    c = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a.cuda(), None, *dev_packed(wc, wm), out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    assert rel_fro(c.cpu().numpy().astype(np.float64), want) <= TOL
+
+
+def test_grouped_gemm_weight_only(h, oracle):
+    counts = [40, 0, 200, 3]
+    E, N, K = len(counts), 270, 192
+    M = sum(counts)
+    offs = np.zeros(E + 1, np.int32)
+    offs[1:] = np.cumsum(counts)
+    rng = np.random.default_rng(8)
+    ab = synth.bits(torch.from_numpy(rng.standard_normal((M, K))).to(torch.bfloat16))
+    wc, wm = oracle.quantize(synth.bits(torch.from_numpy(rng.standard_normal((E * N, K)) * 0.02).to(torch.bfloat16)))
+    wdec = oracle.dequantize(wc, wm)
+    want = np.concatenate([oracle.gemm_f64(ab[offs[e]:offs[e + 1]], wdec[e * N:(e + 1) * N]) for e in range(E)])
+    wcd, wmd = dev_packed(wc.reshape(E, N, K // 2), wm.reshape(E, N, K // 64))
+    c = h.hif4_grouped_gemm(h.HIF4_A_BF16_KEEP, synth.from_bits(ab).cuda(), None, wcd, wmd,
+                            torch.from_numpy(offs).cuda(), out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    assert rel_fro(c.cpu().numpy().astype(np.float64), want) <= TOL
+
+
+def test_grouped_gemm_moe_config_sampled(h, oracle):
+    """64 experts, K=7168, N=2048, 8192 routed rows: two rows of every non-empty expert against the oracle."""
+    E, K, N = 64, 7168, 2048
+    offs = synth.moe_offsets()
+    M = int(offs[-1])
+    assert M == 8192
+    a = synth.activation_gaussian(M, K, config=4)
+    g = torch.Generator(device="cuda").manual_seed(44)
+    w = (torch.randn((E * N, K), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    wcd, wmd = h.hif4_quantize(w)   # encoder output is checked against the oracle on the sampled rows below
+    c = h.hif4_grouped_gemm(h.HIF4_A_BF16_QUANTIZE, a.cuda(), None, wcd.view(E, N, K // 2), wmd.view(E, N, K // 64),
+                            torch.from_numpy(offs).cuda(), out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(6)
+    cols = np.sort(rng.choice(N, 48, replace=False))
+    errs, refs = 0.0, 0.0
+    for e in range(E):
+        lo, hi = int(offs[e]), int(offs[e + 1])
+        if hi == lo:
+            continue
+        rows = np.unique([lo, hi - 1])
+        ac, am = oracle.quantize(synth.bits(a)[rows])
+        wrows = torch.from_numpy(e * N + cols).cuda()
+        wb = synth.bits(w[wrows].cpu())
+        wc, wm = oracle.quantize(wb)
+        assert (wcd[wrows].cpu().numpy() == wc).all() and (wmd[wrows].cpu().numpy().view(np.uint32) == wm).all()
+        want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc, wm))
+        got = c[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
+        errs += np.sum((got - want) ** 2)
+        refs += np.sum(want ** 2)
+    assert np.sqrt(errs / refs) <= TOL
