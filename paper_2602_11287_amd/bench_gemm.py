@@ -1,0 +1,128 @@
+"""GEMM legs of bench.py: the HiF4 GEMM configurations on seeded synthetic tensors with the
+shapes of LLM linear layers.  Big operands are drawn on the device (same distributions as
+the CPU generators in synth.py) to keep the benchmark short; parity on these shapes is
+covered by tests/test_gpu_gemm.py."""
+import numpy as np
+import torch
+
+
+def _timed(fn, n):
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(n):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / n
+
+
+def _randn_bf16(shape, sigma, gen, dev, chunk_rows=8192):
+    out = torch.empty(shape, dtype=torch.bfloat16, device=dev)
+    for r in range(0, shape[0], chunk_rows):
+        n = min(chunk_rows, shape[0] - r)
+        out[r:r + n] = (torch.randn((n, shape[1]), generator=gen, device=dev) * sigma).to(torch.bfloat16)
+    return out
+
+
+def _quantize_rows(hif4, w, chunk_rows=16384):
+    codes = torch.empty((w.shape[0], w.shape[1] // 2), dtype=torch.uint8, device=w.device)
+    meta = torch.empty((w.shape[0], w.shape[1] // 64), dtype=torch.int32, device=w.device)
+    for r in range(0, w.shape[0], chunk_rows):
+        hif4.hif4_quantize(w[r:r + chunk_rows], codes[r:r + chunk_rows], meta[r:r + chunk_rows])
+    return codes, meta
+
+
+def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=True):
+    legs = {}
+    gen = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 99)
+    steps = max(2, min(steps, 10))
+
+    # ---- weight-only decode shape: M=16, N=4096, K=4096 (HBM-bound weight streaming)
+    M, N, K = 16, 4096, 4096
+    w = synth.weight_gaussian(N, K, 0.02, config=2, channel_scale=True).to(dev)
+    a = synth.activation_gaussian(M, K, config=2).to(dev)
+    wc, wm = hif4.hif4_quantize(w)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    f = lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_KEEP, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c)
+    for _ in range(warmup):
+        f()
+    ms = _timed(f, steps * 10)
+    nbytes = N * K // 64 * 36 + M * K * 2 + M * N * 2
+    legs["gemm_weight_only_M16_N4096_K4096"] = {
+        "us": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1), "GFLOP": round(2 * M * N * K / 1e9, 3),
+        "roofline": {"bound": "hbm", "kernel": "hif4::gemm_skinny_kernel", "achieved": round(nbytes / ms / 1e6, 1),
+                     "peak": hbm_peak_gbps, "unit": "GB/s", "frac": round(nbytes / ms / 1e6 / hbm_peak_gbps, 4),
+                     "traffic": None}}
+    del w, wc, wm
+
+    def mfma_leg(name, M, N, K, fn, kernel):
+        for _ in range(max(1, min(warmup, 2))):
+            fn()
+        ms = _timed(fn, steps)
+        tf = 2.0 * M * N * K / ms / 1e9
+        legs[name] = {"ms": round(ms, 4), "TFLOPs": round(tf, 1),
+                      "roofline": {"bound": "mfma", "kernel": kernel, "achieved": round(tf, 1), "peak": mfma_peak_tflops,
+                                   "unit": "TFLOP/s", "frac": round(tf / mfma_peak_tflops, 4), "traffic": None}}
+
+    # ---- W4A4 prefill: M=4096, N=11008, K=4096, activations quantised inside the call
+    M, N, K = 4096, 11008, 4096
+    a = synth.activation_channel_outliers(M, K).to(dev)
+    w = _randn_bf16((N, K), 0.02, gen, dev)
+    wc, wm = _quantize_rows(hif4, w)
+    del w
+    ac, am = hif4.hif4_quantize(a)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
+    mfma_leg("gemm_w4a4_quantize_inside_M4096_N11008_K4096", M, N, K,
+             lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
+             "hif4::gemm_kernel<256,256>")
+    mfma_leg("gemm_w4a4_prepacked_M4096_N11008_K4096", M, N, K,
+             lambda: hif4.hif4_gemm(hif4.HIF4_A_HIF4, ac, am, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c),
+             "hif4::gemm_kernel<256,256>")
+    del a, ac, am, wc, wm, c, ws
+
+    # ---- grouped W4A4, MoE-shaped: 64 experts, K=7168, N=2048, 8192 routed rows
+    E, K, N = 64, 7168, 2048
+    offs = synth.moe_offsets()
+    M = int(offs[-1])
+    a = synth.activation_gaussian(M, K, config=4).to(dev)
+    w = _randn_bf16((E * N, K), 0.02, gen, dev)
+    wc, wm = _quantize_rows(hif4, w)
+    del w
+    wc, wm = wc.view(E, N, K // 2), wm.view(E, N, K // 64)
+    od = torch.from_numpy(offs).to(dev)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
+    mfma_leg("grouped_gemm_w4a4_E64_rows8192_N2048_K7168", M, N, K,
+             lambda: hif4.hif4_grouped_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, od, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
+             "hif4::gemm_kernel<128,256,grouped>")
+    nbytes = E * N * K // 64 * 36 + M * K * 2 + M * N * 2
+    legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["GBps_algorithmic"] = round(
+        nbytes / legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["ms"] / 1e6, 1)
+    del a, wc, wm, c, ws
+
+    # ---- large prefill: M=16384, N=28672, K=8192, heavy-tailed activations
+    if large:
+        M, N, K = 16384, 28672, 8192
+        a = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        for r in range(0, M, 4096):   # Student-t(4) scaled to unit variance = z / sqrt(chi2_4 / 4) / sqrt(2)
+            z = torch.randn((4096, K), generator=gen, device=dev)
+            chi = torch.randn((4, 4096, K), generator=gen, device=dev).pow(2).sum(0)
+            a[r:r + 4096] = (z / torch.sqrt(chi / 4.0) / np.sqrt(2.0)).to(torch.bfloat16)
+        del z, chi
+        w = _randn_bf16((N, K), 0.015, gen, dev)
+        wc, wm = _quantize_rows(hif4, w)
+        c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
+        mfma_leg("gemm_w4a4_quantize_inside_M16384_N28672_K8192", M, N, K,
+                 lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
+                 "hif4::gemm_kernel<256,256>")
+        # speed reference on the same shape: the vendor library's plain BF16 GEMM on the unquantised operands
+        ref = lambda: torch.matmul(a, w.t(), out=c)
+        ref()
+        ms = _timed(ref, max(2, steps // 2))
+        legs["reference_bf16_library_gemm_M16384_N28672_K8192"] = {"ms": round(ms, 4), "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
+        del a, w, wc, wm, c, ws
+    torch.cuda.empty_cache()
+    return legs
