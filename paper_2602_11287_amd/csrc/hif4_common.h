@@ -67,6 +67,9 @@ __device__ __forceinline__ uint32_t pk_fma_f16(uint32_t a, uint32_t b, uint32_t 
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// Bit-field insert: bits of a where mask is set, bits of b elsewhere (v_bfi_b32).
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
+
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 __device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 

@@ -16,42 +16,87 @@
 //
 // K order inside a unit: the sum over k may run in any order as long as both operands
 // use the same one.  A group of 8 elements j (one dword of codes) becomes one 16-byte LDS
-// cell holding its elements in the order 0,1,2,3,4,5,6,7 -> (0,1),(2,3),(4,5),(6,7) as
-// BF16 pairs; MFMA sub-step s (of 4) takes cell 2s from lanes 0..31 and cell 2s+1 from
+// cell holding its elements in the order 0,2,1,3,4,6,5,7 (see expand_chunk) as BF16
+// pairs; MFMA sub-step s (of 4) takes cell 2s from lanes 0..31 and cell 2s+1 from
 // lanes 32..63.  Cells are stored [j][row], so both the expansion writes and the operand
 // reads of a wave touch consecutive 16-byte cells.
 #include "hif4_common.h"
+
+#ifndef HIF4_GEMM_SCHED
+#define HIF4_GEMM_SCHED 1
+#endif
 
 namespace hif4 {
 
 // ------------------------------------------------------------------ expansion
 
-// One dword of codes (group of 8 number j of a unit with metadata m) -> 8 BF16 in a uint4.
+// One dword of codes (group of 8 number j of a unit with metadata m) -> 8 BF16 in a uint4,
+// in the cell order e0,e2 | e1,e3 | e4,e6 | e5,e7 (the K order inside a cell is free as long
+// as both operands share it; this one puts the two sign bits of every pair 16 bits apart in
+// the codes dword, so one shift and one bit-field insert place both).
 // `sbase` is the fp32 pattern of (4+M) * 2^(E-52) for the unit, or a NaN pattern.
 __device__ __forceinline__ uint4 expand_chunk(uint32_t c, uint32_t m, uint32_t sbase, int j)
 {
     const uint32_t e8 = (m >> (8 + j)) & 1u;
     const uint32_t e16a = (m >> (16 + 2 * j)) & 1u, e16b = (m >> (17 + 2 * j)) & 1u;
     const float sa = u2f(sbase + ((e8 + e16a) << 23)), sb = u2f(sbase + ((e8 + e16b) << 23));
-    const uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u;
-    const uint32_t sl = (c << 4) & 0x80808080u, sh = c & 0x80808080u;
-    float f[8];
-    f[0] = (float)(lo & 0xFFu) * sa;
-    f[1] = (float)((lo >> 8) & 0xFFu) * sa;
-    f[2] = (float)((lo >> 16) & 0xFFu) * sa;
-    f[3] = (float)(lo >> 24) * sa;
-    f[4] = (float)(hi & 0xFFu) * sb;
-    f[5] = (float)((hi >> 8) & 0xFFu) * sb;
-    f[6] = (float)((hi >> 16) & 0xFFu) * sb;
-    f[7] = (float)(hi >> 24) * sb;
-    uint32_t r[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const uint32_t pair = __builtin_amdgcn_perm(f2u(f[2 * t + 1]), f2u(f[2 * t]), 0x07060302u);
-        const uint32_t sg = __builtin_amdgcn_perm(0u, t < 2 ? sl : sh, (t & 1) ? 0x030C020Cu : 0x010C000Cu);
-        r[t] = pair | sg;
-    }
-    return make_uint4(r[0], r[1], r[2], r[3]);
+    uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u; // magnitudes of elements 0..3 / 4..7, one per byte
+    asm volatile("" : "+v"(lo), "+v"(hi));                      // keep them as bytes: v_cvt_f32_ubyteN reads them in place
+    const float f0 = (float)(lo & 0xFFu) * sa, f1 = (float)((lo >> 8) & 0xFFu) * sa;
+    const float f2 = (float)((lo >> 16) & 0xFFu) * sa, f3 = (float)(lo >> 24) * sa;
+    const float f4 = (float)(hi & 0xFFu) * sb, f5 = (float)((hi >> 8) & 0xFFu) * sb;
+    const float f6 = (float)((hi >> 16) & 0xFFu) * sb, f7 = (float)(hi >> 24) * sb;
+    // exact values: the BF16 form is the top half of the fp32 pattern.  Signs: element t at
+    // bit 8t+3, element 4+t at bit 8t+7 of c.
+    constexpr uint32_t MAG = 0x7FFF7FFFu;
+    uint4 r;
+    r.x = bfi(MAG, __builtin_amdgcn_perm(f2u(f2), f2u(f0), 0x07060302u), c << 12);
+    r.y = bfi(MAG, __builtin_amdgcn_perm(f2u(f3), f2u(f1), 0x07060302u), c << 4);
+    r.z = bfi(MAG, __builtin_amdgcn_perm(f2u(f6), f2u(f4), 0x07060302u), c << 8);
+    r.w = bfi(MAG, __builtin_amdgcn_perm(f2u(f7), f2u(f5), 0x07060302u), c);
+    return r;
+}
+
+// The same expansion cut into five pieces, so that the GEMM main loop can place one piece
+// after each MFMA: chunk_begin (masks and the two group scales), then four pairs.
+struct ChunkState {
+    uint32_t c, lo, hi;
+    float sa, sb;
+};
+
+__device__ __forceinline__ ChunkState chunk_begin(uint32_t c, uint32_t m, uint32_t sbase, int j)
+{
+    ChunkState st;
+    const uint32_t e8 = (m >> (8 + j)) & 1u;
+    const uint32_t e16a = (m >> (16 + 2 * j)) & 1u, e16b = (m >> (17 + 2 * j)) & 1u;
+    st.sa = u2f(sbase + ((e8 + e16a) << 23));
+    st.sb = u2f(sbase + ((e8 + e16b) << 23));
+    st.c = c;
+    st.lo = c & 0x07070707u;
+    st.hi = (c >> 4) & 0x07070707u;
+    asm volatile("" : "+v"(st.lo), "+v"(st.hi));
+    return st;
+}
+
+template <int T>
+__device__ __forceinline__ uint32_t chunk_pair(const ChunkState &st)
+{
+    constexpr uint32_t MAG = 0x7FFF7FFFu;
+    if (T == 0) return bfi(MAG, __builtin_amdgcn_perm(f2u((float)((st.lo >> 16) & 0xFFu) * st.sa), f2u((float)(st.lo & 0xFFu) * st.sa), 0x07060302u), st.c << 12);
+    if (T == 1) return bfi(MAG, __builtin_amdgcn_perm(f2u((float)(st.lo >> 24) * st.sa), f2u((float)((st.lo >> 8) & 0xFFu) * st.sa), 0x07060302u), st.c << 4);
+    if (T == 2) return bfi(MAG, __builtin_amdgcn_perm(f2u((float)((st.hi >> 16) & 0xFFu) * st.sb), f2u((float)(st.hi & 0xFFu) * st.sb), 0x07060302u), st.c << 8);
+    return bfi(MAG, __builtin_amdgcn_perm(f2u((float)(st.hi >> 24) * st.sb), f2u((float)((st.hi >> 8) & 0xFFu) * st.sb), 0x07060302u), st.c);
+}
+
+// 8 consecutive plain BF16 values -> the same cell order.
+__device__ __forceinline__ uint4 permute_bf16_cell(uint4 v)
+{
+    uint4 r;
+    r.x = __builtin_amdgcn_perm(v.y, v.x, 0x05040100u); // e0, e2
+    r.y = __builtin_amdgcn_perm(v.y, v.x, 0x07060302u); // e1, e3
+    r.z = __builtin_amdgcn_perm(v.w, v.z, 0x05040100u); // e4, e6
+    r.w = __builtin_amdgcn_perm(v.w, v.z, 0x07060302u); // e5, e7
+    return r;
 }
 
 // fp32 pattern of the unit scale (4+M) * 2^(E-48-4), NaN for the NaN unit.
@@ -121,34 +166,32 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     const int col0 = tile_n * BN;
     const int upr = g.K / 64; // units per row
 
-    // ---- expansion role of this thread: unit `u` of the tile (A rows first, then W rows)
-    constexpr int UPT = (BM + BN + NT - 1) / NT; // units per thread per K step
-    const uint32_t *src_codes[UPT];
-    const uint32_t *src_meta[UPT];
-    const uint16_t *src_bf16[UPT];
-    int cell0[UPT];
-    bool active[UPT];
-#pragma unroll
-    for (int i = 0; i < UPT; ++i) {
-        const int u = tid + i * NT;
-        active[i] = u < BM + BN;
-        if (u < BM) {
-            int r = row0 + u;
-            r = r < rows_end ? r : rows_end - 1; // rows past the edge repeat the last one; never stored
-            src_codes[i] = g.a_codes + (int64_t)r * (g.K / 8);
-            src_meta[i] = g.a_meta + (int64_t)r * upr;
-            src_bf16[i] = reinterpret_cast<const uint16_t *>(g.a_codes) + (int64_t)r * g.lda;
-            cell0[i] = u;
-        } else {
-            int r = col0 + (u - BM);
-            r = r < g.N ? r : g.N - 1;
-            src_codes[i] = w_codes + (int64_t)r * (g.K / 8);
-            src_meta[i] = w_meta + (int64_t)r * upr;
-            src_bf16[i] = nullptr;
-            cell0[i] = 8 * BM + (u - BM);
-        }
+    // ---- expansion role of this thread: unit `u` of the tile (A rows first, then W rows).
+    // With fewer units than threads the surplus threads repeat the last units (same bytes to
+    // the same cells), which keeps the loop body free of branches.
+    static_assert(BM + BN <= NT, "one unit per thread and K step");
+    const int u = tid < BM + BN ? tid : tid - (NT - BN);
+    const bool is_a = u < BM;
+    const uint32_t *src_codes;
+    const uint32_t *src_meta;
+    int cell0, cstride;
+    if (is_a) {
+        int r = row0 + u;
+        r = r < rows_end ? r : rows_end - 1; // rows past the edge repeat the last one; never stored
+        src_codes = A_BF16 ? g.a_codes + (int64_t)r * (g.lda / 2) : g.a_codes + (int64_t)r * (g.K / 8);
+        src_meta = A_BF16 ? g.w_meta : g.a_meta + (int64_t)r * upr; // (unused for plain BF16 rows)
+        cell0 = u;
+        cstride = BM;
+    } else {
+        int r = col0 + (u - BM);
+        r = r < g.N ? r : g.N - 1;
+        src_codes = w_codes + (int64_t)r * (g.K / 8);
+        src_meta = w_meta + (int64_t)r * upr;
+        cell0 = 8 * BM + (u - BM);
+        cstride = BN;
     }
     // cell (j, row) of the A part sits at j*BM + row; of the W part at 8*BM + j*BN + row
+    const bool plain = A_BF16 && is_a; // wave-uniform: BM is a multiple of 64
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -158,74 +201,119 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    uint4 pc[UPT][A_BF16 ? 8 : 2]; // next step: packed codes of a unit, or 64 BF16 of a plain A row
-    uint32_t pm[UPT];
-
-    auto fetch = [&](int ks) {
-#pragma unroll
-        for (int i = 0; i < UPT; ++i) {
-            if (!active[i]) continue;
-            if (A_BF16 && (tid + i * NT) < BM) {
-                const uint4 *p = reinterpret_cast<const uint4 *>(src_bf16[i] + (int64_t)ks * 64);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) pc[i][j] = p[j];
-            } else {
-                const uint4 *p = reinterpret_cast<const uint4 *>(src_codes[i] + ks * 8);
-                pc[i][0] = p[0];
-                pc[i][1] = p[1];
-                pm[i] = src_meta[i][ks];
-            }
-        }
-    };
-    auto expand_to = [&](uint4 *buf) {
-#pragma unroll
-        for (int i = 0; i < UPT; ++i) {
-            if (!active[i]) continue;
-            if (A_BF16 && (tid + i * NT) < BM) { // plain BF16 activations: cells are straight copies
-#pragma unroll
-                for (int j = 0; j < 8; ++j) buf[cell0[i] + j * BM] = pc[i][j];
-                continue;
-            }
-            const uint32_t sbase = unit_scale_bits(pm[i]);
-            const uint32_t cw[8] = { pc[i][0].x, pc[i][0].y, pc[i][0].z, pc[i][0].w,
-                                     pc[i][1].x, pc[i][1].y, pc[i][1].z, pc[i][1].w };
-            const int stride = (tid + i * NT) < BM ? BM : BN;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) buf[cell0[i] + j * stride] = expand_chunk(cw[j], pm[i], sbase, j);
-        }
-    };
-
+    // Two register sets of packed input, two K steps ahead of the matrix work.
+    constexpr int NPC = A_BF16 ? 8 : 2;
+    struct Packed { uint4 c[NPC]; uint32_t m; };
     const int nk = upr;
-    if (nk > 0) {
-        fetch(0);
-        expand_to(lds);
-    }
-    __syncthreads();
+
+    auto fetch = [&](Packed &pk, int ks) {
+        ks = ks < nk ? ks : nk - 1; // past the end: reload the last step, never used
+        if (plain) {
+            const uint4 *p = reinterpret_cast<const uint4 *>(src_codes + (int64_t)ks * 32);
+#pragma unroll
+            for (int j = 0; j < NPC; ++j) pk.c[j] = p[j];
+            pk.m = 0;
+        } else {
+            const uint4 *p = reinterpret_cast<const uint4 *>(src_codes + ks * 8);
+            pk.c[0] = p[0];
+            pk.c[1] = p[1];
+            pk.m = src_meta[ks];
+        }
+    };
+    // cells 2q and 2q+1 of this thread's unit -> LDS
+    auto expand_quarter = [&](const Packed &pk, uint4 *buf, int q) {
+        if (plain) {
+            if (NPC == 8) {
+                buf[cell0 + (2 * q) * cstride] = permute_bf16_cell(pk.c[(2 * q) % NPC]);
+                buf[cell0 + (2 * q + 1) * cstride] = permute_bf16_cell(pk.c[(2 * q + 1) % NPC]);
+            }
+        } else {
+            const uint32_t sbase = unit_scale_bits(pk.m);
+            const uint4 cw = pk.c[q / 2];
+            const uint32_t c0 = (q & 1) ? cw.z : cw.x, c1 = (q & 1) ? cw.w : cw.y;
+            buf[cell0 + (2 * q) * cstride] = expand_chunk(c0, pk.m, sbase, 2 * q);
+            buf[cell0 + (2 * q + 1) * cstride] = expand_chunk(c1, pk.m, sbase, 2 * q + 1);
+        }
+    };
 
     const int half = lane / 32, l32 = lane % 32;
-    for (int ks = 0; ks < nk; ++ks) {
-        uint4 *cur = lds + (ks & 1) * CELLS;
-        uint4 *nxt = lds + ((ks + 1) & 1) * CELLS;
-        if (ks + 1 < nk) fetch(ks + 1);
+    constexpr int NMF = TM * TN;  // MFMAs per quarter step
+    constexpr int SPM = 8 / NMF;  // expansion slices (BF16 pairs) placed after each MFMA
+    static_assert(NMF * SPM == 8, "the 8 pairs of a quarter are spread evenly over its MFMAs");
 
+    // One K step: matrix work on `cur`, expansion of the following step from `pk` into `nxt`.
+    // A step has four quarters (one MFMA K-slab of 16 each); a quarter issues TM*TN = 8 MFMAs
+    // and expands two cells (8 BF16 pairs): one pair after each MFMA, fenced, so that the
+    // VALU work runs while the matrix pipeline is busy.  Operand reads of the next quarter are
+    // issued in the middle of the current one.
+    auto k_step = [&](const uint4 *cur, uint4 *nxt, const Packed &pk) {
         const uint4 *abase = cur + wm * (BM / WM) + l32;
         const uint4 *bbase = cur + 8 * BM + wn * (BN / WN) + l32;
+        bf16x8_t af[2][TM], bfr[2][TN];
+        auto load_frags = [&](int s) {
+            const int j = 2 * s + half;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[s & 1][i] = __builtin_bit_cast(bf16x8_t, abase[j * BM + i * 32]);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + i * 32]);
+        };
+        const uint32_t sbase = unit_scale_bits(pk.m);
+        load_frags(0);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const int j = 2 * s + half;
-            bf16x8_t af[TM], bfr[TN];
+            ChunkState st;
+            uint4 cell;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = __builtin_bit_cast(bf16x8_t, abase[j * BM + i * 32]);
+            for (int tm = 0; tm < NMF; ++tm) {
+                acc[tm / TN][tm % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][tm / TN], bfr[s & 1][tm % TN], acc[tm / TN][tm % TN], 0, 0, 0);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) bfr[i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + i * 32]);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int jn = 0; jn < TN; ++jn)
-                    acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[jn], acc[i][jn], 0, 0, 0);
+                for (int sl = 0; sl < SPM; ++sl) {
+                    const int t = tm * SPM + sl;  // slice 0..7 of this quarter
+                    const int jc = 2 * s + t / 4; // cell being expanded
+                    if (plain) {
+                        if (NPC == 8 && t % 4 == 0) nxt[cell0 + jc * cstride] = permute_bf16_cell(pk.c[jc % NPC]);
+                    } else {
+                        if (t % 4 == 0) {
+                            const uint4 cw = pk.c[(jc / 4) % NPC];
+                            const uint32_t cj = (jc % 4 == 0) ? cw.x : (jc % 4 == 1) ? cw.y : (jc % 4 == 2) ? cw.z : cw.w;
+                            st = chunk_begin(cj, pk.m, sbase, jc);
+                            cell.x = chunk_pair<0>(st);
+                        } else if (t % 4 == 1) {
+                            cell.y = chunk_pair<1>(st);
+                        } else if (t % 4 == 2) {
+                            cell.z = chunk_pair<2>(st);
+                        } else {
+                            cell.w = chunk_pair<3>(st);
+                            nxt[cell0 + jc * cstride] = cell;
+                        }
+                    }
+                }
+                if (tm == NMF / 4 && s < 3) load_frags(s + 1);
+#if HIF4_GEMM_SCHED
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+            }
         }
-        if (ks + 1 < nk) expand_to(nxt);
+    };
+
+    uint4 *buf0 = lds, *buf1 = lds + CELLS;
+    Packed set0, set1;
+    fetch(set0, 0);
+    fetch(set1, 1);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) expand_quarter(set0, buf0, q);
+    fetch(set0, 2);
+    __syncthreads();
+
+    for (int ks = 0; ks < nk; ks += 2) {
+        k_step(buf0, buf1, set1); // matrix work of step ks, expansion of step ks+1
+        fetch(set1, ks + 3);
         __syncthreads();
+        if (ks + 1 < nk) {
+            k_step(buf1, buf0, set0); // step ks+1, expansion of step ks+2
+            fetch(set0, ks + 4);
+            __syncthreads();
+        }
     }
 
     // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*half + r%4
@@ -296,7 +384,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const uint16_t *__rest
             for (int mb = 0; mb < MB; ++mb) {
                 const int row = mb * 16 + n_l;
                 uint4 av = make_uint4(0, 0, 0, 0);
-                if (valid && row < M) av = *reinterpret_cast<const uint4 *>(a + (int64_t)row * lda + (int64_t)uc * 64 + j * 8);
+                if (valid && row < M) av = permute_bf16_cell(*reinterpret_cast<const uint4 *>(a + (int64_t)row * lda + (int64_t)uc * 64 + j * 8));
                 acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), bfrag, acc[mb], 0, 0, 0);
             }
         }
