@@ -106,8 +106,10 @@ int hif4_dequantize(const uint8_t *codes, const uint32_t *meta, int64_t rows, in
  *   w_codes    in   uint8 [N][K/2];  w_meta in uint32 [N][K/64]
  *   c          out  BF16 or fp32 [M][ldc] per out_dtype, ldc >= N
  *   workspace       device scratch of at least hif4_gemm_workspace_bytes(a_kind, M, K)
- *                   bytes, 16-byte aligned (holds the packed A for kind 0; may be NULL
- *                   when that size is 0)
+ *                   bytes, 16-byte aligned.  Kinds 0 and 1 use it for the exact BF16 values
+ *                   of the HiF4 activations (2 bytes per element; kind 0 also for the packed
+ *                   planes before that); kind 2 needs none and it may be NULL.  Its contents
+ *                   after the call are unspecified.
  * M == 0 or N == 0 is a no-op; K == 0 writes zeros.
  */
 int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,

@@ -10,6 +10,7 @@ int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int6
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
                 int64_t ldc, int out_dtype, void *workspace, hipStream_t stream);
+size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
 } // namespace hif4
 
 namespace {
@@ -79,11 +80,8 @@ int hif4_dequantize(const uint8_t *codes, const uint32_t *meta, int64_t rows, in
 
 size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K)
 {
-    if (a_kind != HIF4_A_BF16_QUANTIZE || M_or_total_rows <= 0 || K <= 0 || K % HIF4_UNIT != 0) return 0;
-    // packed A: codes plane (rounded up to 16 bytes) followed by the meta plane
-    const size_t codes = (size_t)M_or_total_rows * (size_t)K / 2;
-    const size_t meta = (size_t)M_or_total_rows * (size_t)(K / HIF4_UNIT) * sizeof(uint32_t);
-    return ((codes + 15) & ~(size_t)15) + meta;
+    if (K % HIF4_UNIT != 0) return 0;
+    return hif4::gemm_workspace_bytes(a_kind, M_or_total_rows, K);
 }
 
 int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,

@@ -20,7 +20,7 @@
 // pairs; MFMA sub-step s (of 4) takes cell 2s from lanes 0..31 and cell 2s+1 from
 // lanes 32..63.  Cells are stored [j][row], so both the expansion writes and the operand
 // reads of a wave touch consecutive 16-byte cells.
-#include "hif4_common.h"
+#include "hif4_expand.h"
 
 #ifndef HIF4_GEMM_SCHED
 #define HIF4_GEMM_SCHED 1
@@ -28,106 +28,30 @@
 
 namespace hif4 {
 
-// ------------------------------------------------------------------ expansion
-
-// One dword of codes (group of 8 number j of a unit with metadata m) -> 8 BF16 in a uint4,
-// in the cell order e0,e2 | e1,e3 | e4,e6 | e5,e7 (the K order inside a cell is free as long
-// as both operands share it; this one puts the two sign bits of every pair 16 bits apart in
-// the codes dword, so one shift and one bit-field insert place both).
-// `sbase` is the fp32 pattern of (4+M) * 2^(E-52) for the unit, or a NaN pattern.
-__device__ __forceinline__ uint4 expand_chunk(uint32_t c, uint32_t m, uint32_t sbase, int j)
-{
-    const uint32_t e8 = (m >> (8 + j)) & 1u;
-    const uint32_t e16a = (m >> (16 + 2 * j)) & 1u, e16b = (m >> (17 + 2 * j)) & 1u;
-    const float sa = u2f(sbase + ((e8 + e16a) << 23)), sb = u2f(sbase + ((e8 + e16b) << 23));
-    uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u; // magnitudes of elements 0..3 / 4..7, one per byte
-    asm volatile("" : "+v"(lo), "+v"(hi));                      // keep them as bytes: v_cvt_f32_ubyteN reads them in place
-    const float f0 = (float)(lo & 0xFFu) * sa, f1 = (float)((lo >> 8) & 0xFFu) * sa;
-    const float f2 = (float)((lo >> 16) & 0xFFu) * sa, f3 = (float)(lo >> 24) * sa;
-    const float f4 = (float)(hi & 0xFFu) * sb, f5 = (float)((hi >> 8) & 0xFFu) * sb;
-    const float f6 = (float)((hi >> 16) & 0xFFu) * sb, f7 = (float)(hi >> 24) * sb;
-    // exact values: the BF16 form is the top half of the fp32 pattern.  Signs: element t at
-    // bit 8t+3, element 4+t at bit 8t+7 of c.
-    constexpr uint32_t MAG = 0x7FFF7FFFu;
-    uint4 r;
-    r.x = bfi(MAG, __builtin_amdgcn_perm(f2u(f2), f2u(f0), 0x07060302u), c << 12);
-    r.y = bfi(MAG, __builtin_amdgcn_perm(f2u(f3), f2u(f1), 0x07060302u), c << 4);
-    r.z = bfi(MAG, __builtin_amdgcn_perm(f2u(f6), f2u(f4), 0x07060302u), c << 8);
-    r.w = bfi(MAG, __builtin_amdgcn_perm(f2u(f7), f2u(f5), 0x07060302u), c);
-    return r;
-}
-
-// The same expansion cut into five pieces, so that the GEMM main loop can place one piece
-// after each MFMA: chunk_begin (masks and the two group scales), then four pairs.
-struct ChunkState {
-    uint32_t c, lo, hi;
-    float sa, sb;
-};
-
-__device__ __forceinline__ ChunkState chunk_begin(uint32_t c, uint32_t m, uint32_t sbase, int j)
-{
-    ChunkState st;
-    const uint32_t e8 = (m >> (8 + j)) & 1u;
-    const uint32_t e16a = (m >> (16 + 2 * j)) & 1u, e16b = (m >> (17 + 2 * j)) & 1u;
-    st.sa = u2f(sbase + ((e8 + e16a) << 23));
-    st.sb = u2f(sbase + ((e8 + e16b) << 23));
-    st.c = c;
-    st.lo = c & 0x07070707u;
-    st.hi = (c >> 4) & 0x07070707u;
-    asm volatile("" : "+v"(st.lo), "+v"(st.hi));
-    return st;
-}
-
-template <int T>
-__device__ __forceinline__ uint32_t chunk_pair(const ChunkState &st)
-{
-    constexpr uint32_t MAG = 0x7FFF7FFFu;
-    if (T == 0) return bfi(MAG, __builtin_amdgcn_perm(f2u((float)((st.lo >> 16) & 0xFFu) * st.sa), f2u((float)(st.lo & 0xFFu) * st.sa), 0x07060302u), st.c << 12);
-    if (T == 1) return bfi(MAG, __builtin_amdgcn_perm(f2u((float)(st.lo >> 24) * st.sa), f2u((float)((st.lo >> 8) & 0xFFu) * st.sa), 0x07060302u), st.c << 4);
-    if (T == 2) return bfi(MAG, __builtin_amdgcn_perm(f2u((float)((st.hi >> 16) & 0xFFu) * st.sb), f2u((float)(st.hi & 0xFFu) * st.sb), 0x07060302u), st.c << 8);
-    return bfi(MAG, __builtin_amdgcn_perm(f2u((float)(st.hi >> 24) * st.sb), f2u((float)((st.hi >> 8) & 0xFFu) * st.sb), 0x07060302u), st.c);
-}
-
-// 8 consecutive plain BF16 values -> the same cell order.
-__device__ __forceinline__ uint4 permute_bf16_cell(uint4 v)
-{
-    uint4 r;
-    r.x = __builtin_amdgcn_perm(v.y, v.x, 0x05040100u); // e0, e2
-    r.y = __builtin_amdgcn_perm(v.y, v.x, 0x07060302u); // e1, e3
-    r.z = __builtin_amdgcn_perm(v.w, v.z, 0x05040100u); // e4, e6
-    r.w = __builtin_amdgcn_perm(v.w, v.z, 0x07060302u); // e5, e7
-    return r;
-}
-
-// fp32 pattern of the unit scale (4+M) * 2^(E-48-4), NaN for the NaN unit.
-__device__ __forceinline__ uint32_t unit_scale_bits(uint32_t m)
-{
-    const uint32_t s = ((((m >> 2) & 0x3Fu) + (127u - 50u)) << 23) | ((m & 3u) << 21);
-    return (m & 0xFFu) == 0xFFu ? 0x7FC00000u : s;
-}
-
 // ------------------------------------------------------------------ kernel
 
 struct GemmArgs {
-    const uint32_t *a_codes; // packed A: [M][K/8] dwords, or BF16 A when A_BF16
-    const uint32_t *a_meta;  // [M][K/64]
-    const uint32_t *w_codes; // [E][N][K/8]
+    const uint16_t *a;       // BF16 activations [M][lda]: plain rows, or rows already in cell order
+    const uint32_t *w_codes; // [E][N][K/8] dwords
     const uint32_t *w_meta;  // [E][N][K/64]
     const int32_t *offs;     // grouped: device int32[E+1]; else nullptr
     void *c;
-    int64_t lda; // BF16 A only: row stride in elements
+    int64_t lda; // row stride of a, in elements
     int64_t ldc;
     int M, N, K, E;
     int tiles_n;
 };
 
-template <int BM, int BN, int WM, int WN, bool A_BF16, bool OUT_F32, bool GROUPED>
+// A_CELL: the 8 BF16 of every group of 8 in `a` are already stored in cell order (the
+// library's own decoded copy of a HiF4 operand); otherwise they are permuted on the way in.
+template <int BM, int BN, int WM, int WN, bool A_CELL, bool OUT_F32, bool GROUPED>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 {
     constexpr int NT = 64 * WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32; // MFMA tiles per wave
     constexpr int CELLS = 8 * (BM + BN);                // 16-byte cells per buffer
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tiles are multiples of 32");
+    static_assert(2 * BM <= NT && 2 * BN <= NT && NT % (2 * BM) == 0 && NT % (2 * BN) == 0, "two threads per row");
     extern __shared__ uint4 lds[]; // 2 buffers x CELLS
 
     const int tid = threadIdx.x;
@@ -165,33 +89,23 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     }
     const int col0 = tile_n * BN;
     const int upr = g.K / 64; // units per row
+    const int nk = upr;
 
-    // ---- expansion role of this thread: unit `u` of the tile (A rows first, then W rows).
-    // With fewer units than threads the surplus threads repeat the last units (same bytes to
-    // the same cells), which keeps the loop body free of branches.
-    static_assert(BM + BN <= NT, "one unit per thread and K step");
-    const int u = tid < BM + BN ? tid : tid - (NT - BN);
-    const bool is_a = u < BM;
-    const uint32_t *src_codes;
-    const uint32_t *src_meta;
-    int cell0, cstride;
-    if (is_a) {
-        int r = row0 + u;
-        r = r < rows_end ? r : rows_end - 1; // rows past the edge repeat the last one; never stored
-        src_codes = A_BF16 ? g.a_codes + (int64_t)r * (g.lda / 2) : g.a_codes + (int64_t)r * (g.K / 8);
-        src_meta = A_BF16 ? g.w_meta : g.a_meta + (int64_t)r * upr; // (unused for plain BF16 rows)
-        cell0 = u;
-        cstride = BM;
-    } else {
-        int r = col0 + (u - BM);
-        r = r < g.N ? r : g.N - 1;
-        src_codes = w_codes + (int64_t)r * (g.K / 8);
-        src_meta = w_meta + (int64_t)r * upr;
-        cell0 = 8 * BM + (u - BM);
-        cstride = BN;
-    }
+    // ---- staging role of this thread, per K step: half a packed unit of a W row (4 dwords of
+    // codes -> 4 cells) and half a unit of an A row (64 bytes of BF16 -> 4 cells).  With fewer
+    // rows than thread pairs the surplus threads repeat rows (same bytes to the same cells),
+    // which keeps the loop body free of branches.
+    const int h = tid & 1;
+    const int ra = (tid >> 1) % BM, rw = (tid >> 1) % BN;
+    int arow = row0 + ra;
+    arow = arow < rows_end ? arow : rows_end - 1; // rows past the edge repeat the last one; never stored
+    int wrow = col0 + rw;
+    wrow = wrow < g.N ? wrow : g.N - 1;
+    const uint16_t *a_src = g.a + (int64_t)arow * g.lda + 32 * h;
+    const uint32_t *wc_src = w_codes + (int64_t)wrow * (g.K / 8) + 4 * h;
+    const uint32_t *wm_src = w_meta + (int64_t)wrow * upr;
     // cell (j, row) of the A part sits at j*BM + row; of the W part at 8*BM + j*BN + row
-    const bool plain = A_BF16 && is_a; // wave-uniform: BM is a multiple of 64
+    const int a_cell0 = (4 * h) * BM + ra, w_cell0 = 8 * BM + (4 * h) * BN + rw;
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -201,52 +115,34 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // Two register sets of packed input, two K steps ahead of the matrix work.
-    constexpr int NPC = A_BF16 ? 8 : 2;
-    struct Packed { uint4 c[NPC]; uint32_t m; };
-    const int nk = upr;
-
-    auto fetch = [&](Packed &pk, int ks) {
+    // Two register sets of staged input, two K steps ahead of the matrix work.
+    struct Staged {
+        uint4 wc;
+        uint32_t wm;
+        uint4 a[4];
+    };
+    auto fetch = [&](Staged &st, int ks) {
         ks = ks < nk ? ks : nk - 1; // past the end: reload the last step, never used
-        if (plain) {
-            const uint4 *p = reinterpret_cast<const uint4 *>(src_codes + (int64_t)ks * 32);
+        st.wc = *reinterpret_cast<const uint4 *>(wc_src + ks * 8);
+        st.wm = wm_src[ks];
+        const uint4 *p = reinterpret_cast<const uint4 *>(a_src + (int64_t)ks * 64);
 #pragma unroll
-            for (int j = 0; j < NPC; ++j) pk.c[j] = p[j];
-            pk.m = 0;
-        } else {
-            const uint4 *p = reinterpret_cast<const uint4 *>(src_codes + ks * 8);
-            pk.c[0] = p[0];
-            pk.c[1] = p[1];
-            pk.m = src_meta[ks];
-        }
+        for (int j = 0; j < 4; ++j) st.a[j] = p[j];
     };
-    // cells 2q and 2q+1 of this thread's unit -> LDS
-    auto expand_quarter = [&](const Packed &pk, uint4 *buf, int q) {
-        if (plain) {
-            if (NPC == 8) {
-                buf[cell0 + (2 * q) * cstride] = permute_bf16_cell(pk.c[(2 * q) % NPC]);
-                buf[cell0 + (2 * q + 1) * cstride] = permute_bf16_cell(pk.c[(2 * q + 1) % NPC]);
-            }
-        } else {
-            const uint32_t sbase = unit_scale_bits(pk.m);
-            const uint4 cw = pk.c[q / 2];
-            const uint32_t c0 = (q & 1) ? cw.z : cw.x, c1 = (q & 1) ? cw.w : cw.y;
-            buf[cell0 + (2 * q) * cstride] = expand_chunk(c0, pk.m, sbase, 2 * q);
-            buf[cell0 + (2 * q + 1) * cstride] = expand_chunk(c1, pk.m, sbase, 2 * q + 1);
-        }
-    };
+    auto a_cell = [&](const Staged &st, int q) { return A_CELL ? st.a[q] : permute_bf16_cell(st.a[q]); };
+    auto w_word = [&](const Staged &st, int q) { return q == 0 ? st.wc.x : q == 1 ? st.wc.y : q == 2 ? st.wc.z : st.wc.w; };
 
     const int half = lane / 32, l32 = lane % 32;
-    constexpr int NMF = TM * TN;  // MFMAs per quarter step
-    constexpr int SPM = 8 / NMF;  // expansion slices (BF16 pairs) placed after each MFMA
-    static_assert(NMF * SPM == 8, "the 8 pairs of a quarter are spread evenly over its MFMAs");
+    constexpr int NMF = TM * TN; // MFMAs per quarter step
+    constexpr int SPM = 8 / NMF; // staging slots after each MFMA
+    static_assert(NMF * SPM == 8, "eight staging slots per quarter, spread evenly over its MFMAs");
 
-    // One K step: matrix work on `cur`, expansion of the following step from `pk` into `nxt`.
-    // A step has four quarters (one MFMA K-slab of 16 each); a quarter issues TM*TN = 8 MFMAs
-    // and expands two cells (8 BF16 pairs): one pair after each MFMA, fenced, so that the
-    // VALU work runs while the matrix pipeline is busy.  Operand reads of the next quarter are
-    // issued in the middle of the current one.
-    auto k_step = [&](const uint4 *cur, uint4 *nxt, const Packed &pk) {
+    // One K step: matrix work on `cur`, staging of the following step from `st` into `nxt`.
+    // A step has four quarters (one MFMA K-slab of 16 each).  In quarter q the thread expands
+    // its W dword q (begin + 4 BF16 pairs) and copies its A cell q: one slot of that work
+    // after each MFMA, fenced, so that the VALU work runs while the matrix pipeline is busy.
+    // Operand reads of the next quarter are issued early in the current one.
+    auto k_step = [&](const uint4 *cur, uint4 *nxt, const Staged &st) {
         const uint4 *abase = cur + wm * (BM / WM) + l32;
         const uint4 *bbase = cur + 8 * BM + wn * (BN / WN) + l32;
         bf16x8_t af[2][TM], bfr[2][TN];
@@ -257,35 +153,30 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + i * 32]);
         };
-        const uint32_t sbase = unit_scale_bits(pk.m);
+        const uint32_t sbase = unit_scale_bits(st.wm);
         load_frags(0);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            ChunkState st;
+            ChunkState cs;
             uint4 cell;
 #pragma unroll
             for (int tm = 0; tm < NMF; ++tm) {
                 acc[tm / TN][tm % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][tm / TN], bfr[s & 1][tm % TN], acc[tm / TN][tm % TN], 0, 0, 0);
 #pragma unroll
                 for (int sl = 0; sl < SPM; ++sl) {
-                    const int t = tm * SPM + sl;  // slice 0..7 of this quarter
-                    const int jc = 2 * s + t / 4; // cell being expanded
-                    if (plain) {
-                        if (NPC == 8 && t % 4 == 0) nxt[cell0 + jc * cstride] = permute_bf16_cell(pk.c[jc % NPC]);
-                    } else {
-                        if (t % 4 == 0) {
-                            const uint4 cw = pk.c[(jc / 4) % NPC];
-                            const uint32_t cj = (jc % 4 == 0) ? cw.x : (jc % 4 == 1) ? cw.y : (jc % 4 == 2) ? cw.z : cw.w;
-                            st = chunk_begin(cj, pk.m, sbase, jc);
-                            cell.x = chunk_pair<0>(st);
-                        } else if (t % 4 == 1) {
-                            cell.y = chunk_pair<1>(st);
-                        } else if (t % 4 == 2) {
-                            cell.z = chunk_pair<2>(st);
-                        } else {
-                            cell.w = chunk_pair<3>(st);
-                            nxt[cell0 + jc * cstride] = cell;
-                        }
+                    const int slot = tm * SPM + sl;
+                    if (slot == 0) {
+                        cs = chunk_begin(w_word(st, s), st.wm, sbase, 4 * h + s);
+                        cell.x = chunk_pair<0>(cs);
+                    } else if (slot == 1) {
+                        cell.y = chunk_pair<1>(cs);
+                    } else if (slot == 2) {
+                        cell.z = chunk_pair<2>(cs);
+                    } else if (slot == 3) {
+                        cell.w = chunk_pair<3>(cs);
+                        nxt[w_cell0 + s * BN] = cell;
+                    } else if (slot == 4) {
+                        nxt[a_cell0 + s * BM] = a_cell(st, s);
                     }
                 }
                 if (tm == NMF / 4 && s < 3) load_frags(s + 1);
@@ -297,20 +188,26 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     };
 
     uint4 *buf0 = lds, *buf1 = lds + CELLS;
-    Packed set0, set1;
+    Staged set0, set1;
     fetch(set0, 0);
     fetch(set1, 1);
+    {
+        const uint32_t sbase = unit_scale_bits(set0.wm);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) expand_quarter(set0, buf0, q);
+        for (int q = 0; q < 4; ++q) {
+            buf0[w_cell0 + q * BN] = expand_chunk(w_word(set0, q), set0.wm, sbase, 4 * h + q);
+            buf0[a_cell0 + q * BM] = a_cell(set0, q);
+        }
+    }
     fetch(set0, 2);
     __syncthreads();
 
     for (int ks = 0; ks < nk; ks += 2) {
-        k_step(buf0, buf1, set1); // matrix work of step ks, expansion of step ks+1
+        k_step(buf0, buf1, set1); // matrix work of step ks, staging of step ks+1
         fetch(set1, ks + 3);
         __syncthreads();
         if (ks + 1 < nk) {
-            k_step(buf1, buf0, set0); // step ks+1, expansion of step ks+2
+            k_step(buf1, buf0, set0); // step ks+1, staging of step ks+2
             fetch(set0, ks + 4);
             __syncthreads();
         }
@@ -436,25 +333,39 @@ __global__ void zero_kernel(void *c, int64_t M, int64_t N, int64_t ldc, int elem
 
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream);
+int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 
-template <int BM, int BN, int WM, int WN, bool A_BF16, bool GROUPED>
+template <int BM, int BN, int WM, int WN, bool A_CELL, bool GROUPED>
 static int launch_tiles(const GemmArgs &g, int out_dtype, int m_tiles, hipStream_t stream)
 {
     constexpr size_t lds_bytes = 2 * 8 * (BM + BN) * sizeof(uint4);
     const dim3 grid((unsigned)((int64_t)m_tiles * g.tiles_n)), block(64 * WM * WN);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_kernel<BM, BN, WM, WN, A_BF16, true, GROUPED>;
+        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, true, GROUPED>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     } else {
-        auto k = gemm_kernel<BM, BN, WM, WN, A_BF16, false, GROUPED>;
+        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, false, GROUPED>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     }
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+// Workspace layout.  HIF4_A_BF16_QUANTIZE: packed A (codes, meta), then its decoded BF16 copy;
+// HIF4_A_HIF4: the decoded BF16 copy only.  Every part starts on a 16-byte boundary.
+static inline size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
+
+size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
+{
+    if (M <= 0 || K <= 0) return 0;
+    const size_t decoded = (size_t)M * (size_t)K * 2;
+    if (a_kind == HIF4_A_HIF4) return decoded;
+    if (a_kind == HIF4_A_BF16_QUANTIZE) return align16((size_t)M * (size_t)K / 2) + align16((size_t)M * (size_t)(K / 64) * 4) + decoded;
+    return 0;
 }
 
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
@@ -471,27 +382,35 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         if (M <= 32) return launch_skinny<2>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         return launch_skinny<4>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
     }
+    // HiF4 activations enter the tile kernel as their exact BF16 values (at most 6 significant
+    // bits each), decoded once per call into the workspace in cell order; only the weights are
+    // expanded inside the main loop.  This halves the VALU work next to the MFMA pipeline.
     GemmArgs g;
+    bool a_cell = true;
     if (a_kind == HIF4_A_BF16_KEEP) {
-        g.a_codes = static_cast<const uint32_t *>(a); // BF16 rows, staged as they are
-        g.a_meta = nullptr;
-    } else if (a_kind == HIF4_A_BF16_QUANTIZE) {
-        // quantise A into the workspace: codes plane, then the meta plane at the next 16-byte boundary
-        uint8_t *codes = static_cast<uint8_t *>(workspace);
-        const size_t cbytes = ((size_t)M * (size_t)K / 2 + 15) & ~(size_t)15;
-        uint32_t *meta = reinterpret_cast<uint32_t *>(codes + cbytes);
-        if (int rc = launch_encode(a, M, K, lda, codes, meta, HIF4_ROUND_RNE, stream)) return rc;
-        g.a_codes = reinterpret_cast<const uint32_t *>(codes);
-        g.a_meta = meta;
+        g.a = static_cast<const uint16_t *>(a);
+        g.lda = lda;
+        a_cell = false;
     } else {
-        g.a_codes = static_cast<const uint32_t *>(a);
-        g.a_meta = a_meta;
+        uint8_t *ws = static_cast<uint8_t *>(workspace);
+        const uint8_t *codes = static_cast<const uint8_t *>(a);
+        const uint32_t *meta = a_meta;
+        if (a_kind == HIF4_A_BF16_QUANTIZE) {
+            uint8_t *qc = ws;
+            uint32_t *qm = reinterpret_cast<uint32_t *>(ws + align16((size_t)M * (size_t)K / 2));
+            if (int rc = launch_encode(a, M, K, lda, qc, qm, HIF4_ROUND_RNE, stream)) return rc;
+            ws = reinterpret_cast<uint8_t *>(qm) + align16((size_t)M * (size_t)(K / 64) * 4);
+            codes = qc;
+            meta = qm;
+        }
+        if (int rc = launch_decode_cells(codes, meta, M, K, ws, stream)) return rc;
+        g.a = reinterpret_cast<const uint16_t *>(ws);
+        g.lda = K;
     }
     g.w_codes = reinterpret_cast<const uint32_t *>(w_codes);
     g.w_meta = w_meta;
     g.offs = offs;
     g.c = c;
-    g.lda = lda;
     g.ldc = ldc;
     g.M = (int)M;
     g.N = (int)N;
@@ -501,13 +420,13 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         constexpr int BM = 128, BN = 256;
         g.tiles_n = (int)((N + BN - 1) / BN);
         const int m_tiles = (int)(M / BM) + E; // upper bound of sum_e ceil(rows_e / BM)
-        if (a_kind == HIF4_A_BF16_KEEP) return launch_tiles<BM, BN, 2, 4, true, true>(g, out_dtype, m_tiles, stream);
+        if (a_cell) return launch_tiles<BM, BN, 2, 4, true, true>(g, out_dtype, m_tiles, stream);
         return launch_tiles<BM, BN, 2, 4, false, true>(g, out_dtype, m_tiles, stream);
     }
     constexpr int BM = 256, BN = 256;
     g.tiles_n = (int)((N + BN - 1) / BN);
     const int m_tiles = (int)((M + BM - 1) / BM);
-    if (a_kind == HIF4_A_BF16_KEEP) return launch_tiles<BM, BN, 2, 4, true, false>(g, out_dtype, m_tiles, stream);
+    if (a_cell) return launch_tiles<BM, BN, 2, 4, true, false>(g, out_dtype, m_tiles, stream);
     return launch_tiles<BM, BN, 2, 4, false, false>(g, out_dtype, m_tiles, stream);
 }
 

@@ -7,7 +7,7 @@
 // micro-exponent domain, two level-3 domains).  The peak magnitude of the unit and
 // the metadata bits are exchanged across the LPU lanes with DPP moves; nothing goes
 // through LDS.
-#include "hif4_common.h"
+#include "hif4_expand.h"
 
 namespace hif4 {
 
@@ -273,7 +273,9 @@ __device__ __forceinline__ uint4 decode_chunk(uint32_t c, uint32_t m, int j)
 }
 
 // One lane decodes CPT chunks of 8 elements; block b owns chunks [b*256*CPT, (b+1)*256*CPT).
-template <bool CONTIG, int CPT, bool NT>
+// CELL: write each group of 8 in the GEMM's cell order (an internal staging format) instead
+// of element order.
+template <bool CONTIG, int CPT, bool NT, bool CELL = false>
 __global__ __launch_bounds__(256) void decode_kernel(const uint32_t *__restrict__ codes,
                                                      const uint32_t *__restrict__ meta, int64_t chunks, int64_t upr,
                                                      int64_t ldy, uint16_t *__restrict__ y)
@@ -300,7 +302,8 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint32_t *__restrict_
             const int64_t row = unit / upr;
             dst = y + row * ldy + (unit - row * upr) * 64 + j * 8;
         }
-        store16<NT>(dst, decode_chunk(c[t], m[t], j));
+        if (CELL) store16<NT>(dst, expand_chunk(c[t], m[t], unit_scale_bits(m[t]), j));
+        else store16<NT>(dst, decode_chunk(c[t], m[t], j));
     }
 }
 
@@ -360,6 +363,19 @@ int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int6
     uint16_t *ys = static_cast<uint16_t *>(y);
     if (ldy == K) hipLaunchKernelGGL((decode_kernel<true, CPT, NT>), grid, block, 0, stream, cd, meta, chunks, upr, ldy, ys);
     else hipLaunchKernelGGL((decode_kernel<false, CPT, NT>), grid, block, 0, stream, cd, meta, chunks, upr, ldy, ys);
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+// HiF4 -> BF16 copy in cell order, dense rows (row stride K): the activation operand of the
+// tile GEMM.  Regular stores: the GEMM reads the copy right away.
+int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream)
+{
+    const int64_t upr = K / 64, chunks = rows * upr * 8;
+    if (chunks == 0) return HIF4_OK;
+    constexpr int CPT = HIF4_DEC_CPT;
+    const dim3 grid((unsigned)((chunks + 256 * CPT - 1) / (256 * CPT))), block(256);
+    hipLaunchKernelGGL((decode_kernel<true, CPT, false, true>), grid, block, 0, stream,
+                       reinterpret_cast<const uint32_t *>(codes), meta, chunks, upr, K, static_cast<uint16_t *>(y));
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 

@@ -72,7 +72,7 @@ def test_gemm_argument_errors(lib):
     from paper_2602_11287_amd import hif4 as h
     g, gg = lib.hif4_gemm, lib.hif4_grouped_gemm
     p = 0x1000
-    ok = dict(a_kind=h.HIF4_A_HIF4, a=p, a_meta=p, lda=256, w=p, wm=p, M=8, N=16, K=256, c=p, ldc=16, out=1, ws=None, wsz=0)
+    ok = dict(a_kind=h.HIF4_A_HIF4, a=p, a_meta=p, lda=256, w=p, wm=p, M=8, N=16, K=256, c=p, ldc=16, out=1, ws=p, wsz=8 * 256 * 2)
 
     def call(**kw):
         a = dict(ok, **kw)
@@ -89,17 +89,21 @@ def test_gemm_argument_errors(lib):
     assert call(c=None) == h.HIF4_ERR_NULL
     assert call(w=p + 4) == h.HIF4_ERR_ALIGN
     assert call(M=0) == h.HIF4_OK and call(N=0) == h.HIF4_OK
-    # quantise-inside-the-call needs a workspace of the advertised size
+    # HiF4 activations need a workspace of the advertised size: the decoded BF16 copy, and for
+    # quantise-inside-the-call the packed planes before it
     need = lib.hif4_gemm_workspace_bytes(h.HIF4_A_BF16_QUANTIZE, 8, 256)
-    assert need == 8 * 128 + 8 * 4 * 4
-    assert lib.hif4_gemm_workspace_bytes(h.HIF4_A_HIF4, 8, 256) == 0
+    assert need == 8 * 128 + 8 * 4 * 4 + 8 * 256 * 2
+    assert lib.hif4_gemm_workspace_bytes(h.HIF4_A_HIF4, 8, 256) == 8 * 256 * 2
     assert lib.hif4_gemm_workspace_bytes(h.HIF4_A_BF16_KEEP, 8, 256) == 0
-    assert call(a_kind=h.HIF4_A_BF16_QUANTIZE, a_meta=None) == h.HIF4_ERR_WORKSPACE
+    assert call(ws=None, wsz=0) == h.HIF4_ERR_WORKSPACE
+    assert call(wsz=8 * 256 * 2 - 1) == h.HIF4_ERR_WORKSPACE
+    assert call(ws=p + 8) == h.HIF4_ERR_ALIGN
+    assert call(a_kind=h.HIF4_A_BF16_QUANTIZE, a_meta=None, ws=None, wsz=0) == h.HIF4_ERR_WORKSPACE
     assert call(a_kind=h.HIF4_A_BF16_QUANTIZE, a_meta=None, ws=p, wsz=need - 1) == h.HIF4_ERR_WORKSPACE
     # grouped: offsets are required once there is work
-    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, 4, 8, 16, 256, p, 16, 1, None, 0, None) == h.HIF4_ERR_NULL
-    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, -1, 8, 16, 256, p, 16, 1, None, 0, None) == h.HIF4_ERR_SHAPE
-    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, 0, 8, 16, 256, p, 16, 1, None, 0, None) == h.HIF4_OK
+    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, 4, 8, 16, 256, p, 16, 1, p, 4096, None) == h.HIF4_ERR_NULL
+    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, -1, 8, 16, 256, p, 16, 1, p, 4096, None) == h.HIF4_ERR_SHAPE
+    assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, 0, 8, 16, 256, p, 16, 1, p, 4096, None) == h.HIF4_OK
 
 
 def test_product_path_has_no_cpu_fallback():
