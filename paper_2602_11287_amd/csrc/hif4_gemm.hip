@@ -39,7 +39,7 @@ struct GemmArgs {
     int64_t lda; // row stride of a, in elements
     int64_t ldc;
     int M, N, K, E;
-    int tiles_n;
+    int tiles_m, tiles_n;
 };
 
 // A_CELL: the 8 BF16 of every group of 8 in `a` are already stored in cell order (the
@@ -49,9 +49,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 {
     constexpr int NT = 64 * WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32; // MFMA tiles per wave
-    constexpr int CELLS = 8 * (BM + BN);                // 16-byte cells per buffer
+    constexpr int PAD = 4;                              // cells; see the staging role below
+    constexpr int W_BASE = 8 * BM + PAD;                // first cell of the W part of a buffer
+    constexpr int CELLS = 8 * (BM + BN) + 2 * PAD;      // 16-byte cells per buffer
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tiles are multiples of 32");
-    static_assert(2 * BM <= NT && 2 * BN <= NT && NT % (2 * BM) == 0 && NT % (2 * BN) == 0, "two threads per row");
+    static_assert(2 * BM <= NT && 2 * BN <= NT, "two threads per row");
     extern __shared__ uint4 lds[]; // 2 buffers x CELLS
 
     const int tid = threadIdx.x;
@@ -62,8 +64,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     int row0, rows_end; // this tile covers rows [row0, min(row0 + BM, rows_end)) of A and C
     const uint32_t *w_codes = g.w_codes;
     const uint32_t *w_meta = g.w_meta;
-    const int tile_n = blockIdx.x % g.tiles_n;
-    int tile_m = blockIdx.x / g.tiles_n;
+    // Block -> tile.  Workgroups are dealt to the 8 XCDs round-robin (block b runs on XCD b % 8)
+    // and each XCD has its own L2, so every XCD gets one contiguous run of the tile list, and
+    // the list walks the tile grid in super-tiles of GM x GN tiles: the ~32 workgroups an XCD
+    // runs at a time then share A rows 8 ways and W rows 4 ways in its L2.
+    constexpr int GM = 4, GN = 8, XCDS = 8;
+    const int per_xcd = (int)(gridDim.x / XCDS);
+    const int t = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
+    const int sn = (g.tiles_n + GN - 1) / GN;
+    const int st = t / (GM * GN), within = t % (GM * GN);
+    const int tile_n = (st % sn) * GN + within % GN;
+    int tile_m = (st / sn) * GM + within / GN;
+    if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return; // padding of the super-tile grid
     if (GROUPED) {
         // walk the experts until the m-tile index falls inside one (uniform across the block)
         int e = 0, acc = 0, found = 0;
@@ -95,6 +107,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     // codes -> 4 cells) and half a unit of an A row (64 bytes of BF16 -> 4 cells).  With fewer
     // rows than thread pairs the surplus threads repeat rows (same bytes to the same cells),
     // which keeps the loop body free of branches.
+    // Two adjacent lanes share a row (its two 64-byte halves), so the global loads of a wave
+    // cover whole 128-byte lines.  In LDS the cells of groups 4..7 are shifted by PAD cells,
+    // which moves the writes of the odd lanes to other banks than those of the even lanes.
     const int h = tid & 1;
     const int ra = (tid >> 1) % BM, rw = (tid >> 1) % BN;
     int arow = row0 + ra;
@@ -104,8 +119,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     const uint16_t *a_src = g.a + (int64_t)arow * g.lda + 32 * h;
     const uint32_t *wc_src = w_codes + (int64_t)wrow * (g.K / 8) + 4 * h;
     const uint32_t *wm_src = w_meta + (int64_t)wrow * upr;
-    // cell (j, row) of the A part sits at j*BM + row; of the W part at 8*BM + j*BN + row
-    const int a_cell0 = (4 * h) * BM + ra, w_cell0 = 8 * BM + (4 * h) * BN + rw;
+    // cell (j, row) of the A part sits at j*BM + row + PAD*(j/4); the W part follows it
+    const int a_cell0 = (4 * h) * BM + ra + PAD * h, w_cell0 = W_BASE + (4 * h) * BN + rw + PAD * h;
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -144,14 +159,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     // Operand reads of the next quarter are issued early in the current one.
     auto k_step = [&](const uint4 *cur, uint4 *nxt, const Staged &st) {
         const uint4 *abase = cur + wm * (BM / WM) + l32;
-        const uint4 *bbase = cur + 8 * BM + wn * (BN / WN) + l32;
+        const uint4 *bbase = cur + W_BASE + wn * (BN / WN) + l32;
         bf16x8_t af[2][TM], bfr[2][TN];
         auto load_frags = [&](int s) {
             const int j = 2 * s + half;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[s & 1][i] = __builtin_bit_cast(bf16x8_t, abase[j * BM + i * 32]);
+            for (int i = 0; i < TM; ++i) af[s & 1][i] = __builtin_bit_cast(bf16x8_t, abase[j * BM + (s / 2) * PAD + i * 32]);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + i * 32]);
+            for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + (s / 2) * PAD + i * 32]);
         };
         const uint32_t sbase = unit_scale_bits(st.wm);
         load_frags(0);
@@ -336,10 +351,13 @@ int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 
 template <int BM, int BN, int WM, int WN, bool A_CELL, bool GROUPED>
-static int launch_tiles(const GemmArgs &g, int out_dtype, int m_tiles, hipStream_t stream)
+static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stream)
 {
-    constexpr size_t lds_bytes = 2 * 8 * (BM + BN) * sizeof(uint4);
-    const dim3 grid((unsigned)((int64_t)m_tiles * g.tiles_n)), block(64 * WM * WN);
+    g.tiles_m = m_tiles;
+    constexpr size_t lds_bytes = 2 * (8 * (BM + BN) + 8) * sizeof(uint4);
+    // the super-tile grid (4 x 8 tiles), padded, split evenly over the 8 XCDs: see the kernel
+    const int64_t padded = (int64_t)((m_tiles + 3) / 4) * ((g.tiles_n + 7) / 8) * 32;
+    const dim3 grid((unsigned)((padded + 7) / 8 * 8)), block(64 * WM * WN);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
         auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, true, GROUPED>;
