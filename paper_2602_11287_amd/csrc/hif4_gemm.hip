@@ -69,13 +69,24 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     // the list walks the tile grid in super-tiles of GM x GN tiles: the ~32 workgroups an XCD
     // runs at a time then share A rows 8 ways and W rows 4 ways in its L2.
     constexpr int GM = 4, GN = 8, XCDS = 8;
-    const int per_xcd = (int)(gridDim.x / XCDS);
-    const int t = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
-    const int sn = (g.tiles_n + GN - 1) / GN;
-    const int st = t / (GM * GN), within = t % (GM * GN);
-    const int tile_n = (st % sn) * GN + within % GN;
-    int tile_m = (st / sn) * GM + within / GN;
-    if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return; // padding of the super-tile grid
+    int tile_m, tile_n;
+    if (GROUPED) {
+        // The tile list of a grouped GEMM ends in an unknown number of empty m-tiles (the grid
+        // is an upper bound), so m-tiles are dealt to the XCDs round-robin instead, all n-tiles
+        // of an m-tile staying on one XCD (they share its A rows).
+        const int i = (int)(blockIdx.x / XCDS);
+        tile_m = (i / g.tiles_n) * XCDS + (int)(blockIdx.x % XCDS);
+        tile_n = i % g.tiles_n;
+        if (tile_m >= g.tiles_m) return;
+    } else {
+        const int per_xcd = (int)(gridDim.x / XCDS);
+        const int t = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
+        const int sn = (g.tiles_n + GN - 1) / GN;
+        const int st = t / (GM * GN), within = t % (GM * GN);
+        tile_n = (st % sn) * GN + within % GN;
+        tile_m = (st / sn) * GM + within / GN;
+        if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return; // padding of the super-tile grid
+    }
     if (GROUPED) {
         // walk the experts until the m-tile index falls inside one (uniform across the block)
         int e = 0, acc = 0, found = 0;
@@ -148,6 +159,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     auto w_word = [&](const Staged &st, int q) { return q == 0 ? st.wc.x : q == 1 ? st.wc.y : q == 2 ? st.wc.z : st.wc.w; };
 
     const int half = lane / 32, l32 = lane % 32;
+    // a wave whose rows all lie past the edge of the tile only helps with staging
+    const bool wave_has_rows = !GROUPED || row0 + wm * (BM / WM) < rows_end;
     constexpr int NMF = TM * TN; // MFMAs per quarter step
     constexpr int SPM = 8 / NMF; // staging slots after each MFMA
     static_assert(NMF * SPM == 8, "eight staging slots per quarter, spread evenly over its MFMAs");
@@ -169,14 +182,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
             for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + (s / 2) * PAD + i * 32]);
         };
         const uint32_t sbase = unit_scale_bits(st.wm);
-        load_frags(0);
+        if (wave_has_rows) load_frags(0);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             ChunkState cs;
             uint4 cell;
 #pragma unroll
             for (int tm = 0; tm < NMF; ++tm) {
-                acc[tm / TN][tm % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][tm / TN], bfr[s & 1][tm % TN], acc[tm / TN][tm % TN], 0, 0, 0);
+                if (wave_has_rows)
+                    acc[tm / TN][tm % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][tm / TN], bfr[s & 1][tm % TN], acc[tm / TN][tm % TN], 0, 0, 0);
 #pragma unroll
                 for (int sl = 0; sl < SPM; ++sl) {
                     const int slot = tm * SPM + sl;
@@ -194,7 +208,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
                         nxt[a_cell0 + s * BM] = a_cell(st, s);
                     }
                 }
-                if (tm == NMF / 4 && s < 3) load_frags(s + 1);
+                if (tm == NMF / 4 && s < 3 && wave_has_rows) load_frags(s + 1);
 #if HIF4_GEMM_SCHED
                 __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -356,7 +370,8 @@ static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stre
     g.tiles_m = m_tiles;
     constexpr size_t lds_bytes = 2 * (8 * (BM + BN) + 8) * sizeof(uint4);
     // the super-tile grid (4 x 8 tiles), padded, split evenly over the 8 XCDs: see the kernel
-    const int64_t padded = (int64_t)((m_tiles + 3) / 4) * ((g.tiles_n + 7) / 8) * 32;
+    const int64_t padded = GROUPED ? (int64_t)((m_tiles + 7) / 8) * 8 * g.tiles_n
+                                   : (int64_t)((m_tiles + 3) / 4) * ((g.tiles_n + 7) / 8) * 32;
     const dim3 grid((unsigned)((padded + 7) / 8 * 8)), block(64 * WM * WN);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
@@ -435,11 +450,20 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     g.K = (int)K;
     g.E = E;
     if (offs) {
-        constexpr int BM = 128, BN = 256;
+        // Row counts per expert live on the device; the host only knows their mean.  Every W
+        // unit is expanded once per m-tile that uses it, so the tile should cover an expert's
+        // rows in one go: 256 rows unless experts are small on average.  The grid is the upper
+        // bound sum_e ceil(rows_e / BM) <= M / BM + E.
+        constexpr int BN = 256;
         g.tiles_n = (int)((N + BN - 1) / BN);
-        const int m_tiles = (int)(M / BM) + E; // upper bound of sum_e ceil(rows_e / BM)
-        if (a_cell) return launch_tiles<BM, BN, 2, 4, true, true>(g, out_dtype, m_tiles, stream);
-        return launch_tiles<BM, BN, 2, 4, false, true>(g, out_dtype, m_tiles, stream);
+        if (M > (int64_t)E * 96) {
+            const int m_tiles = (int)(M / 256) + E;
+            if (a_cell) return launch_tiles<256, BN, 2, 4, true, true>(g, out_dtype, m_tiles, stream);
+            return launch_tiles<256, BN, 2, 4, false, true>(g, out_dtype, m_tiles, stream);
+        }
+        const int m_tiles = (int)(M / 128) + E;
+        if (a_cell) return launch_tiles<128, BN, 2, 4, true, true>(g, out_dtype, m_tiles, stream);
+        return launch_tiles<128, BN, 2, 4, false, true>(g, out_dtype, m_tiles, stream);
     }
     constexpr int BM = 256, BN = 256;
     g.tiles_n = (int)((N + BN - 1) / BN);
