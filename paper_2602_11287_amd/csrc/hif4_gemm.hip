@@ -293,25 +293,40 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(const uint16_t *__rest
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
 
-    for (int p = wave; p < npairs; p += KS) {
-        const int u = 2 * p + (q >> 1);
-        const bool valid = u < upr;
-        const int uc = valid ? u : upr - 1;
-        uint4 cw = *reinterpret_cast<const uint4 *>(wrow + uc * 8 + (q & 1) * 4);
-        uint32_t meta = mrow[uc];
-        if (!valid) { cw = make_uint4(0, 0, 0, 0); meta = 0; } // an odd unit count: the missing half adds zeros
-        const uint32_t sbase = unit_scale_bits(meta);
-        const uint32_t cwa[4] = { cw.x, cw.y, cw.z, cw.w };
+    // PF pairs of units per trip, every load of the trip issued before the first use: the
+    // kernel lives on memory latency (a wave sees only a few trips).
+    constexpr int PF = MB == 1 ? 4 : MB == 2 ? 2 : 1;
+    for (int p0 = wave; p0 < npairs; p0 += KS * PF) {
+        uint4 cw[PF], av[PF][4][MB];
+        uint32_t meta[PF];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int j = 4 * (q & 1) + t;
-            const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, expand_chunk(cwa[t], meta, sbase, j));
+        for (int i = 0; i < PF; ++i) {
+            const int u = 2 * (p0 + i * KS) + (q >> 1);
+            const bool valid = u < upr; // an odd unit count or a short last trip: the missing part adds zeros
+            const int uc = valid ? u : upr - 1;
+            cw[i] = *reinterpret_cast<const uint4 *>(wrow + uc * 8 + (q & 1) * 4);
+            meta[i] = mrow[uc];
+            if (!valid) { cw[i] = make_uint4(0, 0, 0, 0); meta[i] = 0; }
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const int row = mb * 16 + n_l;
-                uint4 av = make_uint4(0, 0, 0, 0);
-                if (valid && row < M) av = permute_bf16_cell(*reinterpret_cast<const uint4 *>(a + (int64_t)row * lda + (int64_t)uc * 64 + j * 8));
-                acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), bfrag, acc[mb], 0, 0, 0);
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int row = mb * 16 + n_l, j = 4 * (q & 1) + t;
+                    av[i][t][mb] = make_uint4(0, 0, 0, 0);
+                    if (valid && row < M) av[i][t][mb] = *reinterpret_cast<const uint4 *>(a + (int64_t)row * lda + (int64_t)uc * 64 + j * 8);
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < PF; ++i) {
+            const uint32_t sbase = unit_scale_bits(meta[i]);
+            const uint32_t cwa[4] = { cw[i].x, cw[i].y, cw[i].z, cw[i].w };
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int j = 4 * (q & 1) + t;
+                const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, expand_chunk(cwa[t], meta[i], sbase, j));
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, permute_bf16_cell(av[i][t][mb])), bfrag, acc[mb], 0, 0, 0);
             }
         }
     }
