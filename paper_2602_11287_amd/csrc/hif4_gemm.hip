@@ -267,80 +267,113 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 // ------------------------------------------------------------------ skinny weight-only GEMM
 
 // C[M][N] = A[M][K] (BF16) * W[N][K]^T (HiF4) for M <= 16 * MB: bound by streaming W once
-// from HBM.  A workgroup owns 16 output columns; its 8 waves split K by pairs of units and
-// add their partial tiles through LDS.  v_mfma_f32_16x16x32_bf16: lane (n, q) = (lane % 16,
-// lane / 16) supplies 8 consecutive k of weight row n (one dword of codes, expanded in
-// registers, never through LDS) and of activation row n; for the pair of units (2p, 2p+1)
-// lane q loads the 16 code bytes [16 q, 16 q + 16) of the 64-byte pair, so a weight row's
-// bytes are read as one contiguous run.
-template <int MB, bool OUT_F32>
-__global__ __launch_bounds__(512) void gemm_skinny_kernel(const uint16_t *__restrict__ a, int64_t lda,
-                                                          const uint32_t *__restrict__ w_codes,
-                                                          const uint32_t *__restrict__ w_meta, void *c, int64_t ldc,
-                                                          int M, int N, int K)
+// from HBM.  A workgroup owns 16 output columns; its waves split K into contiguous ranges and
+// add their partial tiles through LDS at the end.  v_mfma_f32_16x16x32_bf16: lane (n, q) =
+// (lane % 16, lane / 16) supplies 8 consecutive k of weight row n (one dword of codes,
+// expanded in registers) and of activation row n.
+// K advances by pairs of units (128 values).  For a pair, lane (n, q) loads the 16 code
+// bytes [16 q, 16 q + 16) of row n's 64 bytes, so a weight row is read as one contiguous run;
+// MFMA t (0..3) of the pair then takes group 4 q + t of the pair's 16 groups of 8.  The
+// activations of the pair (16 MB rows x 256 bytes) are loaded with fully coalesced 16-byte
+// loads (16 lanes per row), written to a wave-private LDS slab [group][row] in cell order and
+// read back in the MFMA operand layout; no workgroup barrier is involved.  NBUF pairs are in
+// flight per wave (registers and slabs), because the kernel lives on memory latency.
+template <int MB, int WAVES, bool OUT_F32>
+__global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const uint16_t *__restrict__ a, int64_t lda,
+                                                                 const uint32_t *__restrict__ w_codes,
+                                                                 const uint32_t *__restrict__ w_meta, void *c,
+                                                                 int64_t ldc, int M, int N, int K)
 {
-    constexpr int KS = 8;
-    __shared__ float red[KS][MB][256];
+    constexpr int NBUF = MB == 1 ? 4 : 2;
+    constexpr int ROWS = 16 * MB, RSTRIDE = ROWS + 1; // +1 cell: the 16 lanes of a row write 16 different banks
+    constexpr int SLAB = 16 * RSTRIDE;                // cells per pair
+    constexpr int NLD = ROWS / 4;                     // activation loads per lane and pair
+    extern __shared__ uint4 lds[];
+    float *red = reinterpret_cast<float *>(lds + WAVES * NBUF * SLAB); // [WAVES][MB][256]
+
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
     const int n_l = lane % 16, q = lane / 16;
     const int col = blockIdx.x * 16 + n_l;
     const int colc = col < N ? col : N - 1;
     const int upr = K / 64, npairs = (upr + 1) / 2;
+    const int ppw = (npairs + WAVES - 1) / WAVES;
+    const int p_begin = wave * ppw, p_end = p_begin + ppw < npairs ? p_begin + ppw : npairs;
     const uint32_t *wrow = w_codes + (int64_t)colc * (K / 8);
     const uint32_t *mrow = w_meta + (int64_t)colc * upr;
+    uint4 *slab = lds + wave * NBUF * SLAB;
+
+    struct InFlight {
+        uint4 wc;
+        uint32_t m;
+        uint4 a[NLD];
+    };
+    // loads of pair p; anything past the end of K (a short last pair, a pair past the range) is zero
+    auto issue = [&](InFlight &f, int p) {
+        const int u = 2 * p + (q >> 1);
+        const bool wvalid = p < p_end && u < upr;
+        const int uc = u < upr ? u : upr - 1;
+        f.wc = make_uint4(0, 0, 0, 0);
+        f.m = 0;
+        if (wvalid) {
+            f.wc = *reinterpret_cast<const uint4 *>(wrow + uc * 8 + (q & 1) * 4);
+            f.m = mrow[uc];
+        }
+        const int ua = 2 * p + (n_l >> 3); // unit of this lane's 16-byte piece of an activation row
+#pragma unroll
+        for (int r = 0; r < NLD; ++r) {
+            const int row = 4 * r + q;
+            f.a[r] = make_uint4(0, 0, 0, 0);
+            if (p < p_end && ua < upr && row < M)
+                f.a[r] = *reinterpret_cast<const uint4 *>(a + (int64_t)row * lda + (int64_t)p * 128 + n_l * 8);
+        }
+    };
 
     f32x4_t acc[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
 
-    // PF pairs of units per trip, every load of the trip issued before the first use: the
-    // kernel lives on memory latency (a wave sees only a few trips).
-    constexpr int PF = MB == 1 ? 4 : MB == 2 ? 2 : 1;
-    for (int p0 = wave; p0 < npairs; p0 += KS * PF) {
-        uint4 cw[PF], av[PF][4][MB];
-        uint32_t meta[PF];
+    InFlight fl[NBUF];
 #pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            const int u = 2 * (p0 + i * KS) + (q >> 1);
-            const bool valid = u < upr; // an odd unit count or a short last trip: the missing part adds zeros
-            const int uc = valid ? u : upr - 1;
-            cw[i] = *reinterpret_cast<const uint4 *>(wrow + uc * 8 + (q & 1) * 4);
-            meta[i] = mrow[uc];
-            if (!valid) { cw[i] = make_uint4(0, 0, 0, 0); meta[i] = 0; }
+    for (int i = 0; i < NBUF; ++i) issue(fl[i], p_begin + i);
+
+    for (int p = p_begin; p < p_end; p += NBUF) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+        for (int i = 0; i < NBUF; ++i) {
+            if (p + i < p_end) { // wave-uniform
+                uint4 *sl = slab + i * SLAB;
+                // lane (piece n_l, row 4r + q) -> cell [n_l][row]
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const int row = mb * 16 + n_l, j = 4 * (q & 1) + t;
-                    av[i][t][mb] = make_uint4(0, 0, 0, 0);
-                    if (valid && row < M) av[i][t][mb] = *reinterpret_cast<const uint4 *>(a + (int64_t)row * lda + (int64_t)uc * 64 + j * 8);
+                for (int r = 0; r < NLD; ++r) sl[n_l * RSTRIDE + 4 * r + q] = permute_bf16_cell(fl[i].a[r]);
+                const uint4 wc = fl[i].wc;
+                const uint32_t m = fl[i].m;
+                issue(fl[i], p + i + NBUF);
+                __builtin_amdgcn_wave_barrier(); // the reads below see the whole wave's writes (LDS is in order)
+                const uint32_t sbase = unit_scale_bits(m);
+                const uint32_t cwa[4] = { wc.x, wc.y, wc.z, wc.w };
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, expand_chunk(cwa[t], m, sbase, 4 * (q & 1) + t));
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const uint4 av = sl[(4 * q + t) * RSTRIDE + mb * 16 + n_l];
+                        acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av), bfrag, acc[mb], 0, 0, 0);
+                    }
                 }
-        }
-#pragma unroll
-        for (int i = 0; i < PF; ++i) {
-            const uint32_t sbase = unit_scale_bits(meta[i]);
-            const uint32_t cwa[4] = { cw[i].x, cw[i].y, cw[i].z, cw[i].w };
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int j = 4 * (q & 1) + t;
-                const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, expand_chunk(cwa[t], meta[i], sbase, j));
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, permute_bf16_cell(av[i][t][mb])), bfrag, acc[mb], 0, 0, 0);
+                __builtin_amdgcn_wave_barrier();
             }
         }
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) red[wave][mb][r * 64 + lane] = acc[mb][r];
+        for (int r = 0; r < 4; ++r) red[(wave * MB + mb) * 256 + r * 64 + lane] = acc[mb][r];
     __syncthreads();
     // thread -> (mb, r, lane): output row mb*16 + 4*(lane/16) + r, column lane%16
-    for (int idx = tid; idx < MB * 256; idx += 512) {
+    for (int idx = tid; idx < MB * 256; idx += 64 * WAVES) {
         const int mb = idx / 256, rem = idx % 256, r = rem / 64, ln = rem % 64;
         float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < KS; ++w) v += red[w][mb][rem];
+        for (int w = 0; w < WAVES; ++w) v += red[(w * MB + mb) * 256 + rem];
         const int row = mb * 16 + 4 * (ln / 16) + r, cc = blockIdx.x * 16 + (ln % 16);
         if (row < M && cc < N) {
             if (OUT_F32) static_cast<float *>(c)[(int64_t)row * ldc + cc] = v;
@@ -353,13 +386,24 @@ template <int MB>
 static int launch_skinny(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N,
                          int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream)
 {
-    const dim3 grid((unsigned)((N + 15) / 16)), block(512);
+    constexpr int WAVES = MB == 4 ? 4 : 8, NBUF = MB == 1 ? 4 : 2;
+    constexpr size_t lds_bytes = (size_t)WAVES * NBUF * 16 * (16 * MB + 1) * sizeof(uint4) + (size_t)WAVES * MB * 256 * sizeof(float);
+    static_assert(lds_bytes <= 160 * 1024, "fits the LDS of one CU");
+    const dim3 grid((unsigned)((N + 15) / 16)), block(64 * WAVES);
     const uint16_t *ap = static_cast<const uint16_t *>(a);
     const uint32_t *wc = reinterpret_cast<const uint32_t *>(w_codes);
-    if (out_dtype == HIF4_OUT_F32)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MB, true>), grid, block, 0, stream, ap, lda, wc, w_meta, c, ldc, (int)M, (int)N, (int)K);
-    else
-        hipLaunchKernelGGL((gemm_skinny_kernel<MB, false>), grid, block, 0, stream, ap, lda, wc, w_meta, c, ldc, (int)M, (int)N, (int)K);
+    hipError_t e;
+    if (out_dtype == HIF4_OUT_F32) {
+        auto k = gemm_skinny_kernel<MB, WAVES, true>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return HIF4_ERR_DEVICE;
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, ap, lda, wc, w_meta, c, ldc, (int)M, (int)N, (int)K);
+    } else {
+        auto k = gemm_skinny_kernel<MB, WAVES, false>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return HIF4_ERR_DEVICE;
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, ap, lda, wc, w_meta, c, ldc, (int)M, (int)N, (int)K);
+    }
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 
