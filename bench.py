@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense BF16 MFMA, published
 BYTES_PER_UNIT = 164          # 128 B of BF16 + 36 B of packed unit, either direction
+# HBM bytes per launch on the default workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a
+# plain 512 MiB device copy (FETCH_SIZE x 1.99988, WRITE_SIZE x 1.0): profiles/encode_decode_kernels_c1x64.md
+MEASURED_TRAFFIC_BYTES = {"hif4::encode_kernel": 671758 * 1024, "hif4::decode_kernel": 671880 * 1024}
 
 
 def main():
@@ -132,7 +135,8 @@ def main():
             "sqnr_db_first_copy": round(float(sqnr_db), 2),
         },
         "roofline": {"bound": "hbm", "kernel": dom[0], "achieved": round(dom[2], 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(dom[2] / HBM_PEAK_GBPS, 4), "traffic": None},
+                     "unit": "GB/s", "frac": round(dom[2] / HBM_PEAK_GBPS, 4),
+                     "algorithmic_bytes": bytes_dir, "traffic": MEASURED_TRAFFIC_BYTES[dom[0]]},
     }
 
     if not args.no_gemm:
@@ -154,6 +158,19 @@ def main():
             spent += time.perf_counter() - t
             reps += 1
         cpu_gbps = reps * 2 * (rows1 * K // 64) * BYTES_PER_UNIT / spent / 1e9
+        # quantisation error of the three 4-bit block formats on the same matrix (CPU, oracle side), and
+        # the GPU's encode+decode of that matrix against the oracle's
+        from oracle import bfp4_comparators as cmp
+        xf = oracle.bf16_bits_to_f64(xb)
+        deq = oracle.bf16_bits_to_f64(oracle.dequantize(wc, wm))
+        out["sqnr_db"] = {"data": "1024x4096 N(0,1), 0.1% entries x64",
+                          "hif4": round(cmp.sqnr_db(xf, deq), 2),
+                          "nvfp4": round(cmp.sqnr_db(xf, cmp.nvfp4_fake_quant(xf)), 2),
+                          "nvfp4_pts": round(cmp.sqnr_db(xf, cmp.nvfp4_fake_quant(xf, pts=True)), 2),
+                          "mxfp4": round(cmp.sqnr_db(xf, cmp.mxfp4_fake_quant(xf)), 2)}
+        out["gpu_matches_oracle_first_copy"] = bool(
+            (codes[:rows1].cpu().numpy() == wc).all() and (meta[:rows1].cpu().numpy().view(np.uint32) == wm).all()
+            and (synth.bits(y[:rows1].cpu()) == oracle.dequantize(wc, wm)).all())
         out["cpu_baseline"] = {"value": round(cpu_gbps, 4), "unit": "GB/s", "cores": oracle.num_threads(),
                                "kind": "oracle",
                                "sample": f"{reps} x encode+decode of one 1024x4096 matrix (65536 units), OpenMP over rows"}

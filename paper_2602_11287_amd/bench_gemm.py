@@ -51,7 +51,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     nbytes = N * K // 64 * 36 + M * K * 2 + M * N * 2
     legs["gemm_weight_only_M16_N4096_K4096"] = {
         "us": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1), "GFLOP": round(2 * M * N * K / 1e9, 3),
-        "roofline": {"bound": "hbm", "kernel": "hif4::gemm_skinny_kernel", "achieved": round(nbytes / ms / 1e6, 1),
+        "roofline": {"bound": "hbm", "kernel": "hif4::gemm_skinny_kernel<1,8>", "achieved": round(nbytes / ms / 1e6, 1),
                      "peak": hbm_peak_gbps, "unit": "GB/s", "frac": round(nbytes / ms / 1e6 / hbm_peak_gbps, 4),
                      "traffic": None}}
     del w, wc, wm
@@ -96,7 +96,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
     mfma_leg("grouped_gemm_w4a4_E64_rows8192_N2048_K7168", M, N, K,
              lambda: hif4.hif4_grouped_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, od, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-             "hif4::gemm_kernel<128,256,grouped>")
+             "hif4::gemm_kernel<256,256,grouped>")
     nbytes = E * N * K // 64 * 36 + M * K * 2 + M * N * 2
     legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["GBps_algorithmic"] = round(
         nbytes / legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["ms"] / 1e6, 1)
