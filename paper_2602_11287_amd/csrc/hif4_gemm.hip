@@ -183,9 +183,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
         };
         const uint32_t sbase = unit_scale_bits(st.wm);
         if (wave_has_rows) load_frags(0);
+        // the first piece of VALU work runs while the first operands arrive from LDS
+        ChunkState cs = chunk_begin(w_word(st, 0), st.wm, sbase, 4 * h);
+#if HIF4_GEMM_SCHED
+        __builtin_amdgcn_sched_barrier(0);
+#endif
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            ChunkState cs;
             uint4 cell;
 #pragma unroll
             for (int tm = 0; tm < NMF; ++tm) {
@@ -195,10 +199,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
                 for (int sl = 0; sl < SPM; ++sl) {
                     const int slot = tm * SPM + sl;
                     if (slot == 0) {
-                        cs = chunk_begin(w_word(st, s), st.wm, sbase, 4 * h + s);
                         cell.x = chunk_pair<0>(cs);
                     } else if (slot == 1) {
                         cell.y = chunk_pair<1>(cs);
+                        if (s < 3 && wave_has_rows) load_frags(s + 1);
                     } else if (slot == 2) {
                         cell.z = chunk_pair<2>(cs);
                     } else if (slot == 3) {
@@ -206,9 +210,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
                         nxt[w_cell0 + s * BN] = cell;
                     } else if (slot == 4) {
                         nxt[a_cell0 + s * BM] = a_cell(st, s);
+                    } else if (slot == 5) {
+                        if (s < 3) cs = chunk_begin(w_word(st, s + 1), st.wm, sbase, 4 * h + s + 1);
                     }
                 }
-                if (tm == NMF / 4 && s < 3 && wave_has_rows) load_frags(s + 1);
 #if HIF4_GEMM_SCHED
                 __builtin_amdgcn_sched_barrier(0);
 #endif
