@@ -9,8 +9,9 @@ int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int6
                   hipStream_t stream);
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
-                int64_t ldc, int out_dtype, void *workspace, hipStream_t stream);
+                int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream);
 size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
+size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 } // namespace hif4
 
 namespace {
@@ -84,6 +85,12 @@ size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K)
     return hif4::gemm_workspace_bytes(a_kind, M_or_total_rows, K);
 }
 
+size_t hif4_gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
+{
+    if (K % HIF4_UNIT != 0) return 0;
+    return hif4::gemm_workspace_bytes_decoded_w(a_kind, M, N, K);
+}
+
 int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
               const uint32_t *w_meta, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype,
               void *workspace, size_t workspace_bytes, void *stream)
@@ -92,7 +99,7 @@ int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, co
         return rc;
     if (M == 0 || N == 0) return HIF4_OK;
     return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, nullptr, 1, M, N, K, c, ldc, out_dtype, workspace,
-                             static_cast<hipStream_t>(stream));
+                             workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
@@ -106,7 +113,7 @@ int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t
     if (!offs) return HIF4_ERR_NULL;
     if (!aligned(offs, 4)) return HIF4_ERR_ALIGN;
     return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, offs, E, total_rows, N, K, c, ldc, out_dtype,
-                             workspace, static_cast<hipStream_t>(stream));
+                             workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 const char *hif4_status_string(int status)

@@ -34,6 +34,7 @@ struct GemmArgs {
     const uint16_t *a;       // BF16 activations [M][lda]: plain rows, or rows already in cell order
     const uint32_t *w_codes; // [E][N][K/8] dwords
     const uint32_t *w_meta;  // [E][N][K/64]
+    const uint16_t *w_cells; // W_CELL kernels: BF16 values of W [N][K], groups of 8 in cell order
     const int32_t *offs;     // grouped: device int32[E+1]; else nullptr
     void *c;
     int64_t lda; // row stride of a, in elements
@@ -44,7 +45,9 @@ struct GemmArgs {
 
 // A_CELL: the 8 BF16 of every group of 8 in `a` are already stored in cell order (the
 // library's own decoded copy of a HiF4 operand); otherwise they are permuted on the way in.
-template <int BM, int BN, int WM, int WN, bool A_CELL, bool OUT_F32, bool GROUPED>
+// W_CELL: W comes as such a decoded copy too (made once per call when M is large, because the
+// in-loop expansion is repeated by every m-tile), and the main loop is a plain BF16 GEMM.
+template <int BM, int BN, int WM, int WN, bool A_CELL, bool OUT_F32, bool GROUPED, bool W_CELL = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 {
     constexpr int NT = 64 * WM * WN;
@@ -130,6 +133,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     const uint16_t *a_src = g.a + (int64_t)arow * g.lda + 32 * h;
     const uint32_t *wc_src = w_codes + (int64_t)wrow * (g.K / 8) + 4 * h;
     const uint32_t *wm_src = w_meta + (int64_t)wrow * upr;
+    const uint16_t *wb_src = W_CELL ? g.w_cells + (int64_t)wrow * g.K + 32 * h : nullptr;
     // cell (j, row) of the A part sits at j*BM + row + PAD*(j/4); the W part follows it
     const int a_cell0 = (4 * h) * BM + ra + PAD * h, w_cell0 = W_BASE + (4 * h) * BN + rw + PAD * h;
 
@@ -146,11 +150,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
         uint4 wc;
         uint32_t wm;
         uint4 a[4];
+        uint4 w[W_CELL ? 4 : 1];
     };
     auto fetch = [&](Staged &st, int ks) {
         ks = ks < nk ? ks : nk - 1; // past the end: reload the last step, never used
-        st.wc = *reinterpret_cast<const uint4 *>(wc_src + ks * 8);
-        st.wm = wm_src[ks];
+        if (W_CELL) {
+            const uint4 *q = reinterpret_cast<const uint4 *>(wb_src + (int64_t)ks * 64);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) st.w[j] = q[j];
+        } else {
+            st.wc = *reinterpret_cast<const uint4 *>(wc_src + ks * 8);
+            st.wm = wm_src[ks];
+        }
         const uint4 *p = reinterpret_cast<const uint4 *>(a_src + (int64_t)ks * 64);
 #pragma unroll
         for (int j = 0; j < 4; ++j) st.a[j] = p[j];
@@ -166,35 +177,67 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     static_assert(NMF * SPM == 8, "eight staging slots per quarter, spread evenly over its MFMAs");
 
     // One K step: matrix work on `cur`, staging of the following step from `st` into `nxt`.
-    // A step has four quarters (one MFMA K-slab of 16 each).  In quarter q the thread expands
-    // its W dword q (begin + 4 BF16 pairs) and copies its A cell q: one slot of that work
-    // after each MFMA, fenced, so that the VALU work runs while the matrix pipeline is busy.
-    // Operand reads of the next quarter are issued early in the current one.
+    // A step has four phases.  Phase p requests the MFMA operands of quarter p (a K-slab of 16)
+    // from LDS and meanwhile runs the MFMAs of quarter p-1, whose operands arrived during the
+    // phase before; for p = 0 that is the last quarter of the previous step, still in registers.
+    // So the barrier between two steps falls between the operand reads of a quarter and its
+    // MFMAs: right after it every wave has a quarter of matrix work to issue while the first
+    // operands of the new buffer are on their way (the operand registers start out as zeros, so
+    // the first step's phase 0 adds nothing; the last quarter is worked off after the loop).
+    // In phase p the thread also expands its W dword p (begin + 4 BF16 pairs) and copies its A
+    // cell p: one slot of that work after each MFMA, fenced, so that the VALU work runs while
+    // the matrix pipeline is busy.
+    bf16x8_t af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[1][i] = bf16x8_t{ 0, 0, 0, 0, 0, 0, 0, 0 };
+#pragma unroll
+    for (int i = 0; i < TN; ++i) bfr[1][i] = bf16x8_t{ 0, 0, 0, 0, 0, 0, 0, 0 };
+    auto mfma = [&](int fb, int tm) {
+        if (wave_has_rows)
+            acc[tm / TN][tm % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fb][tm / TN], bfr[fb][tm % TN], acc[tm / TN][tm % TN], 0, 0, 0);
+    };
+    auto fence = [] {
+#if HIF4_GEMM_SCHED
+        __builtin_amdgcn_sched_barrier(0);
+#endif
+    };
     auto k_step = [&](const uint4 *cur, uint4 *nxt, const Staged &st) {
         const uint4 *abase = cur + wm * (BM / WM) + l32;
         const uint4 *bbase = cur + W_BASE + wn * (BN / WN) + l32;
-        bf16x8_t af[2][TM], bfr[2][TN];
         auto load_frags = [&](int s) {
+            if (!wave_has_rows) return;
             const int j = 2 * s + half;
 #pragma unroll
             for (int i = 0; i < TM; ++i) af[s & 1][i] = __builtin_bit_cast(bf16x8_t, abase[j * BM + (s / 2) * PAD + i * 32]);
 #pragma unroll
             for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + (s / 2) * PAD + i * 32]);
         };
+        if (W_CELL) {
+            // both operands are ready-made cells: a phase copies one cell of each
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                load_frags(s);
+                fence();
+#pragma unroll
+                for (int tm = 0; tm < NMF; ++tm) {
+                    mfma((s + 1) & 1, tm);
+                    if (tm == NMF / 4) nxt[w_cell0 + s * BN] = st.w[s];
+                    else if (tm == NMF / 2) nxt[a_cell0 + s * BM] = a_cell(st, s);
+                    fence();
+                }
+            }
+            return;
+        }
         const uint32_t sbase = unit_scale_bits(st.wm);
-        if (wave_has_rows) load_frags(0);
-        // the first piece of VALU work runs while the first operands arrive from LDS
         ChunkState cs = chunk_begin(w_word(st, 0), st.wm, sbase, 4 * h);
-#if HIF4_GEMM_SCHED
-        __builtin_amdgcn_sched_barrier(0);
-#endif
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             uint4 cell;
+            load_frags(s);
+            fence();
 #pragma unroll
             for (int tm = 0; tm < NMF; ++tm) {
-                if (wave_has_rows)
-                    acc[tm / TN][tm % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][tm / TN], bfr[s & 1][tm % TN], acc[tm / TN][tm % TN], 0, 0, 0);
+                mfma((s + 1) & 1, tm);
 #pragma unroll
                 for (int sl = 0; sl < SPM; ++sl) {
                     const int slot = tm * SPM + sl;
@@ -202,7 +245,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
                         cell.x = chunk_pair<0>(cs);
                     } else if (slot == 1) {
                         cell.y = chunk_pair<1>(cs);
-                        if (s < 3 && wave_has_rows) load_frags(s + 1);
                     } else if (slot == 2) {
                         cell.z = chunk_pair<2>(cs);
                     } else if (slot == 3) {
@@ -214,9 +256,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
                         if (s < 3) cs = chunk_begin(w_word(st, s + 1), st.wm, sbase, 4 * h + s + 1);
                     }
                 }
-#if HIF4_GEMM_SCHED
-                __builtin_amdgcn_sched_barrier(0);
-#endif
+                fence();
             }
         }
     };
@@ -226,10 +266,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     fetch(set0, 0);
     fetch(set1, 1);
     {
-        const uint32_t sbase = unit_scale_bits(set0.wm);
+        const uint32_t sbase = W_CELL ? 0u : unit_scale_bits(set0.wm);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            buf0[w_cell0 + q * BN] = expand_chunk(w_word(set0, q), set0.wm, sbase, 4 * h + q);
+            buf0[w_cell0 + q * BN] = W_CELL ? set0.w[q] : expand_chunk(w_word(set0, q), set0.wm, sbase, 4 * h + q);
             buf0[a_cell0 + q * BM] = a_cell(set0, q);
         }
     }
@@ -246,6 +286,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
             __syncthreads();
         }
     }
+#pragma unroll
+    for (int tm = 0; tm < NMF; ++tm) mfma(1, tm); // quarter 3 of the last step
 
     // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*half + r%4
 #pragma unroll
@@ -428,7 +470,7 @@ int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *
                   hipStream_t stream);
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 
-template <int BM, int BN, int WM, int WN, bool A_CELL, bool GROUPED>
+template <int BM, int BN, int WM, int WN, bool A_CELL, bool GROUPED, bool W_CELL = false>
 static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stream)
 {
     g.tiles_m = m_tiles;
@@ -439,12 +481,12 @@ static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stre
     const dim3 grid((unsigned)((padded + 7) / 8 * 8)), block(64 * WM * WN);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, true, GROUPED>;
+        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, true, GROUPED, W_CELL>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     } else {
-        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, false, GROUPED>;
+        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, false, GROUPED, W_CELL>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
@@ -465,9 +507,23 @@ size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
     return 0;
 }
 
+// From this many rows of A on, a dense GEMM decodes W once into the workspace (if the caller
+// gave room for it) instead of expanding it inside the main loop.  The in-loop expansion of a W
+// unit is repeated by each of the M / 256 m-tiles and slows the loop by about 40 %; the
+// pre-pass moves 2.56 bytes per weight once, which is below 30 % of the GEMM's time from 1024
+// rows on and below 10 % from 4096.
+constexpr int64_t DECODED_W_MIN_ROWS = 1024;
+
+size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
+{
+    const size_t base = gemm_workspace_bytes(a_kind, M, K);
+    if (M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
+    return align16(base) + (size_t)N * (size_t)K * 2;
+}
+
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
-                int64_t ldc, int out_dtype, void *workspace, hipStream_t stream)
+                int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
     if (K == 0) { // empty sum: C = 0 (a fill kernel, so that the call can be captured in a graph)
         const dim3 grid((unsigned)((N + 255) / 256), (unsigned)(M < 65535 ? M : 65535)), block(256);
@@ -506,6 +562,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     }
     g.w_codes = reinterpret_cast<const uint32_t *>(w_codes);
     g.w_meta = w_meta;
+    g.w_cells = nullptr;
     g.offs = offs;
     g.c = c;
     g.ldc = ldc;
@@ -532,6 +589,14 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     constexpr int BM = 256, BN = 256;
     g.tiles_n = (int)((N + BN - 1) / BN);
     const int m_tiles = (int)((M + BM - 1) / BM);
+    const size_t base = align16(gemm_workspace_bytes(a_kind, M, K));
+    if (M >= DECODED_W_MIN_ROWS && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 && workspace_bytes >= base + (size_t)N * (size_t)K * 2) {
+        uint8_t *wcells = static_cast<uint8_t *>(workspace) + base;
+        if (int rc = launch_decode_cells(w_codes, w_meta, N, K, wcells, stream)) return rc;
+        g.w_cells = reinterpret_cast<const uint16_t *>(wcells);
+        if (a_cell) return launch_tiles<BM, BN, 2, 4, true, false, true>(g, out_dtype, m_tiles, stream);
+        return launch_tiles<BM, BN, 2, 4, false, false, true>(g, out_dtype, m_tiles, stream);
+    }
     if (a_cell) return launch_tiles<BM, BN, 2, 4, true, false>(g, out_dtype, m_tiles, stream);
     return launch_tiles<BM, BN, 2, 4, false, false>(g, out_dtype, m_tiles, stream);
 }

@@ -20,7 +20,7 @@ HIF4_A_BF16_QUANTIZE, HIF4_A_HIF4, HIF4_A_BF16_KEEP = 0, 1, 2
 HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 
 EXPORTS = ["hif4_quantize", "hif4_dequantize", "hif4_gemm", "hif4_grouped_gemm",
-           "hif4_gemm_workspace_bytes", "hif4_status_string", "hif4_version"]
+           "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version"]
 
 
 class Hif4Error(RuntimeError):
@@ -50,6 +50,8 @@ def load():
         L.hif4_grouped_gemm.argtypes = [i32, vp, vp, i64, vp, vp, vp, i32, i64, i64, i64, vp, i64, i32, vp, sz, vp]
         L.hif4_gemm_workspace_bytes.restype = sz
         L.hif4_gemm_workspace_bytes.argtypes = [i32, i64, i64]
+        L.hif4_gemm_workspace_bytes_decoded_w.restype = sz
+        L.hif4_gemm_workspace_bytes_decoded_w.argtypes = [i32, i64, i64, i64]
         L.hif4_status_string.restype = C.c_char_p
         L.hif4_status_string.argtypes = [i32]
         L.hif4_version.restype = i32
@@ -83,6 +85,10 @@ def hif4_status_string(status):
 
 def hif4_gemm_workspace_bytes(a_kind, rows, K):
     return int(load().hif4_gemm_workspace_bytes(int(a_kind), int(rows), int(K)))
+
+
+def hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K):
+    return int(load().hif4_gemm_workspace_bytes_decoded_w(int(a_kind), int(M), int(N), int(K)))
 
 
 def hif4_quantize(x, codes=None, meta=None, round_mode=HIF4_ROUND_RNE, stream=None):
@@ -128,7 +134,7 @@ def hif4_gemm(a_kind, a, a_meta, w_codes, w_meta, out_dtype=HIF4_OUT_BF16, c=Non
     lda = _gemm_common(a_kind, a, a_meta, w_codes, M, K)
     if c is None:
         c = torch.empty((M, N), dtype=torch.bfloat16 if out_dtype == HIF4_OUT_BF16 else torch.float32, device=a.device)
-    need = hif4_gemm_workspace_bytes(a_kind, M, K)
+    need = hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
     wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()

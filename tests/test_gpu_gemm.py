@@ -266,3 +266,39 @@ def test_grouped_gemm_moe_config_sampled(h, oracle):
         errs += np.sum((got - want) ** 2)
         refs += np.sum(want ** 2)
     assert np.sqrt(errs / refs) <= TOL
+
+
+@pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
+def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
+    """From 1024 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes the call
+    decode W once instead of inside the main loop: same products in the same order, so the same bits
+    as with the small workspace, and both within tolerance of the oracle."""
+    M, N, K = 1100, 300, 320
+    print(f"gemm decoded-W path kind={kind} M={M} N={N} K={K}", flush=True)
+    ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 977)
+    wcd, wmd = dev_packed(wc, wm)
+    a_bf16 = synth.from_bits(ab).cuda()
+    if kind == "keep":
+        a_kind, a_dev, am_dev = h.HIF4_A_BF16_KEEP, a_bf16, None
+        want = oracle.gemm_f64(ab, oracle.dequantize(wc, wm))
+    else:
+        want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc, wm))
+        if kind == "hif4":
+            a_kind = h.HIF4_A_HIF4
+            a_dev, am_dev = dev_packed(ac, am)
+        else:
+            a_kind, a_dev, am_dev = h.HIF4_A_BF16_QUANTIZE, a_bf16, None
+    small = h.hif4_gemm_workspace_bytes(a_kind, M, K)
+    big = h.hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
+    assert big >= small + N * K * 2
+    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 1023, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 1023, K)
+    ws_small = torch.empty(max(small, 16), dtype=torch.uint8, device="cuda")
+    ws_big = torch.empty(big, dtype=torch.uint8, device="cuda")
+    c_small = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, workspace=ws_small)
+    c_big = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, workspace=ws_big)
+    c_default = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    got = c_big.cpu().numpy().astype(np.float64)
+    assert rel_fro(got, want) <= TOL, rel_fro(got, want)
+    assert rel_fro(c_small.cpu().numpy().astype(np.float64), want) <= TOL
+    assert torch.equal(c_small, c_big) and torch.equal(c_default, c_big)
