@@ -34,7 +34,6 @@ struct GemmArgs {
     const uint16_t *a;       // BF16 activations [M][lda]: plain rows, or rows already in cell order
     const uint32_t *w_codes; // [E][N][K/8] dwords
     const uint32_t *w_meta;  // [E][N][K/64]
-    const uint16_t *w_cells; // W_CELL kernels: BF16 values of W [N][K], groups of 8 in cell order
     const int32_t *offs;     // grouped: device int32[E+1]; else nullptr
     void *c;
     int64_t lda; // row stride of a, in elements
@@ -45,9 +44,7 @@ struct GemmArgs {
 
 // A_CELL: the 8 BF16 of every group of 8 in `a` are already stored in cell order (the
 // library's own decoded copy of a HiF4 operand); otherwise they are permuted on the way in.
-// W_CELL: W comes as such a decoded copy too (made once per call when M is large, because the
-// in-loop expansion is repeated by every m-tile), and the main loop is a plain BF16 GEMM.
-template <int BM, int BN, int WM, int WN, bool A_CELL, bool OUT_F32, bool GROUPED, bool W_CELL = false>
+template <int BM, int BN, int WM, int WN, bool A_CELL, bool OUT_F32, bool GROUPED>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 {
     constexpr int NT = 64 * WM * WN;
@@ -133,7 +130,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     const uint16_t *a_src = g.a + (int64_t)arow * g.lda + 32 * h;
     const uint32_t *wc_src = w_codes + (int64_t)wrow * (g.K / 8) + 4 * h;
     const uint32_t *wm_src = w_meta + (int64_t)wrow * upr;
-    const uint16_t *wb_src = W_CELL ? g.w_cells + (int64_t)wrow * g.K + 32 * h : nullptr;
     // cell (j, row) of the A part sits at j*BM + row + PAD*(j/4); the W part follows it
     const int a_cell0 = (4 * h) * BM + ra + PAD * h, w_cell0 = W_BASE + (4 * h) * BN + rw + PAD * h;
 
@@ -150,18 +146,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
         uint4 wc;
         uint32_t wm;
         uint4 a[4];
-        uint4 w[W_CELL ? 4 : 1];
     };
     auto fetch = [&](Staged &st, int ks) {
         ks = ks < nk ? ks : nk - 1; // past the end: reload the last step, never used
-        if (W_CELL) {
-            const uint4 *q = reinterpret_cast<const uint4 *>(wb_src + (int64_t)ks * 64);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) st.w[j] = q[j];
-        } else {
-            st.wc = *reinterpret_cast<const uint4 *>(wc_src + ks * 8);
-            st.wm = wm_src[ks];
-        }
+        st.wc = *reinterpret_cast<const uint4 *>(wc_src + ks * 8);
+        st.wm = wm_src[ks];
         const uint4 *p = reinterpret_cast<const uint4 *>(a_src + (int64_t)ks * 64);
 #pragma unroll
         for (int j = 0; j < 4; ++j) st.a[j] = p[j];
@@ -212,22 +201,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + (s / 2) * PAD + i * 32]);
         };
-        if (W_CELL) {
-            // both operands are ready-made cells: a phase copies one cell of each
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                load_frags(s);
-                fence();
-#pragma unroll
-                for (int tm = 0; tm < NMF; ++tm) {
-                    mfma((s + 1) & 1, tm);
-                    if (tm == NMF / 4) nxt[w_cell0 + s * BN] = st.w[s];
-                    else if (tm == NMF / 2) nxt[a_cell0 + s * BM] = a_cell(st, s);
-                    fence();
-                }
-            }
-            return;
-        }
         const uint32_t sbase = unit_scale_bits(st.wm);
         ChunkState cs = chunk_begin(w_word(st, 0), st.wm, sbase, 4 * h);
 #pragma unroll
@@ -266,10 +239,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
     fetch(set0, 0);
     fetch(set1, 1);
     {
-        const uint32_t sbase = W_CELL ? 0u : unit_scale_bits(set0.wm);
+        const uint32_t sbase = unit_scale_bits(set0.wm);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            buf0[w_cell0 + q * BN] = W_CELL ? set0.w[q] : expand_chunk(w_word(set0, q), set0.wm, sbase, 4 * h + q);
+            buf0[w_cell0 + q * BN] = expand_chunk(w_word(set0, q), set0.wm, sbase, 4 * h + q);
             buf0[a_cell0 + q * BM] = a_cell(set0, q);
         }
     }
@@ -469,8 +442,11 @@ __global__ void zero_kernel(void *c, int64_t M, int64_t N, int64_t ldc, int elem
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream);
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
+int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes, hipStream_t stream);
+int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc,
+                       int out_dtype, hipStream_t stream);
 
-template <int BM, int BN, int WM, int WN, bool A_CELL, bool GROUPED, bool W_CELL = false>
+template <int BM, int BN, int WM, int WN, bool A_CELL, bool GROUPED>
 static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stream)
 {
     g.tiles_m = m_tiles;
@@ -481,12 +457,12 @@ static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stre
     const dim3 grid((unsigned)((padded + 7) / 8 * 8)), block(64 * WM * WN);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, true, GROUPED, W_CELL>;
+        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, true, GROUPED>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     } else {
-        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, false, GROUPED, W_CELL>;
+        auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, false, GROUPED>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
@@ -507,17 +483,17 @@ size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
     return 0;
 }
 
-// From this many rows of A on, a dense GEMM decodes W once into the workspace (if the caller
-// gave room for it) instead of expanding it inside the main loop.  The in-loop expansion of a W
-// unit is repeated by each of the M / 256 m-tiles and slows the loop by about 40 %; the
-// pre-pass moves 2.56 bytes per weight once, which is below 30 % of the GEMM's time from 1024
-// rows on and below 10 % from 4096.
+// From this many rows of A on, a dense GEMM between two HiF4 operands decodes W once into the
+// workspace as well (if the caller gave room for it) and runs the kernel of hif4_gemm_cells.hip
+// instead of expanding W inside the main loop.  The in-loop expansion of a W unit is repeated
+// by each of the M / 256 m-tiles; the pre-pass moves 2.56 bytes per weight once, which is below
+// 30 % of the GEMM's time from 1024 rows on and below 10 % from 4096.
 constexpr int64_t DECODED_W_MIN_ROWS = 1024;
 
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
 {
     const size_t base = gemm_workspace_bytes(a_kind, M, K);
-    if (M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
+    if (a_kind == HIF4_A_BF16_KEEP || M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
     return align16(base) + (size_t)N * (size_t)K * 2;
 }
 
@@ -556,13 +532,21 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             codes = qc;
             meta = qm;
         }
+        const size_t base = align16(gemm_workspace_bytes(a_kind, M, K));
+        if (!offs && M >= DECODED_W_MIN_ROWS && workspace_bytes >= base + (size_t)N * (size_t)K * 2) {
+            // room for a decoded copy of W and enough rows for it to pay: both operands as
+            // cell planes, main loop without any expansion
+            uint8_t *wplanes = static_cast<uint8_t *>(workspace) + base;
+            if (int rc = launch_decode_planes(codes, meta, M, K, ws, stream)) return rc;
+            if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
+            return launch_gemm_planes(ws, wplanes, M, N, K, c, ldc, out_dtype, stream);
+        }
         if (int rc = launch_decode_cells(codes, meta, M, K, ws, stream)) return rc;
         g.a = reinterpret_cast<const uint16_t *>(ws);
         g.lda = K;
     }
     g.w_codes = reinterpret_cast<const uint32_t *>(w_codes);
     g.w_meta = w_meta;
-    g.w_cells = nullptr;
     g.offs = offs;
     g.c = c;
     g.ldc = ldc;
@@ -589,14 +573,6 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     constexpr int BM = 256, BN = 256;
     g.tiles_n = (int)((N + BN - 1) / BN);
     const int m_tiles = (int)((M + BM - 1) / BM);
-    const size_t base = align16(gemm_workspace_bytes(a_kind, M, K));
-    if (M >= DECODED_W_MIN_ROWS && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 && workspace_bytes >= base + (size_t)N * (size_t)K * 2) {
-        uint8_t *wcells = static_cast<uint8_t *>(workspace) + base;
-        if (int rc = launch_decode_cells(w_codes, w_meta, N, K, wcells, stream)) return rc;
-        g.w_cells = reinterpret_cast<const uint16_t *>(wcells);
-        if (a_cell) return launch_tiles<BM, BN, 2, 4, true, false, true>(g, out_dtype, m_tiles, stream);
-        return launch_tiles<BM, BN, 2, 4, false, false, true>(g, out_dtype, m_tiles, stream);
-    }
     if (a_cell) return launch_tiles<BM, BN, 2, 4, true, false>(g, out_dtype, m_tiles, stream);
     return launch_tiles<BM, BN, 2, 4, false, false>(g, out_dtype, m_tiles, stream);
 }

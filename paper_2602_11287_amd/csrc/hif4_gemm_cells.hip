@@ -1,0 +1,268 @@
+// Dense HiF4 GEMM for many rows: both operands decoded once per call, then a BF16 MFMA main
+// loop fed by direct global -> LDS loads.
+//
+// Why a second path: inside the tile kernel of hif4_gemm.hip every unit of W is expanded by
+// each of the M / 256 tiles of C that use it.  When M is in the thousands that repeated VALU
+// work costs more than decoding W once (2.56 bytes of traffic per weight), so here the exact
+// BF16 values of A and of W (Eq. 2 of the HiF4 paper, Section II-A; at most six significant
+// bits each) are written to the workspace first and the main loop is a plain BF16 GEMM whose
+// partial sums are those of Eq. 4 (Section III-B) per 64-wide K step, accumulated in fp32.
+//
+// Layout of a decoded copy ("cell planes"): one 16-byte cell holds the 8 values of one group of
+// 8 along K in the order 0,2,1,3,4,6,5,7 (expand_chunk); cell (row, group g) sits at index
+// g * rows + row.  So the 64 cells a wave moves with one global_load_lds_dwordx4 (rows r..r+63
+// of one group) are contiguous in memory and land contiguously in LDS, where a K step of a
+// tile is stored [group j of 8][row] as in the other tile kernel.  No VGPR carries staged data,
+// no ds_write is issued, and the staging needs no VALU work at all.
+#include "hif4_expand.h"
+
+namespace hif4 {
+
+// 64 lanes x 16 bytes from global memory straight into 1 KB of LDS starting at byte offset
+// `lds_byte` (the same for the whole wave): global_load_lds_dwordx4, lane l landing at
+// lds_byte + 16 l.  Completion is counted by vmcnt.  Written as inline assembly so that the
+// compiler's wait-count insertion does not see an LDS-writing load: with one pending it would
+// turn every wait for an LDS read into a wait for all of them, and the operand prefetch of the
+// main loop would be lost.  The caller waits for vmcnt(0) itself before the data is read.
+// M0 (the LDS base of such a load) is used by nothing else in these kernels; the s_nop is the
+// wait state the hardware needs between a write of M0 and an LDS-writing load.
+__device__ __forceinline__ void load_to_lds_16(const uint4 *src, uint32_t lds_byte)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte), "v"(src) : "memory");
+}
+
+// byte offset of a __shared__ object inside the workgroup's LDS
+__device__ __forceinline__ uint32_t lds_offset(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
+}
+
+// ------------------------------------------------------------------ decode to cell planes
+
+// Block = 64 rows x 2 units.  Thread (row = tid % 64, hu = tid / 64) expands half a unit (one
+// 16-byte load of codes) to 4 cells; a wave's stores are 64 consecutive cells of one group.
+// The 4-byte-per-lane reads of a wave touch 64 different lines, but the 8 loads that share a
+// line come from the same block, so they are served by the L1.
+__global__ __launch_bounds__(256) void decode_planes_kernel(const uint32_t *__restrict__ codes,
+                                                            const uint32_t *__restrict__ meta, int64_t rows,
+                                                            int64_t upr, uint4 *__restrict__ planes)
+{
+    const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x % 64;
+    const int hu = threadIdx.x / 64;
+    const int64_t unit = (int64_t)blockIdx.y * 2 + (hu >> 1);
+    if (row >= rows || unit >= upr) return;
+    const int hh = hu & 1;
+    const uint4 c = *reinterpret_cast<const uint4 *>(codes + (row * upr + unit) * 8 + 4 * hh);
+    const uint32_t m = meta[row * upr + unit];
+    const uint32_t sbase = unit_scale_bits(m);
+    const uint32_t cw[4] = { c.x, c.y, c.z, c.w };
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int j = 4 * hh + t;
+        planes[(unit * 8 + j) * rows + row] = expand_chunk(cw[t], m, sbase, j);
+    }
+}
+
+int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes,
+                         hipStream_t stream)
+{
+    const int64_t upr = K / 64;
+    if (rows == 0 || upr == 0) return HIF4_OK;
+    const dim3 grid((unsigned)((rows + 63) / 64), (unsigned)((upr + 1) / 2)), block(256);
+    hipLaunchKernelGGL(decode_planes_kernel, grid, block, 0, stream, reinterpret_cast<const uint32_t *>(codes), meta, rows,
+                       upr, static_cast<uint4 *>(planes));
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+// ------------------------------------------------------------------ GEMM on cell planes
+
+struct PlaneGemmArgs {
+    const uint4 *a; // cell planes of A: [K/8][M]
+    const uint4 *w; // cell planes of W: [K/8][N]
+    void *c;
+    int64_t ldc;
+    int M, N, K;
+    int tiles_m, tiles_n;
+};
+
+template <int BM, int BN, int WM, int WN, bool OUT_F32>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs g)
+{
+    constexpr int NW = WM * WN;                          // waves
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // MFMA tiles per wave
+    constexpr int NMF = TM * TN;                         // MFMAs per quarter step
+    constexpr int W_BASE = 8 * BM, CELLS = 8 * (BM + BN); // 16-byte cells per buffer: [j][row] of A, then of W
+    constexpr int IA = 8 * BM / 64 / NW, IW = 8 * BN / 64 / NW; // 64-cell loads per wave and K step
+    static_assert(BM % 64 == 0 && BN % 64 == 0 && (8 * BM / 64) % NW == 0 && (8 * BN / 64) % NW == 0, "whole loads per wave");
+    extern __shared__ uint4 lds[]; // 2 buffers x CELLS
+
+    const int tid = threadIdx.x;
+    const int wave = tid / 64, lane = tid % 64;
+    const int wm = wave / WN, wn = wave % WN;
+
+    // Block -> tile: every XCD (block b runs on XCD b % 8, each with its own L2) gets one
+    // contiguous run of the tile list, and the list walks the tile grid in super-tiles of
+    // GM x GN tiles, so the ~32 workgroups an XCD runs at a time share A rows 8 ways and W rows
+    // 4 ways in its L2.
+    constexpr int GM = 4, GN = 8, XCDS = 8;
+    const int per_xcd = (int)(gridDim.x / XCDS);
+    const int t = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
+    const int sn = (g.tiles_n + GN - 1) / GN;
+    const int stile = t / (GM * GN), within = t % (GM * GN);
+    const int tile_n = (stile % sn) * GN + within % GN;
+    const int tile_m = (stile / sn) * GM + within / GN;
+    if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return; // padding of the super-tile grid
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    const int nk = g.K / 64;
+
+    // ---- staging plan of this wave: load i moves cells (group j, rows rb*64 .. rb*64+63); rows
+    // past the edge of the matrix repeat its last row (never stored).
+    const uint4 *a_src[IA], *w_src[IW];
+    int a_dst[IA], w_dst[IW];
+#pragma unroll
+    for (int i = 0; i < IA; ++i) {
+        const int id = wave * IA + i, j = id / (BM / 64), rb = id % (BM / 64);
+        int row = row0 + rb * 64 + lane;
+        row = row < g.M ? row : g.M - 1;
+        a_src[i] = g.a + (int64_t)j * g.M + row;
+        a_dst[i] = j * BM + rb * 64;
+    }
+#pragma unroll
+    for (int i = 0; i < IW; ++i) {
+        const int id = wave * IW + i, j = id / (BN / 64), rb = id % (BN / 64);
+        int row = col0 + rb * 64 + lane;
+        row = row < g.N ? row : g.N - 1;
+        w_src[i] = g.w + (int64_t)j * g.N + row;
+        w_dst[i] = W_BASE + j * BN + rb * 64;
+    }
+    const int64_t a_step = (int64_t)8 * g.M, w_step = (int64_t)8 * g.N; // cells per K step
+    // enqueue the loads of one K step into `buf` and advance to the next step
+    auto stage = [&](uint4 *buf) {
+        const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_offset(buf));
+#pragma unroll
+        for (int i = 0; i < IA; ++i) {
+            load_to_lds_16(a_src[i], base + (uint32_t)__builtin_amdgcn_readfirstlane(a_dst[i] * 16));
+            a_src[i] += a_step;
+        }
+#pragma unroll
+        for (int i = 0; i < IW; ++i) {
+            load_to_lds_16(w_src[i], base + (uint32_t)__builtin_amdgcn_readfirstlane(w_dst[i] * 16));
+            w_src[i] += w_step;
+        }
+    };
+    // all of this thread's direct loads have landed in LDS
+    auto staged_wait = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int half = lane / 32, l32 = lane % 32;
+    // MFMA operands of two quarters (K-slabs of 16).  Quarter s takes cell 2s from lanes 0..31
+    // and cell 2s+1 from lanes 32..63.  The set that the first phase works on starts as zeros.
+    bf16x8_t af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[1][i] = bf16x8_t{ 0, 0, 0, 0, 0, 0, 0, 0 };
+#pragma unroll
+    for (int i = 0; i < TN; ++i) bfr[1][i] = bf16x8_t{ 0, 0, 0, 0, 0, 0, 0, 0 };
+    auto mfma = [&](int fb, int tm) {
+        acc[tm / TN][tm % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fb][tm / TN], bfr[fb][tm % TN], acc[tm / TN][tm % TN], 0, 0, 0);
+    };
+    // One K step on `cur`: phase p requests the operands of quarter p and runs the MFMAs of
+    // quarter p-1 (for p = 0: the last quarter of the previous step, still in registers), so
+    // the barrier between two steps falls between a quarter's operand reads and its MFMAs.
+    auto k_step = [&](const uint4 *cur) {
+        const uint4 *abase = cur + wm * (BM / WM) + l32;
+        const uint4 *bbase = cur + W_BASE + wn * (BN / WN) + l32;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int j = 2 * s + half;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[s & 1][i] = __builtin_bit_cast(bf16x8_t, abase[j * BM + i * 32]);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + i * 32]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int tm = 0; tm < NMF; ++tm) mfma((s + 1) & 1, tm);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // One loop body for both buffers (no branch around the matrix work), so that the
+    // accumulators are plain loop-carried registers.
+    int cur = 0, nxt = CELLS;
+    stage(lds);
+    staged_wait();
+    __syncthreads();
+    for (int ks = 0; ks < nk; ++ks) {
+        if (ks + 1 < nk) stage(lds + nxt); // every wave is past its reads of that buffer (the barrier above)
+        k_step(lds + cur);
+        staged_wait();
+        __syncthreads();
+        const int t2 = cur;
+        cur = nxt;
+        nxt = t2;
+    }
+#pragma unroll
+    for (int tm = 0; tm < NMF; ++tm) mfma(1, tm); // quarter 3 of the last step
+
+    // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*half + r%4
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+            const int col = col0 + wn * (BN / WN) + jn * 32 + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + wm * (BM / WM) + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                if (row < g.M && col < g.N) {
+                    const float v = acc[i][jn][r];
+                    if (OUT_F32) {
+                        static_cast<float *>(g.c)[(int64_t)row * g.ldc + col] = v;
+                    } else {
+                        static_cast<uint16_t *>(g.c)[(int64_t)row * g.ldc + col] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
+                    }
+                }
+            }
+        }
+    }
+}
+
+
+int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc,
+                       int out_dtype, hipStream_t stream)
+{
+    constexpr int BM = 256, BN = 256, WM = 2, WN = 4; // 8 waves of 128 x 64: measured faster than 4 waves of 128 x 128
+    PlaneGemmArgs g;
+    g.a = static_cast<const uint4 *>(a_planes);
+    g.w = static_cast<const uint4 *>(w_planes);
+    g.c = c;
+    g.ldc = ldc;
+    g.M = (int)M;
+    g.N = (int)N;
+    g.K = (int)K;
+    g.tiles_m = (int)((M + BM - 1) / BM);
+    g.tiles_n = (int)((N + BN - 1) / BN);
+    constexpr size_t lds_bytes = 2 * 8 * (BM + BN) * sizeof(uint4);
+    const int64_t padded = (int64_t)((g.tiles_m + 3) / 4) * ((g.tiles_n + 7) / 8) * 32; // whole super-tiles, a multiple of 8
+    const dim3 grid((unsigned)padded), block(64 * WM * WN);
+    hipError_t e;
+    if (out_dtype == HIF4_OUT_F32) {
+        auto k = gemm_planes_kernel<BM, BN, WM, WN, true>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return HIF4_ERR_DEVICE;
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
+    } else {
+        auto k = gemm_planes_kernel<BM, BN, WM, WN, false>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return HIF4_ERR_DEVICE;
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
+    }
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+} // namespace hif4

@@ -270,9 +270,9 @@ def test_grouped_gemm_moe_config_sampled(h, oracle):
 
 @pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
 def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
-    """From 1024 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes the call
-    decode W once instead of inside the main loop: same products in the same order, so the same bits
-    as with the small workspace, and both within tolerance of the oracle."""
+    """From 1024 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
+    HiF4 operands decode W once instead of inside the main loop: same products in the same order, so the
+    same bits as with the small workspace, and both within tolerance of the oracle."""
     M, N, K = 1100, 300, 320
     print(f"gemm decoded-W path kind={kind} M={M} N={N} K={K}", flush=True)
     ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 977)
@@ -290,10 +290,10 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
             a_kind, a_dev, am_dev = h.HIF4_A_BF16_QUANTIZE, a_bf16, None
     small = h.hif4_gemm_workspace_bytes(a_kind, M, K)
     big = h.hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
-    assert big >= small + N * K * 2
+    assert big == small if kind == "keep" else big >= small + N * K * 2  # BF16 activations: the packed-W kernel only
     assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 1023, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 1023, K)
     ws_small = torch.empty(max(small, 16), dtype=torch.uint8, device="cuda")
-    ws_big = torch.empty(big, dtype=torch.uint8, device="cuda")
+    ws_big = torch.empty(max(big, 16), dtype=torch.uint8, device="cuda")
     c_small = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, workspace=ws_small)
     c_big = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, workspace=ws_big)
     c_default = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
