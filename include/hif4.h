@@ -68,6 +68,9 @@ enum {
 
 enum { HIF4_OUT_BF16 = 0, HIF4_OUT_F32 = 1 };
 
+/* Element type of the matrix hif4_quantize_from converts. */
+enum { HIF4_IN_BF16 = 0, HIF4_IN_F16 = 1 /* IEEE binary16 */, HIF4_IN_F32 = 2 };
+
 /*
  * BF16 -> HiF4: Algorithm 1 (Section II-B) on every unit of a rows x K matrix.
  *   stage 1  peak magnitudes 64 -> 16 -> 8 -> 1;
@@ -86,6 +89,17 @@ enum { HIF4_OUT_BF16 = 0, HIF4_OUT_F32 = 1 };
  */
 int hif4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
                   uint8_t *codes, uint32_t *meta, int round_mode, void *stream);
+
+/*
+ * The same conversion from a BF16, FP16 or FP32 matrix (Section II-B, first paragraph: other
+ * high-precision formats follow the same procedure).  The paper gives no separate algorithm
+ * for them; here every FP16 / FP32 input is first rounded to BF16 with round_mode (FP32 values
+ * beyond the BF16 range become infinities, so their unit becomes the NaN unit), then Algorithm 1
+ * runs as written.  in_dtype == HIF4_IN_BF16 is hif4_quantize.  x and ldx as there, with ldx in
+ * elements and rows starting on 16-byte boundaries (ldx a multiple of 8, or of 4 for FP32).
+ */
+int hif4_quantize_from(int in_dtype, const void *x, int64_t rows, int64_t K, int64_t ldx,
+                       uint8_t *codes, uint32_t *meta, int round_mode, void *stream);
 
 /*
  * HiF4 -> BF16: Eq. 2 (Section II-A) on every unit.  Every finite HiF4 value has at

@@ -45,6 +45,10 @@ def lib():
         L.hif4o_decode_elem_f64.argtypes = [u8p, C.c_uint32, C.c_int]
         L.hif4o_decode_unit.restype = None
         L.hif4o_decode_unit.argtypes = [u8p, C.c_uint32, u16p, C.POINTER(C.c_int)]
+        L.hif4o_quantize_from.restype = C.c_int
+        L.hif4o_quantize_from.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, u8p, u32p, C.c_int]
+        L.hif4o_f16_to_f64.restype = C.c_double
+        L.hif4o_f16_to_f64.argtypes = [C.c_uint16]
         L.hif4o_quantize.restype = C.c_int
         L.hif4o_quantize.argtypes = [u16p, C.c_int64, C.c_int64, C.c_int64, u8p, u32p, C.c_int]
         L.hif4o_dequantize.restype = C.c_int
@@ -150,6 +154,25 @@ def quantize(x, mode=ROUND_RNE):
     if rc:
         raise ValueError(f"hif4o_quantize failed: {rc}")
     return codes, meta
+
+
+def quantize_from(x, mode=ROUND_RNE):
+    """rows x K float32 or float16 matrix (numpy) -> planes: every input is rounded to BF16 first."""
+    x = np.ascontiguousarray(x)
+    assert x.ndim == 2 and x.dtype in (np.float32, np.float16)
+    rows, K = x.shape
+    codes = np.zeros((rows, K // 2), np.uint8)
+    meta = np.zeros((rows, K // 64), np.uint32)
+    in_dtype = 2 if x.dtype == np.float32 else 1
+    rc = lib().hif4o_quantize_from(in_dtype, x.ctypes.data_as(C.c_void_p), rows, K, K,
+                                   _ptr(codes, C.c_uint8), _ptr(meta, C.c_uint32), mode)
+    if rc:
+        raise ValueError(f"hif4o_quantize_from failed: {rc}")
+    return codes, meta
+
+
+def f16_to_f64(h):
+    return lib().hif4o_f16_to_f64(int(h))
 
 
 def dequantize(codes, meta):

@@ -249,6 +249,42 @@ int hif4o_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx,
     return 0;
 }
 
+/* IEEE binary16 pattern -> its exact value, by the definition of the format. */
+double hif4o_f16_to_f64(uint16_t h)
+{
+    int sign = h >> 15, e = (h >> 10) & 0x1F, m = h & 0x3FF;
+    double v;
+    if (e == 0x1F) v = m ? NAN : INFINITY;
+    else if (e == 0) v = ldexp((double)m, -24);          /* subnormal: m * 2^-10 * 2^-14 */
+    else v = ldexp(1.0 + (double)m / 1024.0, e - 15);
+    return sign ? -v : v;
+}
+
+/* FP32 / FP16 matrices (Section II-B, first paragraph: other high-precision formats take
+ * the same procedure).  The paper prints no algorithm for them; the reading taken here is
+ * that every input is first rounded to BF16 with the conversion's rounding mode, after
+ * which Algorithm 1 runs as written.  in_dtype: 1 = FP16 patterns (uint16), 2 = FP32. */
+int hif4o_quantize_from(int in_dtype, const void *x, int64_t rows, int64_t K, int64_t ldx,
+                        uint8_t *codes, uint32_t *meta, int mode)
+{
+    if (in_dtype == 0) return hif4o_quantize((const uint16_t *)x, rows, K, ldx, codes, meta, mode);
+    if (in_dtype != 1 && in_dtype != 2) return -4;
+    if (K % 64 != 0 || rows < 0 || K < 0 || ldx < K) return -2;
+    int64_t upr = K / 64;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t u = 0; u < upr; ++u) {
+            uint16_t v64[64];
+            for (int i = 0; i < 64; ++i) {
+                int64_t at = r * ldx + 64 * u + i;
+                double v = in_dtype == 1 ? hif4o_f16_to_f64(((const uint16_t *)x)[at]) : (double)((const float *)x)[at];
+                v64[i] = hif4o_f64_to_bf16(v, mode);
+            }
+            hif4o_encode_unit(v64, codes + (r * upr + u) * 32, meta + r * upr + u, mode);
+        }
+    return 0;
+}
+
 int hif4o_dequantize(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K,
                      uint16_t *y, int64_t ldy)
 {

@@ -5,6 +5,8 @@
 namespace hif4 {
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream);
+int launch_encode_from(int in_dtype, const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta,
+                       int mode, hipStream_t stream);
 int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, int64_t ldy,
                   hipStream_t stream);
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
@@ -67,6 +69,19 @@ int hif4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, uint
     if (!x_bf16 || !codes || !meta) return HIF4_ERR_NULL;
     if (!aligned(x_bf16, 16) || (ldx % 8) != 0 || !aligned(codes, 16) || !aligned(meta, 4)) return HIF4_ERR_ALIGN;
     return hif4::launch_encode(x_bf16, rows, K, ldx, codes, meta, round_mode, static_cast<hipStream_t>(stream));
+}
+
+int hif4_quantize_from(int in_dtype, const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta,
+                       int round_mode, void *stream)
+{
+    if (in_dtype != HIF4_IN_BF16 && in_dtype != HIF4_IN_F16 && in_dtype != HIF4_IN_F32) return HIF4_ERR_UNSUPPORTED;
+    if (round_mode != HIF4_ROUND_RNE && round_mode != HIF4_ROUND_RHA) return HIF4_ERR_UNSUPPORTED;
+    if (int rc = check_matrix_shape(rows, K, ldx)) return rc;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    if (!x || !codes || !meta) return HIF4_ERR_NULL;
+    const int64_t elems16 = in_dtype == HIF4_IN_F32 ? 4 : 8; // elements per 16 bytes
+    if (!aligned(x, 16) || (ldx % elems16) != 0 || !aligned(codes, 16) || !aligned(meta, 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_encode_from(in_dtype, x, rows, K, ldx, codes, meta, round_mode, static_cast<hipStream_t>(stream));
 }
 
 int hif4_dequantize(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y_bf16, int64_t ldy,

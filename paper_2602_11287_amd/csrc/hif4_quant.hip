@@ -193,11 +193,55 @@ __device__ __forceinline__ uint32_t encode_share(const uint4 (&w)[8 / LPU], int 
     return special ? 0x000000FFu : (mbits | e6);
 }
 
+// Input element types of the encoder.  FP16 and FP32 inputs are first rounded to BF16 by the
+// rounding mode of the conversion (Section II-B: other high-precision formats follow the same
+// procedure; Algorithm 1 itself is written on BF16), then take the same path.
+enum { IN_BF16 = 0, IN_F16 = 1, IN_F32 = 2 };
+
+// One exact fp32 value -> BF16 pattern under MODE; NaNs stay NaNs, overflow gives infinity.
+template <int MODE>
+__device__ __forceinline__ uint32_t input_pair_to_bf16(float lo, float hi)
+{
+    if (MODE == HIF4_ROUND_RNE) return round_bf16_pair<MODE>(lo, hi); // v_cvt_pk_bf16_f32 keeps NaN and Inf
+    uint32_t r[2];
+    const uint32_t u[2] = { f2u(lo), f2u(hi) };
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t a = u[i] & 0x7FFFFFFFu;
+        const uint32_t m = a > 0x7F800000u ? 0x7FC0u : (a + 0x8000u) >> 16; // magnitude, half away from zero
+        r[i] = m | ((u[i] >> 16) & 0x8000u);
+    }
+    return r[0] | (r[1] << 16);
+}
+
+// 8 consecutive input elements starting at element index e of x -> 8 BF16 in a uint4.
+template <int IN, int MODE, bool NT>
+__device__ __forceinline__ uint4 load_chunk(const void *x, int64_t e)
+{
+    if (IN == IN_BF16) return load16<NT>(static_cast<const uint16_t *>(x) + e);
+    if (IN == IN_F16) {
+        const uint4 h = load16<NT>(static_cast<const uint16_t *>(x) + e);
+        const uint32_t hw[4] = { h.x, h.y, h.z, h.w };
+        uint32_t r[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            const h2 v = __builtin_bit_cast(h2, hw[t]);
+            r[t] = input_pair_to_bf16<MODE>((float)v.x, (float)v.y); // FP16 -> fp32 is exact
+        }
+        return make_uint4(r[0], r[1], r[2], r[3]);
+    }
+    const float *f = static_cast<const float *>(x) + e;
+    const uint4 a = load16<NT>(f), b = load16<NT>(f + 4);
+    return make_uint4(input_pair_to_bf16<MODE>(u2f(a.x), u2f(a.y)), input_pair_to_bf16<MODE>(u2f(a.z), u2f(a.w)),
+                      input_pair_to_bf16<MODE>(u2f(b.x), u2f(b.y)), input_pair_to_bf16<MODE>(u2f(b.z), u2f(b.w)));
+}
+
 // Thread block b encodes units [b * UPB, (b+1) * UPB), UPB = UPT * 256 / LPU; a thread's
 // t-th unit is UPB*b + t*(256/LPU) + threadIdx/LPU, so that every load and store
 // instruction of a wave touches one contiguous range.
-template <int LPU, int MODE, bool CONTIG, int UPT, bool NT>
-__global__ __launch_bounds__(256) void encode_kernel(const uint16_t *__restrict__ x, int64_t units, int64_t upr,
+template <int LPU, int MODE, bool CONTIG, int UPT, bool NT, int IN = IN_BF16>
+__global__ __launch_bounds__(256) void encode_kernel(const void *__restrict__ x, int64_t units, int64_t upr,
                                                      int64_t ldx, uint32_t *__restrict__ codes,
                                                      uint32_t *__restrict__ meta)
 {
@@ -214,15 +258,15 @@ __global__ __launch_bounds__(256) void encode_kernel(const uint16_t *__restrict_
         const int64_t u = first + (int64_t)t * UPS;
         live[t] = u < units;
         unit[t] = live[t] ? u : units - 1; // dead lanes redo the last unit and store nothing
-        const uint16_t *src;
+        int64_t e0; // index of the unit's first element in x
         if (CONTIG) {
-            src = x + unit[t] * 64;
+            e0 = unit[t] * 64;
         } else {
             const int64_t row = unit[t] / upr;
-            src = x + row * ldx + (unit[t] - row * upr) * 64;
+            e0 = row * ldx + (unit[t] - row * upr) * 64;
         }
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) w[t][c] = load16<NT>(src + 8 * (c * LPU + l));
+        for (int c = 0; c < NCH; ++c) w[t][c] = load_chunk<IN, MODE, NT>(x, e0 + 8 * (c * LPU + l));
     }
 #pragma unroll
     for (int t = 0; t < UPT; ++t) {
@@ -329,8 +373,9 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint32_t *__restrict_
 #define HIF4_DEC_NT true
 #endif
 
-int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
-                  hipStream_t stream)
+template <int IN>
+static int launch_encode_in(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
+                            hipStream_t stream)
 {
     const int64_t upr = K / 64, units = rows * upr;
     if (units == 0) return HIF4_OK;
@@ -338,17 +383,31 @@ int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *
     constexpr bool NT = HIF4_ENC_NT;
     constexpr int64_t UPB = (256 / LPU) * UPT; // units per block
     const dim3 grid((unsigned)((units + UPB - 1) / UPB)), block(256);
-    const uint16_t *xs = static_cast<const uint16_t *>(x);
     uint32_t *cd = reinterpret_cast<uint32_t *>(codes);
     const bool contig = ldx == K;
     if (mode == HIF4_ROUND_RNE) {
-        if (contig) hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RNE, true, UPT, NT>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
-        else hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RNE, false, UPT, NT>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
+        if (contig) hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RNE, true, UPT, NT, IN>), grid, block, 0, stream, x, units, upr, ldx, cd, meta);
+        else hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RNE, false, UPT, NT, IN>), grid, block, 0, stream, x, units, upr, ldx, cd, meta);
     } else {
-        if (contig) hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RHA, true, UPT, NT>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
-        else hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RHA, false, UPT, NT>), grid, block, 0, stream, xs, units, upr, ldx, cd, meta);
+        if (contig) hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RHA, true, UPT, NT, IN>), grid, block, 0, stream, x, units, upr, ldx, cd, meta);
+        else hipLaunchKernelGGL((encode_kernel<LPU, HIF4_ROUND_RHA, false, UPT, NT, IN>), grid, block, 0, stream, x, units, upr, ldx, cd, meta);
     }
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
+                  hipStream_t stream)
+{
+    return launch_encode_in<IN_BF16>(x, rows, K, ldx, codes, meta, mode, stream);
+}
+
+// in_dtype: HIF4_IN_BF16 / HIF4_IN_F16 / HIF4_IN_F32 of the C interface (same numbering as above).
+int launch_encode_from(int in_dtype, const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta,
+                       int mode, hipStream_t stream)
+{
+    if (in_dtype == IN_F16) return launch_encode_in<IN_F16>(x, rows, K, ldx, codes, meta, mode, stream);
+    if (in_dtype == IN_F32) return launch_encode_in<IN_F32>(x, rows, K, ldx, codes, meta, mode, stream);
+    return launch_encode_in<IN_BF16>(x, rows, K, ldx, codes, meta, mode, stream);
 }
 
 int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, int64_t ldy,

@@ -19,7 +19,7 @@ HIF4_ROUND_RNE, HIF4_ROUND_RHA = 0, 1
 HIF4_A_BF16_QUANTIZE, HIF4_A_HIF4, HIF4_A_BF16_KEEP = 0, 1, 2
 HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 
-EXPORTS = ["hif4_quantize", "hif4_dequantize", "hif4_gemm", "hif4_grouped_gemm",
+EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_grouped_gemm",
            "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version"]
 
 
@@ -42,6 +42,8 @@ def load():
         vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
         L.hif4_quantize.restype = i32
         L.hif4_quantize.argtypes = [vp, i64, i64, i64, vp, vp, i32, vp]
+        L.hif4_quantize_from.restype = i32
+        L.hif4_quantize_from.argtypes = [i32, vp, i64, i64, i64, vp, vp, i32, vp]
         L.hif4_dequantize.restype = i32
         L.hif4_dequantize.argtypes = [vp, vp, i64, i64, vp, i64, vp]
         L.hif4_gemm.restype = i32
@@ -102,6 +104,23 @@ def hif4_quantize(x, codes=None, meta=None, round_mode=HIF4_ROUND_RNE, stream=No
     ldx = x.stride(0) if rows > 1 else max(x.stride(0), K)
     _check(load().hif4_quantize(_ptr(x), rows, K, ldx, _ptr(codes), _ptr(meta), round_mode, _stream(stream)),
            "hif4_quantize")
+    return codes, meta
+
+
+_IN_DTYPES = {torch.bfloat16: 0, torch.float16: 1, torch.float32: 2}
+
+
+def hif4_quantize_from(x, codes=None, meta=None, round_mode=HIF4_ROUND_RNE, stream=None):
+    """As hif4_quantize for a CUDA bfloat16, float16 or float32 matrix (in_dtype from x.dtype)."""
+    assert x.is_cuda and x.dtype in _IN_DTYPES and x.dim() == 2 and x.stride(1) == 1
+    rows, K = x.shape
+    if codes is None:
+        codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    if meta is None:
+        meta = torch.empty((rows, K // 64), dtype=torch.int32, device=x.device)
+    ldx = x.stride(0) if rows > 1 else max(x.stride(0), K)
+    _check(load().hif4_quantize_from(_IN_DTYPES[x.dtype], _ptr(x), rows, K, ldx, _ptr(codes), _ptr(meta), round_mode,
+                                     _stream(stream)), "hif4_quantize_from")
     return codes, meta
 
 

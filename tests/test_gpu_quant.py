@@ -163,3 +163,50 @@ def test_encode_large_sampled_rows(h, oracle):
     assert (codes[rows].cpu().numpy() == wc).all()
     assert (meta[rows].cpu().numpy().view(np.uint32) == wm).all()
     assert (synth.bits(y[rows].cpu()) == oracle.dequantize(wc, wm)).all()
+
+
+def wide_matrix(rows, K, seed, dtype):
+    """fp32 / fp16 inputs whose low mantissa bits matter: Gaussian bulk with spread scales, exact ties of
+    the BF16 rounding (odd and even neighbours), values at and beyond the edge of the BF16 range, subnormals,
+    zeros of both signs, NaN and infinities."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((rows, K)) * np.exp(rng.uniform(-4, 4, (rows, 1)))
+    x = x.astype(dtype)
+    flat = x.reshape(-1)
+    n = flat.size
+    # BF16 ties: 8 leading significand bits, then exactly one half unit in the last place
+    base = (1.0 + rng.integers(0, 128, n // 50) / 128.0 + 1.0 / 256.0) * 2.0 ** rng.integers(-6, 6, n // 50)
+    flat[rng.integers(0, n, n // 50)] = (base * rng.choice([-1.0, 1.0], n // 50)).astype(dtype)
+    specials = [0.0, -0.0, np.inf, -np.inf, np.nan, 6.0e-8, -6.0e-8, 65504.0, -65504.0, 1.0009765625]
+    if dtype == np.float32:
+        specials += [3.4e38, -3.4e38, 3.3895e38, 1e-40, -1e-45, 1.17549435e-38, 2.0 ** -127 * 1.00390625]
+    for v in specials:
+        flat[rng.integers(0, n, max(1, n // 4000))] = dtype(v)
+    return x
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("rows,K", [(1, 64), (37, 192), (259, 320), (64, 4096)])
+def test_encode_from_fp32_fp16_matches_oracle(h, oracle, rows, K, mode, dtype):
+    print(f"encode from {dtype.__name__} rows={rows} K={K} mode={mode}", flush=True)
+    x = wide_matrix(rows, K, 500 + rows + K, dtype)
+    want_c, want_m = oracle.quantize_from(x, mode)
+    codes, meta = h.hif4_quantize_from(torch.from_numpy(x).cuda(), round_mode=mode)
+    torch.cuda.synchronize()
+    assert (meta.cpu().numpy().view(np.uint32) == want_m).all()
+    assert (codes.cpu().numpy() == want_c).all()
+
+
+def test_encode_from_strided_and_bf16(h, oracle):
+    x = wide_matrix(33, 256, 77, np.float32)
+    big = torch.zeros((33, 256 + 64), dtype=torch.float32, device="cuda")
+    big[:, :256] = torch.from_numpy(x).cuda()
+    codes, meta = h.hif4_quantize_from(big[:, :256])
+    want_c, want_m = oracle.quantize_from(x)
+    assert (codes.cpu().numpy() == want_c).all() and (meta.cpu().numpy().view(np.uint32) == want_m).all()
+    # in_dtype BF16 is hif4_quantize
+    xb = torch.from_numpy(x).to(torch.bfloat16).cuda()
+    c1, m1 = h.hif4_quantize_from(xb)
+    c2, m2 = h.hif4_quantize(xb)
+    assert torch.equal(c1, c2) and torch.equal(m1, m2)

@@ -317,3 +317,52 @@ def test_mse_ratios_of_section_3a(oracle, x):
     # in range, the direct cast of NVFP4 agrees with the scaled one
     mse_nv_direct = np.mean((X - cmp.nvfp4_fake_quant(Xb)) ** 2)
     assert abs(mse_nv_direct / mse_nv - 1.0) < 0.02
+
+
+# ---- FP32 / FP16 inputs: the reading is "round to BF16 first, then Algorithm 1" --------------------
+
+def test_quantize_from_equals_library_bf16_conversion_then_algorithm_1(oracle):
+    """Under RNE the conversion step is what torch's CPU float32/float16 -> bfloat16 cast does (a library
+    routine written by others); the rest is the pinned BF16 encoder."""
+    import torch
+    from paper_2602_11287_amd import synth
+    rng = np.random.default_rng(11)
+    x = (rng.standard_normal((16, 512)) * np.exp(rng.uniform(-5, 5, (16, 1)))).astype(np.float32)
+    x[0, :8] = [np.inf, -np.inf, np.nan, 3.4e38, -3.4e38, 1e-40, 0.0, -0.0]
+    with np.errstate(over="ignore"):
+        x16 = x.astype(np.float16)      # the large entries become infinities
+    for arr in (x, x16):
+        c1, m1 = oracle.quantize_from(arr)
+        c2, m2 = oracle.quantize(synth.bits(torch.from_numpy(arr).to(torch.bfloat16)))
+        assert (c1 == c2).all() and (m1 == m2).all()
+
+
+def test_quantize_from_half_away_ties_and_overflow(oracle):
+    """A BF16 tie in the input goes to the even neighbour under RNE and away from zero under RHA, and a
+    float32 beyond the BF16 range turns its unit into the NaN unit (it rounds to infinity)."""
+    x = np.zeros((1, 64), np.float32)
+    x[0, 0] = 7.0                       # fixes the unit scale: E6M2 = 1.0, REC = 1.0
+    x[0, 8] = 1.0 + 2.0 ** -8 + 0.125   # 1.12890625: BF16 neighbours 1.125 (even) and 1.1328125; own group of 8
+    for mode, want_bf16 in ((0, 1.125), (1, 1.1328125)):
+        c, m = oracle.quantize_from(x, mode)
+        xb = np.zeros((1, 64), np.float32)
+        xb[0, 0], xb[0, 8] = 7.0, want_bf16
+        c2, m2 = oracle.quantize_from(xb, mode)     # exact in BF16: no conversion rounding
+        assert (c == c2).all() and (m == m2).all()
+    # the two roundings of that input give different codes for element 8 (low nibble of byte 4, both
+    # micro-exponents of its groups clear): 1.125 is a tie of the S1P2 grid and goes to 1.0 (even);
+    # 1.1328125 goes to 1.25
+    c_rne, _ = oracle.quantize_from(x, 0)
+    c_rha, _ = oracle.quantize_from(x, 1)
+    assert (c_rne[0, 4] & 0xF) == 4 and (c_rha[0, 4] & 0xF) == 5
+    big = np.zeros((1, 64), np.float32)
+    big[0, 5] = 3.4e38
+    c, m = oracle.quantize_from(big)
+    assert m[0, 0] == 0xFF and not c.any()
+
+
+def test_f16_widening_matches_numpy(oracle):
+    for h in list(range(0, 65536, 7)) + [0x7C00, 0xFC00, 0x0001, 0x8001, 0x03FF, 0x0400, 0x7BFF]:
+        want = float(np.uint16(h).view(np.float16))
+        got = oracle.f16_to_f64(h)
+        assert (np.isnan(want) and np.isnan(got)) or got == want
