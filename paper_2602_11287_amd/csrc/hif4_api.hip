@@ -2,6 +2,8 @@
 // caller's stream.  See include/hif4.h for the contract of every entry point.
 #include "hif4_common.h"
 
+#include "../../include/hif4_compare.h"
+
 namespace hif4 {
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream);
@@ -12,6 +14,11 @@ int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int6
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
                 int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream);
+int launch_fake_quant(int format, const void *x, int64_t rows, int64_t K, int64_t ldx, const uint32_t *tensor_peak, double *y,
+                      double *sq_err, hipStream_t stream);
+int launch_abs_max(const void *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *peak, hipStream_t stream);
+int launch_sq_err(const void *x, const void *y, int64_t rows, int64_t K, int64_t ldx, int64_t ldy, double *sq_err,
+                  hipStream_t stream);
 size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 } // namespace hif4
@@ -129,6 +136,54 @@ int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t
     if (!aligned(offs, 4)) return HIF4_ERR_ALIGN;
     return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, offs, E, total_rows, N, K, c, ldc, out_dtype,
                              workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+// ---- comparison tools (include/hif4_compare.h)
+
+static int check_compare_matrix(const void *x, int64_t rows, int64_t K, int64_t ldx, int64_t group)
+{
+    if (rows < 0 || K < 0 || K % group != 0 || ldx < K || rows >= MAX_DIM || K >= MAX_DIM || ldx >= MAX_DIM) return HIF4_ERR_SHAPE;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    if (!x) return HIF4_ERR_NULL;
+    if (!aligned(x, 16) || (ldx % 8) != 0) return HIF4_ERR_ALIGN;
+    return HIF4_OK;
+}
+
+int hif4cmp_mxfp4_fake_quant(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, double *y, double *sq_err, void *stream)
+{
+    if (int rc = check_compare_matrix(x_bf16, rows, K, ldx, 32)) return rc;
+    if (!aligned(y, 8) || !aligned(sq_err, 8)) return HIF4_ERR_ALIGN;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    return hif4::launch_fake_quant(0, x_bf16, rows, K, ldx, nullptr, y, sq_err, static_cast<hipStream_t>(stream));
+}
+
+int hif4cmp_nvfp4_fake_quant(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, const uint32_t *tensor_peak, double *y,
+                             double *sq_err, void *stream)
+{
+    if (int rc = check_compare_matrix(x_bf16, rows, K, ldx, 16)) return rc;
+    if (!aligned(y, 8) || !aligned(sq_err, 8) || !aligned(tensor_peak, 4)) return HIF4_ERR_ALIGN;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    return hif4::launch_fake_quant(1, x_bf16, rows, K, ldx, tensor_peak, y, sq_err, static_cast<hipStream_t>(stream));
+}
+
+int hif4cmp_abs_max(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, uint32_t *peak, void *stream)
+{
+    if (int rc = check_compare_matrix(x_bf16, rows, K, ldx, 8)) return rc;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    if (!peak) return HIF4_ERR_NULL;
+    if (!aligned(peak, 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_abs_max(x_bf16, rows, K, ldx, peak, static_cast<hipStream_t>(stream));
+}
+
+int hif4cmp_sq_err_bf16(const void *x_bf16, const void *y_bf16, int64_t rows, int64_t K, int64_t ldx, int64_t ldy,
+                        double *sq_err, void *stream)
+{
+    if (int rc = check_compare_matrix(x_bf16, rows, K, ldx, 8)) return rc;
+    if (int rc = check_compare_matrix(y_bf16, rows, K, ldy, 8)) return rc;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    if (!sq_err) return HIF4_ERR_NULL;
+    if (!aligned(sq_err, 8)) return HIF4_ERR_ALIGN;
+    return hif4::launch_sq_err(x_bf16, y_bf16, rows, K, ldx, ldy, sq_err, static_cast<hipStream_t>(stream));
 }
 
 const char *hif4_status_string(int status)

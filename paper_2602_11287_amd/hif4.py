@@ -20,7 +20,8 @@ HIF4_A_BF16_QUANTIZE, HIF4_A_HIF4, HIF4_A_BF16_KEEP = 0, 1, 2
 HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 
 EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_grouped_gemm",
-           "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version"]
+           "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version",
+           "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16"]
 
 
 class Hif4Error(RuntimeError):
@@ -54,6 +55,14 @@ def load():
         L.hif4_gemm_workspace_bytes.argtypes = [i32, i64, i64]
         L.hif4_gemm_workspace_bytes_decoded_w.restype = sz
         L.hif4_gemm_workspace_bytes_decoded_w.argtypes = [i32, i64, i64, i64]
+        L.hif4cmp_mxfp4_fake_quant.restype = i32
+        L.hif4cmp_mxfp4_fake_quant.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+        L.hif4cmp_nvfp4_fake_quant.restype = i32
+        L.hif4cmp_nvfp4_fake_quant.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
+        L.hif4cmp_abs_max.restype = i32
+        L.hif4cmp_abs_max.argtypes = [vp, i64, i64, i64, vp, vp]
+        L.hif4cmp_sq_err_bf16.restype = i32
+        L.hif4cmp_sq_err_bf16.argtypes = [vp, vp, i64, i64, i64, i64, vp, vp]
         L.hif4_status_string.restype = C.c_char_p
         L.hif4_status_string.argtypes = [i32]
         L.hif4_version.restype = i32
@@ -182,3 +191,43 @@ def hif4_grouped_gemm(a_kind, a, a_meta, w_codes, w_meta, offs, out_dtype=HIF4_O
                                     N, K, _ptr(c), ldc, out_dtype, _ptr(workspace), wsz, _stream(stream)),
            "hif4_grouped_gemm")
     return c
+
+
+# ---- comparison tools of include/hif4_compare.h (quantisation-error study, Section III-A) -------------
+
+def _cmp_matrix(x):
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
+    rows, K = x.shape
+    return rows, K, (x.stride(0) if rows > 1 else max(x.stride(0), K))
+
+
+def hif4cmp_mxfp4_fake_quant(x, y=None, sq_err=None, stream=None):
+    """x CUDA bfloat16 [rows, K]; y float64 [rows, K] or None; sq_err float64 [1] (added to) or None."""
+    rows, K, ldx = _cmp_matrix(x)
+    _check(load().hif4cmp_mxfp4_fake_quant(_ptr(x), rows, K, ldx, _ptr(y), _ptr(sq_err), _stream(stream)),
+           "hif4cmp_mxfp4_fake_quant")
+    return y
+
+
+def hif4cmp_nvfp4_fake_quant(x, tensor_peak=None, y=None, sq_err=None, stream=None):
+    """tensor_peak: int32 [1] written by hif4cmp_abs_max (per-tensor scaling) or None (direct cast)."""
+    rows, K, ldx = _cmp_matrix(x)
+    _check(load().hif4cmp_nvfp4_fake_quant(_ptr(x), rows, K, ldx, _ptr(tensor_peak), _ptr(y), _ptr(sq_err),
+                                           _stream(stream)), "hif4cmp_nvfp4_fake_quant")
+    return y
+
+
+def hif4cmp_abs_max(x, peak, stream=None):
+    """peak: int32 [1], zeroed by the caller; receives the BF16 pattern of max|x|."""
+    rows, K, ldx = _cmp_matrix(x)
+    _check(load().hif4cmp_abs_max(_ptr(x), rows, K, ldx, _ptr(peak), _stream(stream)), "hif4cmp_abs_max")
+    return peak
+
+
+def hif4cmp_sq_err_bf16(x, y, sq_err, stream=None):
+    rows, K, ldx = _cmp_matrix(x)
+    _, _, ldy = _cmp_matrix(y)
+    assert y.shape == x.shape
+    _check(load().hif4cmp_sq_err_bf16(_ptr(x), _ptr(y), rows, K, ldx, ldy, _ptr(sq_err), _stream(stream)),
+           "hif4cmp_sq_err_bf16")
+    return sq_err

@@ -18,9 +18,16 @@ def lib():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "hif4.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hif4_[a-z_0-9]+)\s*\(", text)))
+    """Every function declared in any header under include/."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if not f.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, f)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(hif4[a-z]*_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -110,3 +117,31 @@ def test_product_path_has_no_cpu_fallback():
     """The binding imports neither the oracle nor any CPU implementation."""
     src = open(os.path.join(ROOT, "paper_2602_11287_amd", "hif4.py")).read()
     assert "oracle" not in src.replace("no CPU fallback", "")
+
+
+def test_quantize_from_argument_errors(lib):
+    from paper_2602_11287_amd import hif4 as h
+    q = lib.hif4_quantize_from
+    p = 0x1000
+    assert q(3, p, 4, 128, 128, p, p, 0, None) == h.HIF4_ERR_UNSUPPORTED      # unknown input type
+    assert q(2, p, 4, 128, 128, p, p, 2, None) == h.HIF4_ERR_UNSUPPORTED      # unknown rounding
+    assert q(2, p, 4, 100, 100, p, p, 0, None) == h.HIF4_ERR_SHAPE
+    assert q(1, None, 4, 128, 128, p, p, 0, None) == h.HIF4_ERR_NULL
+    assert q(2, p, 4, 128, 130, p, p, 0, None) == h.HIF4_ERR_ALIGN            # fp32 rows: ldx multiple of 4
+    assert q(1, p, 4, 128, 132, p, p, 0, None) == h.HIF4_ERR_ALIGN            # fp16 rows: ldx multiple of 8
+    assert q(2, p + 4, 4, 128, 128, p, p, 0, None) == h.HIF4_ERR_ALIGN
+    assert q(2, None, 0, 128, 128, None, None, 0, None) == h.HIF4_OK
+
+
+def test_compare_tools_argument_errors(lib):
+    from paper_2602_11287_amd import hif4 as h
+    p = 0x1000
+    assert lib.hif4cmp_mxfp4_fake_quant(p, 4, 48, 48, None, None, None) == h.HIF4_ERR_SHAPE   # K % 32
+    assert lib.hif4cmp_nvfp4_fake_quant(p, 4, 40, 40, None, None, None, None) == h.HIF4_ERR_SHAPE  # K % 16
+    assert lib.hif4cmp_mxfp4_fake_quant(None, 4, 64, 64, None, None, None) == h.HIF4_ERR_NULL
+    assert lib.hif4cmp_mxfp4_fake_quant(p, 4, 64, 64, p + 4, None, None) == h.HIF4_ERR_ALIGN
+    assert lib.hif4cmp_nvfp4_fake_quant(p, 4, 64, 64, p + 2, None, None, None) == h.HIF4_ERR_ALIGN
+    assert lib.hif4cmp_abs_max(p, 4, 64, 64, None, None) == h.HIF4_ERR_NULL
+    assert lib.hif4cmp_sq_err_bf16(p, p, 4, 64, 64, 32, p, None) == h.HIF4_ERR_SHAPE          # ldy < K
+    assert lib.hif4cmp_sq_err_bf16(p, p, 4, 64, 64, 64, None, None) == h.HIF4_ERR_NULL
+    assert lib.hif4cmp_mxfp4_fake_quant(None, 0, 64, 64, None, None, None) == h.HIF4_OK
