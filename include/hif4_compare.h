@@ -44,6 +44,27 @@ int hif4cmp_abs_max(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, ui
 int hif4cmp_sq_err_bf16(const void *x_bf16, const void *y_bf16, int64_t rows, int64_t K, int64_t ldx, int64_t ldy,
                         double *sq_err, void *stream);
 
+/*
+ * Speed reference: a GEMM on CDNA4's native MXFP4 matrix instruction
+ * (v_mfma_scale_f32_32x32x64_f8f6f4 with both operands E2M1 and one E8M0 scale per 32 values),
+ * on the same tile kernel that hif4_gemm uses for decoded operands.  It shows what the hardware's
+ * own 4-bit block format reaches on a shape; it computes C = dq(A) * dq(W)^T for MXFP4-quantised
+ * operands, not a HiF4 product.
+ *
+ * hif4ref_mxfp4_pack quantises a finite BF16 matrix [rows][ldx] to MXFP4 (rule as in
+ * hif4cmp_mxfp4_fake_quant) in the layout the kernel reads:
+ *   cells  : 16 bytes per group of 32 along K, element i in nibble i (sign, two exponent bits,
+ *            one mantissa bit); cell (row, group g) at index g * rows + row;  rows * K / 2 bytes
+ *   scales : the biased exponents of the group scales; the byte of group j of K step ks (256
+ *            wide) of a row sits at ((ks * 2 + j % 2) * rows + row) * 4 + j / 2;  rows * K / 32 bytes
+ * K must be a multiple of 256 for both calls.  Pointers 16-byte aligned.
+ */
+int hif4ref_mxfp4_pack(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, void *cells, void *scales, void *stream);
+
+/* C[M][N] (BF16 or fp32 per out_dtype of hif4.h, row stride ldc) from two packed operands. */
+int hif4ref_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_cells, const void *w_scales,
+                       int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

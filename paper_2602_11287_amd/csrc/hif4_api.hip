@@ -19,6 +19,9 @@ int launch_fake_quant(int format, const void *x, int64_t rows, int64_t K, int64_
 int launch_abs_max(const void *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *peak, hipStream_t stream);
 int launch_sq_err(const void *x, const void *y, int64_t rows, int64_t K, int64_t ldx, int64_t ldy, double *sq_err,
                   hipStream_t stream);
+int launch_mxfp4_pack(const void *x, int64_t rows, int64_t K, int64_t ldx, void *cells, void *scales, hipStream_t stream);
+int launch_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_cells, const void *w_scales, int64_t M, int64_t N,
+                      int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream);
 size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 } // namespace hif4
@@ -184,6 +187,28 @@ int hif4cmp_sq_err_bf16(const void *x_bf16, const void *y_bf16, int64_t rows, in
     if (!sq_err) return HIF4_ERR_NULL;
     if (!aligned(sq_err, 8)) return HIF4_ERR_ALIGN;
     return hif4::launch_sq_err(x_bf16, y_bf16, rows, K, ldx, ldy, sq_err, static_cast<hipStream_t>(stream));
+}
+
+int hif4ref_mxfp4_pack(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, void *cells, void *scales, void *stream)
+{
+    if (int rc = check_compare_matrix(x_bf16, rows, K, ldx, 256)) return rc;
+    if (rows == 0 || K == 0) return HIF4_OK;
+    if (!cells || !scales) return HIF4_ERR_NULL;
+    if (!aligned(cells, 16) || !aligned(scales, 16)) return HIF4_ERR_ALIGN;
+    return hif4::launch_mxfp4_pack(x_bf16, rows, K, ldx, cells, scales, static_cast<hipStream_t>(stream));
+}
+
+int hif4ref_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_cells, const void *w_scales, int64_t M,
+                       int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype, void *stream)
+{
+    if (out_dtype != HIF4_OUT_BF16 && out_dtype != HIF4_OUT_F32) return HIF4_ERR_UNSUPPORTED;
+    if (M < 0 || N < 0 || K <= 0 || K % 256 != 0 || ldc < N) return HIF4_ERR_SHAPE;
+    if (M >= MAX_DIM || N >= MAX_DIM || K >= MAX_DIM || ldc >= MAX_DIM) return HIF4_ERR_SHAPE;
+    if (M == 0 || N == 0) return HIF4_OK;
+    if (!a_cells || !a_scales || !w_cells || !w_scales || !c) return HIF4_ERR_NULL;
+    if (!aligned(a_cells, 16) || !aligned(w_cells, 16) || !aligned(a_scales, 4) || !aligned(w_scales, 4)) return HIF4_ERR_ALIGN;
+    if (!aligned(c, out_dtype == HIF4_OUT_BF16 ? 2 : 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_mxfp4_gemm(a_cells, a_scales, w_cells, w_scales, M, N, K, c, ldc, out_dtype, static_cast<hipStream_t>(stream));
 }
 
 const char *hif4_status_string(int status)

@@ -77,17 +77,23 @@ int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t row
 // ------------------------------------------------------------------ GEMM on cell planes
 
 struct PlaneGemmArgs {
-    const uint4 *a; // cell planes of A: [K/8][M]
-    const uint4 *w; // cell planes of W: [K/8][N]
+    const uint4 *a; // cell planes of A: [K/8][M]  (MXFP4: [K/32][M])
+    const uint4 *w; // cell planes of W: [K/8][N]  (MXFP4: [K/32][N])
+    const uint32_t *a_scale, *w_scale; // MXFP4 only: scale planes, see mxfp4_pack_kernel
     void *c;
     int64_t ldc;
     int M, N, K;
     int tiles_m, tiles_n;
 };
 
-template <int BM, int BN, int WM, int WN, bool OUT_F32>
+// MX = false: BF16 cells, a K step is 64 wide and a quarter is one v_mfma_f32_32x32x16_bf16.
+// MX = true (speed reference, not a HiF4 path): MXFP4 cells of 32 E2M1 values with one E8M0
+// scale each, a K step is 256 wide and a quarter is one v_mfma_scale_f32_32x32x64_f8f6f4, which
+// takes a lane's 32 values and their scale as they are.  Everything else is shared.
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool MX = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs g)
 {
+    constexpr int KSTEP = MX ? 256 : 64;
     constexpr int NW = WM * WN;                          // waves
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // MFMA tiles per wave
     constexpr int NMF = TM * TN;                         // MFMAs per quarter step
@@ -113,7 +119,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
     const int tile_m = (stile / sn) * GM + within / GN;
     if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return; // padding of the super-tile grid
     const int row0 = tile_m * BM, col0 = tile_n * BN;
-    const int nk = g.K / 64;
+    const int nk = g.K / KSTEP;
 
     // ---- staging plan of this wave: load i moves cells (group j, rows rb*64 .. rb*64+63); rows
     // past the edge of the matrix repeat its last row (never stored).
@@ -162,15 +168,56 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     const int half = lane / 32, l32 = lane % 32;
-    // MFMA operands of two quarters (K-slabs of 16).  Quarter s takes cell 2s from lanes 0..31
-    // and cell 2s+1 from lanes 32..63.  The set that the first phase works on starts as zeros.
-    bf16x8_t af[2][TM], bfr[2][TN];
+    // MFMA operands of two quarters (K-slabs of 16, or of 64 for MXFP4).  Quarter s takes cell 2s
+    // from lanes 0..31 and cell 2s+1 from lanes 32..63.  The set that the first phase works on
+    // starts as zeros.
+    uint4 af[2][TM], bfr[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[1][i] = bf16x8_t{ 0, 0, 0, 0, 0, 0, 0, 0 };
+    for (int i = 0; i < TM; ++i) af[1][i] = make_uint4(0, 0, 0, 0);
 #pragma unroll
-    for (int i = 0; i < TN; ++i) bfr[1][i] = bf16x8_t{ 0, 0, 0, 0, 0, 0, 0, 0 };
-    auto mfma = [&](int fb, int tm) {
-        acc[tm / TN][tm % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fb][tm / TN], bfr[fb][tm % TN], acc[tm / TN][tm % TN], 0, 0, 0);
+    for (int i = 0; i < TN; ++i) bfr[1][i] = make_uint4(0, 0, 0, 0);
+    // MXFP4 scales: one dword per lane, tile and K step, byte s for quarter s (straight from
+    // global memory, one step ahead); `prev` serves the quarter that is worked off after the barrier.
+    struct Scales {
+        uint32_t a[TM], b[TN];
+    };
+    Scales sc_prev, sc_cur, sc_next;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) sc_prev.a[i] = sc_cur.a[i] = sc_next.a[i] = 0x7F7F7F7Fu; // 2^0
+#pragma unroll
+    for (int i = 0; i < TN; ++i) sc_prev.b[i] = sc_cur.b[i] = sc_next.b[i] = 0x7F7F7F7Fu;
+    auto load_scales = [&](Scales &sc, int ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int row = row0 + wm * (BM / WM) + i * 32 + l32;
+            row = row < g.M ? row : g.M - 1;
+            sc.a[i] = g.a_scale[((int64_t)ks * 2 + half) * g.M + row];
+        }
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            int row = col0 + wn * (BN / WN) + i * 32 + l32;
+            row = row < g.N ? row : g.N - 1;
+            sc.b[i] = g.w_scale[((int64_t)ks * 2 + half) * g.N + row];
+        }
+    };
+    // MFMA number tm of quarter q (of the step whose scales are sc) on operand set fb
+    auto mfma = [&](int fb, int tm, int q, const Scales &sc) {
+        f32x16_t &d = acc[tm / TN][tm % TN];
+        const uint4 a = af[fb][tm / TN], b = bfr[fb][tm % TN];
+        if constexpr (MX) {
+#if defined(__HIP_DEVICE_COMPILE__)
+            typedef int v8i __attribute__((ext_vector_type(8)));
+            const v8i A = { (int)a.x, (int)a.y, (int)a.z, (int)a.w, 0, 0, 0, 0 }, B = { (int)b.x, (int)b.y, (int)b.z, (int)b.w, 0, 0, 0, 0 };
+            const int sa = (int)sc.a[tm / TN], sb = (int)sc.b[tm % TN];
+            // cbsz = blgp = 4: both operands FP4 (E2M1); the op_sel arguments pick the scale byte
+            if (q == 0) d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B, d, 4, 4, 0, sa, 0, sb);
+            else if (q == 1) d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B, d, 4, 4, 1, sa, 1, sb);
+            else if (q == 2) d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B, d, 4, 4, 2, sa, 2, sb);
+            else d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B, d, 4, 4, 3, sa, 3, sb);
+#endif
+        } else {
+            d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), d, 0, 0, 0);
+        }
     };
     // One K step on `cur`: phase p requests the operands of quarter p and runs the MFMAs of
     // quarter p-1 (for p = 0: the last quarter of the previous step, still in registers), so
@@ -182,12 +229,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
         for (int s = 0; s < 4; ++s) {
             const int j = 2 * s + half;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[s & 1][i] = __builtin_bit_cast(bf16x8_t, abase[j * BM + i * 32]);
+            for (int i = 0; i < TM; ++i) af[s & 1][i] = abase[j * BM + i * 32];
 #pragma unroll
-            for (int i = 0; i < TN; ++i) bfr[s & 1][i] = __builtin_bit_cast(bf16x8_t, bbase[j * BN + i * 32]);
+            for (int i = 0; i < TN; ++i) bfr[s & 1][i] = bbase[j * BN + i * 32];
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int tm = 0; tm < NMF; ++tm) mfma((s + 1) & 1, tm);
+            for (int tm = 0; tm < NMF; ++tm) mfma((s + 1) & 1, tm, (s + 3) & 3, s == 0 ? sc_prev : sc_cur);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -196,19 +243,27 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
     // accumulators are plain loop-carried registers.
     int cur = 0, nxt = CELLS;
     stage(lds);
+    if (MX) load_scales(sc_cur, 0);
     staged_wait();
     __syncthreads();
     for (int ks = 0; ks < nk; ++ks) {
-        if (ks + 1 < nk) stage(lds + nxt); // every wave is past its reads of that buffer (the barrier above)
+        if (ks + 1 < nk) {
+            stage(lds + nxt); // every wave is past its reads of that buffer (the barrier above)
+            if (MX) load_scales(sc_next, ks + 1);
+        }
         k_step(lds + cur);
         staged_wait();
         __syncthreads();
         const int t2 = cur;
         cur = nxt;
         nxt = t2;
+        if (MX) {
+            sc_prev = sc_cur;
+            sc_cur = sc_next;
+        }
     }
 #pragma unroll
-    for (int tm = 0; tm < NMF; ++tm) mfma(1, tm); // quarter 3 of the last step
+    for (int tm = 0; tm < NMF; ++tm) mfma(1, tm, 3, sc_prev); // quarter 3 of the last step
 
     // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*half + r%4
 #pragma unroll
@@ -233,15 +288,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
 }
 
 
-int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc,
-                       int out_dtype, hipStream_t stream)
+template <bool MX>
+static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int out_dtype, hipStream_t stream)
 {
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4; // 8 waves of 128 x 64: measured faster than 4 waves of 128 x 128
-    PlaneGemmArgs g;
-    g.a = static_cast<const uint4 *>(a_planes);
-    g.w = static_cast<const uint4 *>(w_planes);
-    g.c = c;
-    g.ldc = ldc;
     g.M = (int)M;
     g.N = (int)N;
     g.K = (int)K;
@@ -252,17 +302,106 @@ int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, in
     const dim3 grid((unsigned)padded), block(64 * WM * WN);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_planes_kernel<BM, BN, WM, WN, true>;
+        auto k = gemm_planes_kernel<BM, BN, WM, WN, true, MX>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     } else {
-        auto k = gemm_planes_kernel<BM, BN, WM, WN, false>;
+        auto k = gemm_planes_kernel<BM, BN, WM, WN, false, MX>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     }
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc,
+                       int out_dtype, hipStream_t stream)
+{
+    PlaneGemmArgs g;
+    g.a = static_cast<const uint4 *>(a_planes);
+    g.w = static_cast<const uint4 *>(w_planes);
+    g.a_scale = g.w_scale = nullptr;
+    g.c = c;
+    g.ldc = ldc;
+    return launch_planes<false>(g, M, N, K, out_dtype, stream);
+}
+
+// ------------------------------------------------------------------ MXFP4 speed reference
+
+// BF16 matrix -> MXFP4 in the plane layout of the kernel above.  One thread per group of 32
+// along K (Section I of the HiF4 paper; OCP Microscaling): shared scale 2^(floor(log2 amax) - 2)
+// clipped to 2^-127 .. 2^127, stored as its biased exponent (E8M0); elements E2M1 (sign, two
+// exponent bits, one mantissa bit), nearest with ties to even, saturated at +-6; element i of
+// the group in nibble i of the 16-byte cell.  Cell (row, group g) at g * rows + row.  The scale
+// bytes of the 8 groups of a 256-wide K step are laid out for the MFMA lanes: dword
+// (ks * 2 + h) * rows + row holds groups h, 2 + h, 4 + h, 6 + h of step ks in bytes 0..3.
+// Finite inputs.  K is a multiple of 256.
+__global__ __launch_bounds__(256) void mxfp4_pack_kernel(const uint16_t *__restrict__ x, int64_t rows, int64_t gpr, int64_t ldx,
+                                                         uint4 *__restrict__ cells, uint8_t *__restrict__ scales)
+{
+    // consecutive threads take consecutive rows of one group: the cell stores are contiguous
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= rows * gpr) return;
+    const int64_t g = id / rows, row = id - g * rows;
+    const uint4 *src = reinterpret_cast<const uint4 *>(x + row * ldx + g * 32);
+    uint32_t w[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint4 v = src[i];
+        w[4 * i] = v.x, w[4 * i + 1] = v.y, w[4 * i + 2] = v.z, w[4 * i + 3] = v.w;
+    }
+    uint32_t amax = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t a = w[i] & 0x7FFF7FFFu;
+        amax = umax(amax, umax(a & 0xFFFFu, a >> 16));
+    }
+    // floor(log2 amax) = exponent field - 127 for normals; zero counts as 2^0 (scale 2^-2), and
+    // anything below 2^-125 ends at the lower clip
+    int shared = amax == 0 ? -2 : (int)(amax >> 7) - 127 - 2;
+    shared = shared < -127 ? -127 : shared;
+    const float inv = u2f((uint32_t)(127 - shared) << 23); // 2^-shared, exponent field in 2..254
+    uint32_t out[4] = { 0, 0, 0, 0 };
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        const uint32_t b = (w[i / 2] >> (16 * (i & 1))) & 0xFFFFu;
+        const float a = u2f((b & 0x7FFFu) << 16) * inv; // exact: a power-of-two scaling
+        float r;
+        if (a < 2.0f) r = rintf(a * 2.0f) * 0.5f;
+        else if (a < 4.0f) r = rintf(a);
+        else r = fminf(rintf(a * 0.5f) * 2.0f, 6.0f);
+        // 0, .5, 1, 1.5 -> 0..3;  2, 3 -> 4, 5;  4 -> 6;  6 -> 7
+        const uint32_t mag = r < 2.0f ? (uint32_t)(r * 2.0f) : (r < 4.0f ? 2u + (uint32_t)r : (r < 5.0f ? 6u : 7u));
+        out[i / 8] |= (((b >> 12) & 8u) | mag) << (4 * (i % 8));
+    }
+    cells[g * rows + row] = make_uint4(out[0], out[1], out[2], out[3]);
+    const int64_t ks = g / 8;
+    const int j = (int)(g % 8);
+    scales[(((ks * 2 + (j & 1)) * rows + row) << 2) + (j >> 1)] = (uint8_t)(shared + 127);
+}
+
+int launch_mxfp4_pack(const void *x, int64_t rows, int64_t K, int64_t ldx, void *cells, void *scales, hipStream_t stream)
+{
+    const int64_t gpr = K / 32, n = rows * gpr;
+    if (n == 0) return HIF4_OK;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    hipLaunchKernelGGL(mxfp4_pack_kernel, grid, block, 0, stream, static_cast<const uint16_t *>(x), rows, gpr, ldx,
+                       static_cast<uint4 *>(cells), static_cast<uint8_t *>(scales));
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+int launch_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_cells, const void *w_scales, int64_t M, int64_t N,
+                      int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream)
+{
+    PlaneGemmArgs g;
+    g.a = static_cast<const uint4 *>(a_cells);
+    g.w = static_cast<const uint4 *>(w_cells);
+    g.a_scale = static_cast<const uint32_t *>(a_scales);
+    g.w_scale = static_cast<const uint32_t *>(w_scales);
+    g.c = c;
+    g.ldc = ldc;
+    return launch_planes<true>(g, M, N, K, out_dtype, stream);
 }
 
 } // namespace hif4

@@ -21,7 +21,8 @@ HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 
 EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_grouped_gemm",
            "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version",
-           "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16"]
+           "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16",
+           "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm"]
 
 
 class Hif4Error(RuntimeError):
@@ -63,6 +64,10 @@ def load():
         L.hif4cmp_abs_max.argtypes = [vp, i64, i64, i64, vp, vp]
         L.hif4cmp_sq_err_bf16.restype = i32
         L.hif4cmp_sq_err_bf16.argtypes = [vp, vp, i64, i64, i64, i64, vp, vp]
+        L.hif4ref_mxfp4_pack.restype = i32
+        L.hif4ref_mxfp4_pack.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+        L.hif4ref_mxfp4_gemm.restype = i32
+        L.hif4ref_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, i32, vp]
         L.hif4_status_string.restype = C.c_char_p
         L.hif4_status_string.argtypes = [i32]
         L.hif4_version.restype = i32
@@ -231,3 +236,24 @@ def hif4cmp_sq_err_bf16(x, y, sq_err, stream=None):
     _check(load().hif4cmp_sq_err_bf16(_ptr(x), _ptr(y), rows, K, ldx, ldy, _ptr(sq_err), _stream(stream)),
            "hif4cmp_sq_err_bf16")
     return sq_err
+
+
+def hif4ref_mxfp4_pack(x, stream=None):
+    """CUDA bfloat16 [rows, K], K % 256 == 0 -> (cells uint8 [K/32, rows, 16], scales uint8 [K/128, rows, 4])."""
+    rows, K, ldx = _cmp_matrix(x)
+    cells = torch.empty((K // 32, rows, 16), dtype=torch.uint8, device=x.device)
+    scales = torch.empty((K // 128, rows, 4), dtype=torch.uint8, device=x.device)
+    _check(load().hif4ref_mxfp4_pack(_ptr(x), rows, K, ldx, _ptr(cells), _ptr(scales), _stream(stream)), "hif4ref_mxfp4_pack")
+    return cells, scales
+
+
+def hif4ref_mxfp4_gemm(a_cells, a_scales, w_cells, w_scales, out_dtype=HIF4_OUT_BF16, c=None, stream=None):
+    """Speed reference on the native MXFP4 matrix instruction; operands from hif4ref_mxfp4_pack."""
+    M, N, K = a_cells.shape[1], w_cells.shape[1], a_cells.shape[0] * 32
+    assert w_cells.shape[0] * 32 == K
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16 if out_dtype == HIF4_OUT_BF16 else torch.float32, device=a_cells.device)
+    ldc = c.stride(0) if M > 1 else max(c.stride(0), N)
+    _check(load().hif4ref_mxfp4_gemm(_ptr(a_cells), _ptr(a_scales), _ptr(w_cells), _ptr(w_scales), M, N, K, _ptr(c), ldc,
+                                     out_dtype, _stream(stream)), "hif4ref_mxfp4_gemm")
+    return c

@@ -84,3 +84,45 @@ def test_mse_ratios_of_section_3a_on_gpu(h, x):
     e = err.cpu().numpy()
     assert abs(e[1] / e[0] - 1.32) < 0.03, e[1] / e[0]
     assert abs(e[2] / e[0] - 1.89) < 0.03, e[2] / e[0]
+
+
+E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+
+
+def unpack_mxfp4(cells, scales):
+    """Packed operand of hif4ref_mxfp4_pack -> fp64 [rows, K] by the layout the header documents."""
+    cells, scales = cells.cpu().numpy(), scales.cpu().numpy()
+    G, rows, _ = cells.shape
+    nib = np.empty((G, rows, 32), np.uint8)
+    nib[:, :, 0::2] = cells & 0xF
+    nib[:, :, 1::2] = cells >> 4
+    val = E2M1[nib & 7] * np.where(nib & 8, -1.0, 1.0)
+    out = np.empty((rows, G * 32))
+    for g in range(G):
+        ks, j = divmod(g, 8)
+        byte = scales[ks * 2 + j % 2, :, j // 2].astype(np.int64)
+        out[:, 32 * g:32 * g + 32] = val[g] * (2.0 ** (byte - 127))[:, None]
+    return out
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 256), (300, 200, 512), (257, 513, 768), (1024, 256, 1024)])
+def test_mxfp4_reference_gemm(h, oracle, M, N, K):
+    """The speed reference is a correct MXFP4 GEMM: its packer gives the comparator's values, and the
+    product equals the fp64 product of those values to fp32 accumulation accuracy."""
+    from oracle import bfp4_comparators as cmp
+    print(f"mxfp4 reference M={M} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(M + N + K)
+    a = synth.to_bf16(rng.standard_normal((M, K)) * np.exp(rng.uniform(-2, 2, (M, 1))))
+    w = synth.to_bf16(rng.standard_normal((N, K)) * 0.02)
+    a[0, :32] = 0.0
+    ac, asc = h.hif4ref_mxfp4_pack(a.cuda())
+    wc, wsc = h.hif4ref_mxfp4_pack(w.cuda())
+    af, wf = unpack_mxfp4(ac, asc), unpack_mxfp4(wc, wsc)
+    assert (af == cmp.mxfp4_fake_quant(oracle.bf16_bits_to_f64(synth.bits(a)))).all()
+    assert (wf == cmp.mxfp4_fake_quant(oracle.bf16_bits_to_f64(synth.bits(w)))).all()
+    c = h.hif4ref_mxfp4_gemm(ac, asc, wc, wsc, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    want = af @ wf.T
+    got = c.cpu().numpy().astype(np.float64)
+    rel = np.linalg.norm(got - want) / np.linalg.norm(want)
+    assert rel <= 1e-5, rel
