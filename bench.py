@@ -139,6 +139,44 @@ def main():
                      "algorithmic_bytes": bytes_dir, "traffic": MEASURED_TRAFFIC_BYTES[dom[0]]},
     }
 
+    # ---- encoder fed with FP32 (256 B of input + 36 B of packed unit): an eighth of the batch
+    x32 = x[:rows // 8].float()
+    u32 = x32.shape[0] * K // 64
+    f32_ms = timed(lambda: hif4.hif4_quantize_from(x32, codes[:rows // 8], meta[:rows // 8]), args.steps)
+    out["legs"]["encode_from_fp32"] = {"ms": round(f32_ms, 4), "GBps": round(u32 * 292 / f32_ms / 1e6, 1),
+                                       "pct_hbm_peak": round(100 * u32 * 292 / f32_ms / 1e6 / HBM_PEAK_GBPS, 1)}
+    del x32
+
+    # ---- quantisation-error study of Section III-A on the GPU: 18 Gaussian 1024 x 1024 matrices with
+    # sigma = 0.01 * 2^x, MSE of HiF4, NVFP4 (per-tensor scaled) and MXFP4 against the BF16 input
+    sweep = [synth.to_bf16(synth.gaussian_sweep(i)).to(dev) for i in range(18)]
+    errs = torch.zeros((18, 3), dtype=torch.float64, device=dev)
+    peaks = torch.zeros(18, dtype=torch.int32, device=dev)
+    yq = torch.empty_like(sweep[0])
+    sc = torch.empty((1024, 512), dtype=torch.uint8, device=dev)
+    sm = torch.empty((1024, 16), dtype=torch.int32, device=dev)
+
+    def sweep_pass():
+        errs.zero_()
+        peaks.zero_()
+        for i, m in enumerate(sweep):
+            hif4.hif4_quantize(m, sc, sm)
+            hif4.hif4_dequantize(sc, sm, yq)
+            hif4.hif4cmp_sq_err_bf16(m, yq, errs[i, 0:1])
+            hif4.hif4cmp_abs_max(m, peaks[i:i + 1])
+            hif4.hif4cmp_nvfp4_fake_quant(m, peaks[i:i + 1], None, errs[i, 1:2])
+            hif4.hif4cmp_mxfp4_fake_quant(m, None, errs[i, 2:3])
+
+    sweep_pass()
+    sweep_ms = timed(sweep_pass, 3)
+    e = errs.cpu().numpy()
+    out["legs"]["mse_sweep_section_3a_gpu"] = {
+        "ms_for_18_matrices_3_formats": round(sweep_ms, 3),
+        "mse_nvfp4_pts_over_hif4": round(float(np.mean(e[:, 1] / e[:, 0])), 3),
+        "mse_mxfp4_over_hif4": round(float(np.mean(e[:, 2] / e[:, 0])), 3),
+        "paper": "1 : 1.32 : 1.89"}
+    del sweep, yq
+
     if not args.no_gemm:
         try:
             from paper_2602_11287_amd import bench_gemm

@@ -38,6 +38,17 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     gen = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 99)
     steps = max(2, min(steps, 10))
 
+    # ---- what the matrix pipeline sustains by itself on operands with random bits (power-limited clock):
+    # the ceiling next to which the GEMM rates below are read; the nominal peak stays the roofline's `peak`
+    scratch = torch.empty(131072, dtype=torch.float32, device=dev)
+    ceiling = {}
+    for kind, name in ((0, "bf16_32x32x16"), (1, "fp4_scaled_32x32x64")):
+        flop = hif4.hif4ref_mfma_loop(kind, 512, scratch)
+        ms = _timed(lambda: hif4.hif4ref_mfma_loop(kind, 512, scratch), 50)
+        ceiling[name] = round(flop / ms / 1e9, 1)
+    legs["mfma_only_loop_random_operands_TFLOPs"] = ceiling
+    bf16_ceiling = ceiling["bf16_32x32x16"]
+
     # ---- weight-only decode shape: M=16, N=4096, K=4096 (HBM-bound weight streaming)
     M, N, K = 16, 4096, 4096
     w = synth.weight_gaussian(N, K, 0.02, config=2, channel_scale=True).to(dev)
@@ -63,7 +74,8 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
         tf = 2.0 * M * N * K / ms / 1e9
         legs[name] = {"ms": round(ms, 4), "TFLOPs": round(tf, 1),
                       "roofline": {"bound": "mfma", "kernel": kernel, "achieved": round(tf, 1), "peak": mfma_peak_tflops,
-                                   "unit": "TFLOP/s", "frac": round(tf / mfma_peak_tflops, 4), "traffic": None}}
+                                   "unit": "TFLOP/s", "frac": round(tf / mfma_peak_tflops, 4),
+                                   "frac_of_mfma_only_loop": round(tf / bf16_ceiling, 4), "traffic": None}}
 
     # ---- W4A4 prefill: M=4096, N=11008, K=4096, activations quantised inside the call
     M, N, K = 4096, 11008, 4096
@@ -73,13 +85,23 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     del w
     ac, am = hif4.hif4_quantize(a)
     c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-    ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
+    ws = torch.empty(hif4.hif4_gemm_workspace_bytes_decoded_w(hif4.HIF4_A_BF16_QUANTIZE, M, N, K), dtype=torch.uint8, device=dev)
+    ws_small = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_HIF4, M, K), dtype=torch.uint8, device=dev)
+    planes, tiles = "hif4::gemm_planes_kernel<256,256,2,4>", "hif4::gemm_kernel<256,256,2,4>"
     mfma_leg("gemm_w4a4_quantize_inside_M4096_N11008_K4096", M, N, K,
              lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-             "hif4::gemm_kernel<256,256>")
+             planes)
     mfma_leg("gemm_w4a4_prepacked_M4096_N11008_K4096", M, N, K,
-             lambda: hif4.hif4_gemm(hif4.HIF4_A_HIF4, ac, am, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c),
-             "hif4::gemm_kernel<256,256>")
+             lambda: hif4.hif4_gemm(hif4.HIF4_A_HIF4, ac, am, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
+             planes)
+    mfma_leg("gemm_w4a4_prepacked_small_workspace_M4096_N11008_K4096", M, N, K,      # W expanded inside the main loop
+             lambda: hif4.hif4_gemm(hif4.HIF4_A_HIF4, ac, am, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws_small),
+             tiles)
+    mc, ms_, = hif4.hif4ref_mxfp4_pack(a)
+    wq = hif4.hif4ref_mxfp4_pack(hif4.hif4_dequantize(wc, wm))       # any weights of that shape: speed only
+    ms = _timed(lambda: hif4.hif4ref_mxfp4_gemm(mc, ms_, wq[0], wq[1], c=c), steps)
+    legs["reference_native_mxfp4_mfma_gemm_M4096_N11008_K4096"] = {"ms": round(ms, 4), "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
+    del mc, ms_, wq, ws_small
     del a, ac, am, wc, wm, c, ws
 
     # ---- grouped W4A4, MoE-shaped: 64 experts, K=7168, N=2048, 8192 routed rows
@@ -114,10 +136,23 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
         w = _randn_bf16((N, K), 0.015, gen, dev)
         wc, wm = _quantize_rows(hif4, w)
         c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-        ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
+        ws = torch.empty(hif4.hif4_gemm_workspace_bytes_decoded_w(hif4.HIF4_A_BF16_QUANTIZE, M, N, K), dtype=torch.uint8, device=dev)
         mfma_leg("gemm_w4a4_quantize_inside_M16384_N28672_K8192", M, N, K,
                  lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-                 "hif4::gemm_kernel<256,256>")
+                 planes)
+        small = hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K)
+        mfma_leg("gemm_w4a4_quantize_inside_small_workspace_M16384_N28672_K8192", M, N, K,
+                 lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws[:small]),
+                 tiles)
+        # speed reference on the same shape: CDNA4's native MXFP4 matrix instruction on the same tile kernel
+        mc, ms_ = hif4.hif4ref_mxfp4_pack(a)
+        wq = hif4.hif4ref_mxfp4_pack(w)
+        hif4.hif4ref_mxfp4_gemm(mc, ms_, wq[0], wq[1], c=c)
+        ms = _timed(lambda: hif4.hif4ref_mxfp4_gemm(mc, ms_, wq[0], wq[1], c=c), steps)
+        legs["reference_native_mxfp4_mfma_gemm_M16384_N28672_K8192"] = {
+            "ms": round(ms, 4), "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1),
+            "frac_of_mfma_only_loop": round(2.0 * M * N * K / ms / 1e9 / ceiling["fp4_scaled_32x32x64"], 4)}
+        del mc, ms_, wq
         # speed reference on the same shape: the vendor library's plain BF16 GEMM on the unquantised operands
         ref = lambda: torch.matmul(a, w.t(), out=c)
         ref()

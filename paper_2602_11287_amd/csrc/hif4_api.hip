@@ -22,6 +22,7 @@ int launch_sq_err(const void *x, const void *y, int64_t rows, int64_t K, int64_t
 int launch_mxfp4_pack(const void *x, int64_t rows, int64_t K, int64_t ldx, void *cells, void *scales, hipStream_t stream);
 int launch_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_cells, const void *w_scales, int64_t M, int64_t N,
                       int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream);
+int launch_mfma_loop(int kind, int iters, float *out, hipStream_t stream);
 size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 } // namespace hif4
@@ -209,6 +210,15 @@ int hif4ref_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_
     if (!aligned(a_cells, 16) || !aligned(w_cells, 16) || !aligned(a_scales, 4) || !aligned(w_scales, 4)) return HIF4_ERR_ALIGN;
     if (!aligned(c, out_dtype == HIF4_OUT_BF16 ? 2 : 4)) return HIF4_ERR_ALIGN;
     return hif4::launch_mxfp4_gemm(a_cells, a_scales, w_cells, w_scales, M, N, K, c, ldc, out_dtype, static_cast<hipStream_t>(stream));
+}
+
+int hif4ref_mfma_loop(int kind, int iters, float *out, void *stream)
+{
+    if (kind != 0 && kind != 1) return HIF4_ERR_UNSUPPORTED;
+    if (iters < 0 || iters > (1 << 24)) return HIF4_ERR_SHAPE;
+    if (!out) return HIF4_ERR_NULL;
+    if (!aligned(out, 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_mfma_loop(kind, iters, out, static_cast<hipStream_t>(stream));
 }
 
 const char *hif4_status_string(int status)

@@ -1,0 +1,65 @@
+// What the matrix pipeline sustains on this chip when nothing else is in the way: a loop of
+// independent MFMAs on operands with random bit patterns (trivial operands such as zeros or
+// small integers draw less power and clock higher, which overstates the ceiling a GEMM on real
+// data can reach).  A measurement aid for the benchmark, not part of any HiF4 path.
+#include "hif4_common.h"
+
+namespace hif4 {
+
+__device__ __forceinline__ uint32_t lcg(uint32_t &s)
+{
+    s = s * 1664525u + 1013904223u;
+    return s;
+}
+
+// KIND 0: v_mfma_f32_32x32x16_bf16.  KIND 1: v_mfma_scale_f32_32x32x64_f8f6f4 with both
+// operands FP4 (E2M1) and unit scales.  Eight accumulators per wave (the GEMM kernels' shape:
+// 4 x 2 tiles), 8 waves per workgroup, one workgroup per CU-sized slot.
+template <int KIND>
+__global__ __launch_bounds__(512) void mfma_loop_kernel(float *out, int iters, uint32_t seed)
+{
+    f32x16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    uint32_t s = seed + threadIdx.x * 7919u + blockIdx.x * 104729u;
+    uint4 av[4], bv[2];
+    // BF16: clear the top exponent bit, so that magnitudes stay at or below 2 and the sums finite
+    const uint32_t keep = KIND == 0 ? 0xBFFFBFFFu : 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) av[i] = make_uint4(lcg(s) & keep, lcg(s) & keep, lcg(s) & keep, lcg(s) & keep);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) bv[i] = make_uint4(lcg(s) & keep, lcg(s) & keep, lcg(s) & keep, lcg(s) & keep);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint4 a = av[i / 2], b = bv[i % 2];
+            if constexpr (KIND == 0) {
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), acc[i], 0, 0, 0);
+            } else {
+#if defined(__HIP_DEVICE_COMPILE__)
+                typedef int v8i __attribute__((ext_vector_type(8)));
+                const v8i A = { (int)a.x, (int)a.y, (int)a.z, (int)a.w, 0, 0, 0, 0 }, B = { (int)b.x, (int)b.y, (int)b.z, (int)b.w, 0, 0, 0, 0 };
+                acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A, B, acc[i], 4, 4, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+#endif
+            }
+        }
+    }
+    float t = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += acc[i][r];
+    out[blockIdx.x * 512 + threadIdx.x] = t;
+}
+
+int launch_mfma_loop(int kind, int iters, float *out, hipStream_t stream)
+{
+    const dim3 grid(256), block(512);
+    if (kind == 0) hipLaunchKernelGGL(mfma_loop_kernel<0>, grid, block, 0, stream, out, iters, 1u);
+    else hipLaunchKernelGGL(mfma_loop_kernel<1>, grid, block, 0, stream, out, iters, 1u);
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+} // namespace hif4

@@ -22,7 +22,7 @@ HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_grouped_gemm",
            "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version",
            "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16",
-           "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm"]
+           "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm", "hif4ref_mfma_loop"]
 
 
 class Hif4Error(RuntimeError):
@@ -68,6 +68,8 @@ def load():
         L.hif4ref_mxfp4_pack.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.hif4ref_mxfp4_gemm.restype = i32
         L.hif4ref_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, i32, vp]
+        L.hif4ref_mfma_loop.restype = i32
+        L.hif4ref_mfma_loop.argtypes = [i32, i32, vp, vp]
         L.hif4_status_string.restype = C.c_char_p
         L.hif4_status_string.argtypes = [i32]
         L.hif4_version.restype = i32
@@ -257,3 +259,10 @@ def hif4ref_mxfp4_gemm(a_cells, a_scales, w_cells, w_scales, out_dtype=HIF4_OUT_
     _check(load().hif4ref_mxfp4_gemm(_ptr(a_cells), _ptr(a_scales), _ptr(w_cells), _ptr(w_scales), M, N, K, _ptr(c), ldc,
                                      out_dtype, _stream(stream)), "hif4ref_mxfp4_gemm")
     return c
+
+
+def hif4ref_mfma_loop(kind, iters, out, stream=None):
+    """out: CUDA float32 [131072]; returns the flop count of the launch."""
+    assert out.is_cuda and out.dtype == torch.float32 and out.numel() >= 131072
+    _check(load().hif4ref_mfma_loop(int(kind), int(iters), _ptr(out), _stream(stream)), "hif4ref_mfma_loop")
+    return 2048 * int(iters) * 8 * (32768 if kind == 0 else 131072)
