@@ -155,7 +155,7 @@ size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K)
  * many bytes, hif4_gemm decodes W once per call into the workspace (2 more bytes per weight)
  * and runs its main loop on the decoded values of both operands.  The result is the same bit
  * for bit; only the speed differs.  Equals hif4_gemm_workspace_bytes() when M is too small for
- * this to pay (below 1024 rows) and for a_kind 2.  A workspace between the two sizes is used as
+ * this to pay (below 8192 rows) and for a_kind 2.  A workspace between the two sizes is used as
  * the smaller one.  Host function.
  */
 size_t hif4_gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);

@@ -85,23 +85,19 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     del w
     ac, am = hif4.hif4_quantize(a)
     c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-    ws = torch.empty(hif4.hif4_gemm_workspace_bytes_decoded_w(hif4.HIF4_A_BF16_QUANTIZE, M, N, K), dtype=torch.uint8, device=dev)
-    ws_small = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_HIF4, M, K), dtype=torch.uint8, device=dev)
+    ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
     planes, tiles = "hif4::gemm_planes_kernel<256,256,2,4>", "hif4::gemm_kernel<256,256,2,4>"
     mfma_leg("gemm_w4a4_quantize_inside_M4096_N11008_K4096", M, N, K,
              lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-             planes)
+             tiles)
     mfma_leg("gemm_w4a4_prepacked_M4096_N11008_K4096", M, N, K,
              lambda: hif4.hif4_gemm(hif4.HIF4_A_HIF4, ac, am, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-             planes)
-    mfma_leg("gemm_w4a4_prepacked_small_workspace_M4096_N11008_K4096", M, N, K,      # W expanded inside the main loop
-             lambda: hif4.hif4_gemm(hif4.HIF4_A_HIF4, ac, am, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws_small),
              tiles)
     mc, ms_, = hif4.hif4ref_mxfp4_pack(a)
     wq = hif4.hif4ref_mxfp4_pack(hif4.hif4_dequantize(wc, wm))       # any weights of that shape: speed only
     ms = _timed(lambda: hif4.hif4ref_mxfp4_gemm(mc, ms_, wq[0], wq[1], c=c), steps)
     legs["reference_native_mxfp4_mfma_gemm_M4096_N11008_K4096"] = {"ms": round(ms, 4), "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
-    del mc, ms_, wq, ws_small
+    del mc, ms_, wq
     del a, ac, am, wc, wm, c, ws
 
     # ---- grouped W4A4, MoE-shaped: 64 experts, K=7168, N=2048, 8192 routed rows

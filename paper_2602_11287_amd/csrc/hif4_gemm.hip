@@ -485,10 +485,11 @@ size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
 
 // From this many rows of A on, a dense GEMM between two HiF4 operands decodes W once into the
 // workspace as well (if the caller gave room for it) and runs the kernel of hif4_gemm_cells.hip
-// instead of expanding W inside the main loop.  The in-loop expansion of a W unit is repeated
-// by each of the M / 256 m-tiles; the pre-pass moves 2.56 bytes per weight once, which is below
-// 30 % of the GEMM's time from 1024 rows on and below 10 % from 4096.
-constexpr int64_t DECODED_W_MIN_ROWS = 1024;
+// instead of expanding W inside the main loop.  Measured on MI355X: the main loop without any
+// expansion is 3 to 5 % faster (same matrix-pipeline occupancy, higher clock because the VALUs
+// idle), and the pre-pass that decodes W costs 2.56 bytes per weight once per call, which that
+// margin covers from about 8192 rows on (at 4096 rows the two paths tie).
+constexpr int64_t DECODED_W_MIN_ROWS = 8192;
 
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
 {

@@ -270,10 +270,10 @@ def test_grouped_gemm_moe_config_sampled(h, oracle):
 
 @pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
 def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
-    """From 1024 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
+    """From 8192 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
     HiF4 operands decode W once instead of inside the main loop: same products in the same order, so the
     same bits as with the small workspace, and both within tolerance of the oracle."""
-    M, N, K = 1100, 300, 320
+    M, N, K = 8192 + 77, 300, 320
     print(f"gemm decoded-W path kind={kind} M={M} N={N} K={K}", flush=True)
     ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 977)
     wcd, wmd = dev_packed(wc, wm)
@@ -291,7 +291,7 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
     small = h.hif4_gemm_workspace_bytes(a_kind, M, K)
     big = h.hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
     assert big == small if kind == "keep" else big >= small + N * K * 2  # BF16 activations: the packed-W kernel only
-    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 1023, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 1023, K)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 8191, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 8191, K)
     ws_small = torch.empty(max(small, 16), dtype=torch.uint8, device="cuda")
     ws_big = torch.empty(max(big, 16), dtype=torch.uint8, device="cuda")
     c_small = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, workspace=ws_small)
@@ -302,3 +302,32 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
     assert rel_fro(got, want) <= TOL, rel_fro(got, want)
     assert rel_fro(c_small.cpu().numpy().astype(np.float64), want) <= TOL
     assert torch.equal(c_small, c_big) and torch.equal(c_default, c_big)
+
+
+def test_gemm_many_rows_many_tiles_sampled(h, oracle):
+    """16384 x 2048 x 8192 with the activations quantised inside the call: 512 tiles over the whole chip
+    through the decoded-operand path (the launch shape of the large prefill benchmark leg, fewer
+    columns); a seeded sample of rows x columns against the oracle."""
+    M, N, K = 16384, 2048, 8192
+    print(f"gemm sampled M={M} N={N} K={K}", flush=True)
+    g = torch.Generator().manual_seed(synth.BASE_SEED + 55)
+    z = torch.randn((M, K), generator=g)
+    chi = torch.randn((4, M, K), generator=g).pow(2).sum(0)
+    a = (z / torch.sqrt(chi / 4.0) / np.sqrt(2.0)).to(torch.bfloat16)      # Student-t(4), unit variance
+    del z, chi
+    w = synth.weight_gaussian(N, K, 0.015, config=5)
+    wc, wm = oracle.quantize(synth.bits(w))
+    wcd, wmd = dev_packed(wc, wm)
+    ad = a.cuda()
+    big = h.hif4_gemm_workspace_bytes_decoded_w(h.HIF4_A_BF16_QUANTIZE, M, N, K)
+    assert big > h.hif4_gemm_workspace_bytes(h.HIF4_A_BF16_QUANTIZE, M, K)
+    c = h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, ad, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32,
+                    workspace=torch.empty(big, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    rows = np.sort(np.concatenate([rng.choice(M, 94, replace=False), [0, M - 1]]))
+    cols = np.sort(np.concatenate([rng.choice(N, 94, replace=False), [0, N - 1]]))
+    ac, am = oracle.quantize(synth.bits(a)[rows])
+    want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc[cols], wm[cols]))
+    got = c[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
+    assert rel_fro(got, want) <= TOL, rel_fro(got, want)
