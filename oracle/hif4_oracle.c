@@ -20,7 +20,8 @@
  * Parity unpinned (the paper is silent; these are documented readings): the bit
  * layout of the packed unit, RNE as the default of the two roundings the paper
  * allows, Inf inputs producing the NaN unit, the reciprocal table being rounded
- * to nearest, the sign of zero copying the input sign.
+ * to nearest, the sign of zero copying the input sign, FP16 / FP32 inputs being
+ * rounded to BF16 before Algorithm 1 (hif4o_quantize_from).
  *
  * Packed layout used on both sides of the boundary:
  *   codes[row][K/2] : 32 bytes per unit, 4 bytes per group of 8 elements; inside
