@@ -133,6 +133,21 @@ int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * hif4_gemm whose result leaves as HiF4: C = A * W^T is rounded to BF16 as HIF4_OUT_BF16 would
+ * round it, and every row of C is then converted by Algorithm 1 (Section II-B) with units of 64
+ * consecutive columns, i.e. along the axis the next linear layer reduces over (the paper converts
+ * every linear layer's input before its matrix product, Section IV).  The planes equal
+ * hif4_quantize(result of hif4_gemm with HIF4_OUT_BF16) bit for bit; C never crosses HBM as BF16.
+ *   c_codes  out  uint8 [M][N/2], c_meta out uint32 [M][N/64];  N a multiple of 64
+ * Other arguments, workspace and errors as hif4_gemm.
+ */
+int hif4_gemm_to_hif4(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
+                      const uint8_t *w_codes, const uint32_t *w_meta,
+                      int64_t M, int64_t N, int64_t K,
+                      uint8_t *c_codes, uint32_t *c_meta, int round_mode,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Grouped (mixture-of-experts) GEMM: the rows of A are sorted by expert; expert e owns
  * rows offs[e] .. offs[e+1]-1 and multiplies them by its own weights
  * W[e] (w_codes [E][N][K/2], w_meta [E][N][K/64]).  offs is a DEVICE int32[E+1] array,

@@ -13,7 +13,7 @@ int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int6
                   hipStream_t stream);
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
-                int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream);
+                uint32_t *c_meta, int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream);
 int launch_fake_quant(int format, const void *x, int64_t rows, int64_t K, int64_t ldx, const uint32_t *tensor_peak, double *y,
                       double *sq_err, hipStream_t stream);
 int launch_abs_max(const void *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *peak, hipStream_t stream);
@@ -124,8 +124,24 @@ int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, co
     if (int rc = check_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, workspace, workspace_bytes))
         return rc;
     if (M == 0 || N == 0) return HIF4_OK;
-    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, nullptr, 1, M, N, K, c, ldc, out_dtype, workspace,
+    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, nullptr, 1, M, N, K, c, nullptr, ldc, out_dtype, workspace,
                              workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+int hif4_gemm_to_hif4(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
+                      const uint32_t *w_meta, int64_t M, int64_t N, int64_t K, uint8_t *c_codes, uint32_t *c_meta,
+                      int round_mode, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (round_mode != HIF4_ROUND_RNE && round_mode != HIF4_ROUND_RHA) return HIF4_ERR_UNSUPPORTED;
+    if (N % HIF4_UNIT != 0) return HIF4_ERR_SHAPE; // units of the result run along N
+    // the other checks are those of hif4_gemm with a BF16 result of row stride N in place of the planes
+    if (int rc = check_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, M, N, K, c_codes, N, HIF4_OUT_BF16, workspace, workspace_bytes))
+        return rc;
+    if (M == 0 || N == 0) return HIF4_OK;
+    if (!c_meta) return HIF4_ERR_NULL;
+    if (!aligned(c_codes, 16) || !aligned(c_meta, 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, nullptr, 1, M, N, K, c_codes, c_meta, N, 16 + round_mode,
+                             workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
@@ -138,7 +154,7 @@ int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t
     if (total_rows == 0 || N == 0 || E == 0) return HIF4_OK;
     if (!offs) return HIF4_ERR_NULL;
     if (!aligned(offs, 4)) return HIF4_ERR_ALIGN;
-    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, offs, E, total_rows, N, K, c, ldc, out_dtype,
+    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, offs, E, total_rows, N, K, c, nullptr, ldc, out_dtype,
                              workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 

@@ -20,6 +20,7 @@
 // pairs; MFMA sub-step s (of 4) takes cell 2s from lanes 0..31 and cell 2s+1 from
 // lanes 32..63.  Cells are stored [j][row], so both the expansion writes and the operand
 // reads of a wave touch consecutive 16-byte cells.
+#include "hif4_emit.h"
 #include "hif4_expand.h"
 
 #ifndef HIF4_GEMM_SCHED
@@ -36,6 +37,7 @@ struct GemmArgs {
     const uint32_t *w_meta;  // [E][N][K/64]
     const int32_t *offs;     // grouped: device int32[E+1]; else nullptr
     void *c;
+    uint32_t *c_meta; // EMIT kernels: c is the codes plane [M][N/2] of the HiF4 result, this its metadata plane
     int64_t lda; // row stride of a, in elements
     int64_t ldc;
     int M, N, K, E;
@@ -44,7 +46,8 @@ struct GemmArgs {
 
 // A_CELL: the 8 BF16 of every group of 8 in `a` are already stored in cell order (the
 // library's own decoded copy of a HiF4 operand); otherwise they are permuted on the way in.
-template <int BM, int BN, int WM, int WN, bool A_CELL, bool OUT_F32, bool GROUPED>
+// EMIT >= 0: the result is written as HiF4 with units along N (rounding mode EMIT), see hif4_emit.h.
+template <int BM, int BN, int WM, int WN, bool A_CELL, bool OUT_F32, bool GROUPED, int EMIT = -1>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 {
     constexpr int NT = 64 * WM * WN;
@@ -262,6 +265,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmArgs g)
 #pragma unroll
     for (int tm = 0; tm < NMF; ++tm) mfma(1, tm); // quarter 3 of the last step
 
+    if constexpr (EMIT >= 0) {
+        emit_hif4_tile<BM, BN, WM, WN, EMIT>(acc, lds, row0, rows_end, col0, g.N, static_cast<uint32_t *>(g.c), g.c_meta);
+        return;
+    }
     // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*half + r%4
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -443,19 +450,35 @@ int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *
                   hipStream_t stream);
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes, hipStream_t stream);
-int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc,
-                       int out_dtype, hipStream_t stream);
+int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, uint32_t *c_meta,
+                       int64_t ldc, int out_dtype, hipStream_t stream);
+
+// Internal output kinds beyond HIF4_OUT_BF16 / HIF4_OUT_F32: the result as HiF4 (c = codes plane, c_meta).
+enum { OUT_HIF4_RNE = 16, OUT_HIF4_RHA = 17 };
 
 template <int BM, int BN, int WM, int WN, bool A_CELL, bool GROUPED>
 static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stream)
 {
     g.tiles_m = m_tiles;
-    constexpr size_t lds_bytes = 2 * (8 * (BM + BN) + 8) * sizeof(uint4);
+    constexpr size_t loop_bytes = 2 * (8 * (BM + BN) + 8) * sizeof(uint4);
+    constexpr size_t lds_bytes = loop_bytes;
     // the super-tile grid (4 x 8 tiles), padded, split evenly over the 8 XCDs: see the kernel
     const int64_t padded = GROUPED ? (int64_t)((m_tiles + 7) / 8) * 8 * g.tiles_n
                                    : (int64_t)((m_tiles + 3) / 4) * ((g.tiles_n + 7) / 8) * 32;
     const dim3 grid((unsigned)((padded + 7) / 8 * 8)), block(64 * WM * WN);
     hipError_t e;
+    if constexpr (!GROUPED) {
+        if (out_dtype == OUT_HIF4_RNE || out_dtype == OUT_HIF4_RHA) { // result written as HiF4
+            constexpr size_t emit_bytes = emit_lds_bytes<BM, BN>() > loop_bytes ? emit_lds_bytes<BM, BN>() : loop_bytes;
+            static_assert(emit_bytes <= 160 * 1024, "fits the LDS of one CU");
+            auto k = out_dtype == OUT_HIF4_RNE ? gemm_kernel<BM, BN, WM, WN, A_CELL, false, false, HIF4_ROUND_RNE>
+                                               : gemm_kernel<BM, BN, WM, WN, A_CELL, false, false, HIF4_ROUND_RHA>;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)emit_bytes);
+            if (e != hipSuccess) return HIF4_ERR_DEVICE;
+            hipLaunchKernelGGL(k, grid, block, emit_bytes, stream, g);
+            return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+        }
+    }
     if (out_dtype == HIF4_OUT_F32) {
         auto k = gemm_kernel<BM, BN, WM, WN, A_CELL, true, GROUPED>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -498,16 +521,24 @@ size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t 
     return align16(base) + (size_t)N * (size_t)K * 2;
 }
 
+// out_dtype: HIF4_OUT_BF16, HIF4_OUT_F32, or 16 + rounding mode for a HiF4 result (c = codes plane, c_meta = its
+// metadata plane, ldc unused; dense calls only).
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
-                int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream)
+                uint32_t *c_meta, int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    const bool emit = out_dtype == OUT_HIF4_RNE || out_dtype == OUT_HIF4_RHA;
     if (K == 0) { // empty sum: C = 0 (a fill kernel, so that the call can be captured in a graph)
         const dim3 grid((unsigned)((N + 255) / 256), (unsigned)(M < 65535 ? M : 65535)), block(256);
-        hipLaunchKernelGGL(zero_kernel, grid, block, 0, stream, c, M, N, ldc, out_dtype == HIF4_OUT_F32 ? 4 : 2);
+        if (emit) { // the all-zero unit: codes 0, metadata 0 (E6M2 at its least code, no micro-exponents)
+            hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((N / 4 + 255) / 256), grid.y), block, 0, stream, c, M, N / 4, N / 4, 2);
+            hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((N / 64 + 255) / 256), grid.y), block, 0, stream, c_meta, M, N / 64, N / 64, 4);
+        } else {
+            hipLaunchKernelGGL(zero_kernel, grid, block, 0, stream, c, M, N, ldc, out_dtype == HIF4_OUT_F32 ? 4 : 2);
+        }
         return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
     }
-    if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64) { // decode-shaped: stream the weights once
+    if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64 && !emit) { // decode-shaped: stream the weights once
         if (M <= 16) return launch_skinny<1>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         if (M <= 32) return launch_skinny<2>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         return launch_skinny<4>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
@@ -540,7 +571,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             uint8_t *wplanes = static_cast<uint8_t *>(workspace) + base;
             if (int rc = launch_decode_planes(codes, meta, M, K, ws, stream)) return rc;
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
-            return launch_gemm_planes(ws, wplanes, M, N, K, c, ldc, out_dtype, stream);
+            return launch_gemm_planes(ws, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
         if (int rc = launch_decode_cells(codes, meta, M, K, ws, stream)) return rc;
         g.a = reinterpret_cast<const uint16_t *>(ws);
@@ -550,6 +581,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     g.w_meta = w_meta;
     g.offs = offs;
     g.c = c;
+    g.c_meta = c_meta;
     g.ldc = ldc;
     g.M = (int)M;
     g.N = (int)N;

@@ -14,6 +14,7 @@
 // of one group) are contiguous in memory and land contiguously in LDS, where a K step of a
 // tile is stored [group j of 8][row] as in the other tile kernel.  No VGPR carries staged data,
 // no ds_write is issued, and the staging needs no VALU work at all.
+#include "hif4_emit.h"
 #include "hif4_expand.h"
 
 namespace hif4 {
@@ -81,6 +82,7 @@ struct PlaneGemmArgs {
     const uint4 *w; // cell planes of W: [K/8][N]  (MXFP4: [K/32][N])
     const uint32_t *a_scale, *w_scale; // MXFP4 only: scale planes, see mxfp4_pack_kernel
     void *c;
+    uint32_t *c_meta; // EMIT kernels: c is the codes plane of the HiF4 result, this its metadata plane
     int64_t ldc;
     int M, N, K;
     int tiles_m, tiles_n;
@@ -90,7 +92,8 @@ struct PlaneGemmArgs {
 // MX = true (speed reference, not a HiF4 path): MXFP4 cells of 32 E2M1 values with one E8M0
 // scale each, a K step is 256 wide and a quarter is one v_mfma_scale_f32_32x32x64_f8f6f4, which
 // takes a lane's 32 values and their scale as they are.  Everything else is shared.
-template <int BM, int BN, int WM, int WN, bool OUT_F32, bool MX = false>
+// EMIT >= 0: the result is written as HiF4 with units along N (rounding mode EMIT), see hif4_emit.h.
+template <int BM, int BN, int WM, int WN, bool OUT_F32, bool MX = false, int EMIT = -1>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs g)
 {
     constexpr int KSTEP = MX ? 256 : 64;
@@ -265,6 +268,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
 #pragma unroll
     for (int tm = 0; tm < NMF; ++tm) mfma(1, tm, 3, sc_prev); // quarter 3 of the last step
 
+    if constexpr (EMIT >= 0) {
+        emit_hif4_tile<BM, BN, WM, WN, EMIT>(acc, lds, row0, g.M, col0, g.N, static_cast<uint32_t *>(g.c), g.c_meta);
+        return;
+    }
+
     // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*half + r%4
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -301,6 +309,18 @@ static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int o
     const int64_t padded = (int64_t)((g.tiles_m + 3) / 4) * ((g.tiles_n + 7) / 8) * 32; // whole super-tiles, a multiple of 8
     const dim3 grid((unsigned)padded), block(64 * WM * WN);
     hipError_t e;
+    if constexpr (!MX) {
+        if (out_dtype == 16 + HIF4_ROUND_RNE || out_dtype == 16 + HIF4_ROUND_RHA) { // result written as HiF4
+            constexpr size_t emit_bytes = emit_lds_bytes<BM, BN>() > lds_bytes ? emit_lds_bytes<BM, BN>() : lds_bytes;
+            static_assert(emit_bytes <= 160 * 1024, "fits the LDS of one CU");
+            auto k = out_dtype == 16 + HIF4_ROUND_RNE ? gemm_planes_kernel<BM, BN, WM, WN, false, false, HIF4_ROUND_RNE>
+                                                       : gemm_planes_kernel<BM, BN, WM, WN, false, false, HIF4_ROUND_RHA>;
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)emit_bytes);
+            if (e != hipSuccess) return HIF4_ERR_DEVICE;
+            hipLaunchKernelGGL(k, grid, block, emit_bytes, stream, g);
+            return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+        }
+    }
     if (out_dtype == HIF4_OUT_F32) {
         auto k = gemm_planes_kernel<BM, BN, WM, WN, true, MX>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -315,14 +335,16 @@ static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int o
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 
-int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc,
-                       int out_dtype, hipStream_t stream)
+// out_dtype as in launch_gemm: 16 + rounding mode writes the result as HiF4 (c = codes plane, c_meta).
+int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, uint32_t *c_meta,
+                       int64_t ldc, int out_dtype, hipStream_t stream)
 {
     PlaneGemmArgs g;
     g.a = static_cast<const uint4 *>(a_planes);
     g.w = static_cast<const uint4 *>(w_planes);
     g.a_scale = g.w_scale = nullptr;
     g.c = c;
+    g.c_meta = c_meta;
     g.ldc = ldc;
     return launch_planes<false>(g, M, N, K, out_dtype, stream);
 }
@@ -400,6 +422,7 @@ int launch_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_c
     g.a_scale = static_cast<const uint32_t *>(a_scales);
     g.w_scale = static_cast<const uint32_t *>(w_scales);
     g.c = c;
+    g.c_meta = nullptr;
     g.ldc = ldc;
     return launch_planes<true>(g, M, N, K, out_dtype, stream);
 }

@@ -145,3 +145,23 @@ def test_compare_tools_argument_errors(lib):
     assert lib.hif4cmp_sq_err_bf16(p, p, 4, 64, 64, 32, p, None) == h.HIF4_ERR_SHAPE          # ldy < K
     assert lib.hif4cmp_sq_err_bf16(p, p, 4, 64, 64, 64, None, None) == h.HIF4_ERR_NULL
     assert lib.hif4cmp_mxfp4_fake_quant(None, 0, 64, 64, None, None, None) == h.HIF4_OK
+
+
+def test_gemm_to_hif4_argument_errors(lib):
+    from paper_2602_11287_amd import hif4 as h
+    f = lib.hif4_gemm_to_hif4
+    p = 0x1000
+    ok = (h.HIF4_A_BF16_KEEP, p, None, 128, p, p, 4, 128, 128, p, p, 0, None, 0, None)
+    def call(**kw):
+        names = ["a_kind", "a", "a_meta", "lda", "w_codes", "w_meta", "M", "N", "K", "c_codes", "c_meta", "round", "ws", "wsz", "stream"]
+        args = list(ok)
+        for k, v in kw.items():
+            args[names.index(k)] = v
+        return f(*args)
+    assert call(N=100) == h.HIF4_ERR_SHAPE            # units of the result run along N
+    assert call(round=5) == h.HIF4_ERR_UNSUPPORTED
+    assert call(c_meta=None) == h.HIF4_ERR_NULL
+    assert call(c_codes=None) == h.HIF4_ERR_NULL
+    assert call(c_codes=p + 8) == h.HIF4_ERR_ALIGN
+    assert call(a_kind=h.HIF4_A_HIF4, a_meta=p, ws=None) == h.HIF4_ERR_WORKSPACE
+    assert call(M=0, a=None, c_codes=None, c_meta=None) == h.HIF4_OK

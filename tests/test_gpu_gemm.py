@@ -331,3 +331,68 @@ def test_gemm_many_rows_many_tiles_sampled(h, oracle):
     want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc[cols], wm[cols]))
     got = c[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
     assert rel_fro(got, want) <= TOL, rel_fro(got, want)
+
+
+def test_gemm_equals_fake_quant_linear(h):
+    """The "simulated format" linear layer (quantise, dequantise, then a matrix product of the
+    dequantised BF16 values, as in the paper's accuracy experiments) is what hif4_gemm with activations
+    quantised inside computes: decoded values are exact in BF16, so only the fp32 summation order differs."""
+    M, N, K = 200, 300, 1024
+    g = torch.Generator(device="cuda").manual_seed(3)
+    a = torch.randn((M, K), generator=g, device="cuda").to(torch.bfloat16)
+    w = (torch.randn((N, K), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    wc, wm = h.hif4_quantize(w)
+    a_fq = h.hif4_dequantize(*h.hif4_quantize(a))
+    w_fq = h.hif4_dequantize(wc, wm)
+    want = a_fq.double() @ w_fq.double().T
+    got = h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=h.HIF4_OUT_F32).double()
+    rel = (torch.linalg.norm(got - want) / torch.linalg.norm(want)).item()
+    assert rel <= 1e-5, rel
+
+
+@pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
+@pytest.mark.parametrize("M,N,K,mode", [(1, 64, 64, 0), (300, 320, 512, 0), (257, 576, 192, 1), (70, 1024, 1088, 0)])
+def test_gemm_to_hif4_equals_gemm_then_quantize(h, oracle, kind, M, N, K, mode):
+    """The HiF4-emitting epilogue gives hif4_quantize(BF16 result of hif4_gemm) bit for bit (same products,
+    same summation order, same BF16 rounding, Algorithm 1 with the encoder's arithmetic); the BF16 result
+    and the encoder are each checked against the oracle elsewhere, and here the oracle's encoder is applied
+    to the GPU's BF16 result as well."""
+    print(f"gemm_to_hif4 kind={kind} M={M} N={N} K={K} mode={mode}", flush=True)
+    ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 4242 + M)
+    wcd, wmd = dev_packed(wc, wm)
+    if kind == "keep":
+        a_kind, a_dev, am_dev = h.HIF4_A_BF16_KEEP, synth.from_bits(ab).cuda(), None
+    elif kind == "hif4":
+        a_kind = h.HIF4_A_HIF4
+        a_dev, am_dev = dev_packed(ac, am)
+    else:
+        a_kind, a_dev, am_dev = h.HIF4_A_BF16_QUANTIZE, synth.from_bits(ab).cuda(), None
+    c16 = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_BF16)
+    want_c, want_m = h.hif4_quantize(c16, round_mode=mode)
+    got_c, got_m = h.hif4_gemm_to_hif4(a_kind, a_dev, am_dev, wcd, wmd, round_mode=mode)
+    torch.cuda.synchronize()
+    assert torch.equal(got_m, want_m)
+    assert torch.equal(got_c, want_c)
+    oc, om = oracle.quantize(synth.bits(c16.cpu()), mode)
+    assert (got_c.cpu().numpy() == oc).all() and (got_m.cpu().numpy().view(np.uint32) == om).all()
+
+
+def test_gemm_to_hif4_many_rows_and_k0(h, oracle):
+    """Through the decoded-operand kernel (8192+ rows, large workspace), and the empty sum."""
+    M, N, K = 8192 + 40, 192, 256
+    ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 99)
+    wcd, wmd = dev_packed(wc, wm)
+    acd, amd = dev_packed(ac, am)
+    c16 = h.hif4_gemm(h.HIF4_A_HIF4, acd, amd, wcd, wmd, out_dtype=h.HIF4_OUT_BF16)
+    want_c, want_m = h.hif4_quantize(c16)
+    got_c, got_m = h.hif4_gemm_to_hif4(h.HIF4_A_HIF4, acd, amd, wcd, wmd)
+    assert torch.equal(got_m, want_m) and torch.equal(got_c, want_c)
+    # K == 0: C = 0, the all-zero unit everywhere
+    a0 = torch.empty((5, 0), dtype=torch.uint8, device="cuda")
+    am0 = torch.empty((5, 0), dtype=torch.int32, device="cuda")
+    w0 = torch.empty((128, 0), dtype=torch.uint8, device="cuda")
+    m0 = torch.empty((128, 0), dtype=torch.int32, device="cuda")
+    cc = torch.full((5, 64), 0xAB, dtype=torch.uint8, device="cuda")
+    cm = torch.full((5, 2), -1, dtype=torch.int32, device="cuda")
+    h.hif4_gemm_to_hif4(h.HIF4_A_HIF4, a0, am0, w0, m0, c_codes=cc, c_meta=cm)
+    assert not cc.any() and not cm.any()
