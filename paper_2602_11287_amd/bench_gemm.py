@@ -140,6 +140,19 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
         mfma_leg("gemm_w4a4_quantize_inside_small_workspace_M16384_N28672_K8192", M, N, K,
                  lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws[:small]),
                  tiles)
+        # the result leaving as HiF4 (input of the next layer): epilogue of the same kernel, against the BF16
+        # result followed by a separate encoder pass
+        oc = torch.empty((M, N // 2), dtype=torch.uint8, device=dev)
+        om = torch.empty((M, N // 64), dtype=torch.int32, device=dev)
+        mfma_leg("gemm_w4a4_to_hif4_M16384_N28672_K8192", M, N, K,
+                 lambda: hif4.hif4_gemm_to_hif4(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, c_codes=oc, c_meta=om, workspace=ws),
+                 planes + " (HiF4 epilogue)")
+
+        def two_step():
+            hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws)
+            hif4.hif4_quantize(c, oc, om)
+        mfma_leg("gemm_w4a4_then_quantize_M16384_N28672_K8192", M, N, K, two_step, planes + " + hif4::encode_kernel")
+        del oc, om
         # speed reference on the same shape: CDNA4's native MXFP4 matrix instruction on the same tile kernel
         mc, ms_ = hif4.hif4ref_mxfp4_pack(a)
         wq = hif4.hif4ref_mxfp4_pack(w)
