@@ -32,6 +32,40 @@ __device__ __forceinline__ uint4 expand_chunk(uint32_t c, uint32_t m, uint32_t s
     return r;
 }
 
+// Eq. 2 for 8 consecutive elements: group-of-8 number j of a unit with metadata m,
+// codes dword c (byte t: element t low nibble, element 4+t high nibble) -> 16 bytes of BF16.
+__device__ __forceinline__ uint4 decode_chunk(uint32_t c, uint32_t m, int j)
+{
+    if ((m & 0xFFu) == 0xFFu) return make_uint4(0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u, 0x7FC07FC0u);
+    // value = (4 + M) * mag * 2^(E - 48 - 4 + E1_8 + E1_16): at most 6 significant bits, exact.
+    // (4 + M) * 2^x as an fp32 pattern: exponent x + 2, mantissa M in the top two bits.
+    const uint32_t e8 = (m >> (8 + j)) & 1u;
+    const uint32_t e16a = (m >> (16 + 2 * j)) & 1u, e16b = (m >> (17 + 2 * j)) & 1u;
+    const uint32_t sbase = ((((m >> 2) & 0x3Fu) + (127u - 50u) + e8) << 23) | ((m & 3u) << 21);
+    const float sa = u2f(sbase + (e16a << 23)), sb = u2f(sbase + (e16b << 23));
+    const uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u; // magnitudes of elements 0..3 / 4..7
+    const uint32_t sl = (c << 4) & 0x80808080u, sh = c & 0x80808080u; // their signs, bit 7 of each byte
+    float f[8];
+    f[0] = (float)(lo & 0xFFu) * sa;
+    f[1] = (float)((lo >> 8) & 0xFFu) * sa;
+    f[2] = (float)((lo >> 16) & 0xFFu) * sa;
+    f[3] = (float)(lo >> 24) * sa;
+    f[4] = (float)(hi & 0xFFu) * sb;
+    f[5] = (float)((hi >> 8) & 0xFFu) * sb;
+    f[6] = (float)((hi >> 16) & 0xFFu) * sb;
+    f[7] = (float)(hi >> 24) * sb;
+    uint32_t r[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        // exact values: their BF16 form is the top half of the fp32 pattern
+        const uint32_t pair = __builtin_amdgcn_perm(f2u(f[2 * t + 1]), f2u(f[2 * t]), 0x07060302u);
+        // sign bytes of elements 2t, 2t+1 -> bits 15 and 31
+        const uint32_t sg = __builtin_amdgcn_perm(0u, t < 2 ? sl : sh, (t & 1) ? 0x030C020Cu : 0x010C000Cu);
+        r[t] = pair | sg;
+    }
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
 // The same expansion cut into five pieces, so that the GEMM main loop can place one piece
 // after each MFMA: chunk_begin (masks and the two group scales), then four pairs.
 struct ChunkState {

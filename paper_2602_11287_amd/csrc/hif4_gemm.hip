@@ -469,6 +469,9 @@ int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *
                   hipStream_t stream);
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes, hipStream_t stream);
+int launch_gemm_stream(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N, int64_t K,
+                       void *c, int64_t ldc, int out_dtype, hipStream_t stream);
+constexpr int64_t STREAM_MIN_COLUMNS = 10240;
 int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, uint32_t *c_meta,
                        int64_t ldc, int out_dtype, hipStream_t stream);
 
@@ -558,6 +561,11 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
     }
     if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64 && !emit) { // decode-shaped: stream the weights once
+        // 33 to 64 rows against many columns: columns split over workgroups only, whole K per wave, the
+        // activations shared through LDS (hif4_gemm_stream.hip; measured 100 us against 191 us for
+        // 64 x 28672 x 8192).  With fewer rows or columns the split of K over the waves of a workgroup
+        // below is as fast or faster (both kernels are bound by the expansion arithmetic, not by HBM).
+        if (M > 32 && K % 128 == 0 && N >= STREAM_MIN_COLUMNS) return launch_gemm_stream(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         if (M <= 16) return launch_skinny<1>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         if (M <= 32) return launch_skinny<2>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         return launch_skinny<4>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);

@@ -396,3 +396,37 @@ def test_gemm_to_hif4_many_rows_and_k0(h, oracle):
     cm = torch.full((5, 2), -1, dtype=torch.int32, device="cuda")
     h.hif4_gemm_to_hif4(h.HIF4_A_HIF4, a0, am0, w0, m0, c_codes=cc, c_meta=cm)
     assert not cc.any() and not cm.any()
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 10240, 1024), (33, 10250, 2048 + 128), (48, 12000, 512), (40, 16384, 128),
+                                   (16, 8192, 4096), (64, 10240, 192)])
+def test_gemm_weight_only_wide_weights(h, oracle, M, N, K):
+    """33 to 64 rows against 10240 or more columns, K a multiple of 128: the column-split kernel, whole K per
+    wave, activations through LDS by direct loads.  (The last two shapes stay on the other kernel.)"""
+    print(f"weight-only streaming M={M} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(M * 7 + N)
+    a = synth.to_bf16(rng.standard_normal((M, K)))
+    w = synth.weight_gaussian(N, K, 0.02, config=2, tensor=3 + M, channel_scale=True)
+    wc, wm = oracle.quantize(synth.bits(w))
+    # a NaN unit and an all-zero unit in the weights, a subnormal activation
+    wm[3, 1] = 0xFF
+    wc[3, 32:64] = 0
+    wm[5, 0] = 0
+    wc[5, :32] = 0
+    ab = synth.bits(a).copy()
+    ab[M - 1, K - 1] = 0x0001
+    want = oracle.gemm_f64(ab, oracle.dequantize(wc, wm))
+    wcd, wmd = dev_packed(wc, wm)
+    ad = synth.from_bits(ab).cuda()
+    c32 = h.hif4_gemm(h.HIF4_A_BF16_KEEP, ad, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    c16 = h.hif4_gemm(h.HIF4_A_BF16_KEEP, ad, None, wcd, wmd, out_dtype=h.HIF4_OUT_BF16)
+    torch.cuda.synchronize()
+    got = c32.cpu().numpy().astype(np.float64)
+    nan = np.isnan(want)
+    assert nan[:, 3].all() and (np.isnan(got) == nan).all()
+    assert rel_fro(got[~nan], want[~nan]) <= TOL, rel_fro(got[~nan], want[~nan])
+    # BF16 output: one BF16 ulp of the exact value, plus the fp32 summation error, which matters for the few
+    # of the 100 000+ sums that cancel to almost nothing
+    g16 = c16.double().cpu().numpy()
+    ok = np.abs(g16[~nan] - want[~nan]) <= 2.0 ** -8 * np.abs(want[~nan]) + 1e-5 * np.abs(want[~nan]).max()
+    assert ok.all()
