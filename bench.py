@@ -139,6 +139,13 @@ def main():
                      "algorithmic_bytes": bytes_dir, "traffic": MEASURED_TRAFFIC_BYTES[dom[0]]},
     }
 
+    # ---- what a plain device-to-device copy of the same batch sustains (read 512 MiB, write 512 MiB): the
+    # practical ceiling of streaming kernels on this machine, next to the 8 TB/s the fractions are quoted against
+    copy_ms = timed(lambda: y.copy_(x), args.steps)
+    out["legs"]["reference_device_copy_512MiB"] = {"ms": round(copy_ms, 4), "GBps": round(2 * x.numel() * 2 / copy_ms / 1e6, 1),
+                                                   "pct_hbm_peak": round(100 * 2 * x.numel() * 2 / copy_ms / 1e6 / HBM_PEAK_GBPS, 1)}
+    hif4.hif4_dequantize(codes, meta, y)   # y holds the decoded batch again (checked below)
+
     # ---- encoder fed with FP32 (256 B of input + 36 B of packed unit): an eighth of the batch
     x32 = x[:rows // 8].float()
     u32 = x32.shape[0] * K // 64

@@ -430,3 +430,30 @@ def test_gemm_weight_only_wide_weights(h, oracle, M, N, K):
     g16 = c16.double().cpu().numpy()
     ok = np.abs(g16[~nan] - want[~nan]) <= 2.0 ** -8 * np.abs(want[~nan]) + 1e-5 * np.abs(want[~nan]).max()
     assert ok.all()
+
+
+def test_grouped_gemm_many_experts(h, oracle):
+    """More experts than lanes of a wave (the search for an m-tile's expert runs 64 experts at a time),
+    many of them empty, sizes from 0 to 300 rows."""
+    rng = np.random.default_rng(21)
+    E, N, K = 150, 96, 128
+    counts = rng.choice([0, 0, 1, 3, 40, 128, 129, 256, 300], size=E)
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    M = int(offs[-1])
+    print(f"grouped gemm E={E} rows={M}", flush=True)
+    ab, (ac, am), _ = quantized_operands(oracle, M, 8, K, 5)
+    w = synth.to_bf16(rng.standard_normal((E * N, K)) * 0.02)
+    wc, wm = oracle.quantize(synth.bits(w))
+    adec, wdec = oracle.dequantize(ac, am), oracle.dequantize(wc, wm)
+    want = np.zeros((M, N))
+    for e in range(E):
+        lo, hi = offs[e], offs[e + 1]
+        if hi > lo:
+            want[lo:hi] = oracle.gemm_f64(adec[lo:hi], wdec[e * N:(e + 1) * N])
+    acd, amd = dev_packed(ac, am)
+    wcd, wmd = dev_packed(wc, wm)
+    c = h.hif4_grouped_gemm(h.HIF4_A_HIF4, acd, amd, wcd.view(E, N, K // 2), wmd.view(E, N, K // 64),
+                            torch.from_numpy(offs).cuda(), out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    got = c.cpu().numpy().astype(np.float64)
+    assert rel_fro(got, want) <= TOL, rel_fro(got, want)
