@@ -457,3 +457,23 @@ def test_grouped_gemm_many_experts(h, oracle):
     torch.cuda.synchronize()
     got = c.cpu().numpy().astype(np.float64)
     assert rel_fro(got, want) <= TOL, rel_fro(got, want)
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 272, 256), (40, 10240, 256)])
+def test_gemm_weight_only_strided_rows(h, oracle, M, N, K):
+    """Row strides larger than the row length for A and C in the two few-row kernels; nothing is written
+    between the rows of C."""
+    rng = np.random.default_rng(M + N)
+    a = synth.to_bf16(rng.standard_normal((M, K)))
+    w = synth.to_bf16(rng.standard_normal((N, K)) * 0.02)
+    wc, wm = oracle.quantize(synth.bits(w))
+    wcd, wmd = dev_packed(wc, wm)
+    abuf = torch.full((M, K + 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    abuf[:, :K] = a.cuda()
+    cbuf = torch.full((M, N + 24), -1.0, dtype=torch.float32, device="cuda")
+    h.hif4_gemm(h.HIF4_A_BF16_KEEP, abuf[:, :K], None, wcd, wmd, out_dtype=h.HIF4_OUT_F32, c=cbuf[:, :N])
+    c = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a.cuda(), None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    assert torch.equal(cbuf[:, :N], c) and (cbuf[:, N:] == -1.0).all()
+    want = oracle.gemm_f64(synth.bits(a), oracle.dequantize(wc, wm))
+    assert rel_fro(c.cpu().numpy().astype(np.float64), want) <= TOL
