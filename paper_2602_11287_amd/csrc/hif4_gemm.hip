@@ -467,6 +467,7 @@ __global__ void zero_kernel(void *c, int64_t M, int64_t N, int64_t ldc, int elem
 
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream);
+int launch_encode_to_cells(const void *x, int64_t rows, int64_t K, int64_t ldx, void *cells, int mode, hipStream_t stream);
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes, hipStream_t stream);
 int launch_gemm_stream(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N, int64_t K,
@@ -581,27 +582,35 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         a_cell = false;
     } else {
         uint8_t *ws = static_cast<uint8_t *>(workspace);
-        const uint8_t *codes = static_cast<const uint8_t *>(a);
-        const uint32_t *meta = a_meta;
-        if (a_kind == HIF4_A_BF16_QUANTIZE) {
-            uint8_t *qc = ws;
-            uint32_t *qm = reinterpret_cast<uint32_t *>(ws + align16((size_t)M * (size_t)K / 2));
-            if (int rc = launch_encode(a, M, K, lda, qc, qm, HIF4_ROUND_RNE, stream)) return rc;
-            ws = reinterpret_cast<uint8_t *>(qm) + align16((size_t)M * (size_t)(K / 64) * 4);
-            codes = qc;
-            meta = qm;
-        }
         const size_t base = align16(gemm_workspace_bytes(a_kind, M, K));
-        if (!offs && M >= DECODED_W_MIN_ROWS && workspace_bytes >= base + (size_t)N * (size_t)K * 2) {
+        const bool planes = !offs && M >= DECODED_W_MIN_ROWS && workspace_bytes >= base + (size_t)N * (size_t)K * 2;
+        // the decoded copy of A sits behind the room for its packed planes (HIF4_A_BF16_QUANTIZE)
+        uint8_t *adec = a_kind == HIF4_A_BF16_QUANTIZE
+                            ? ws + align16((size_t)M * (size_t)K / 2) + align16((size_t)M * (size_t)(K / 64) * 4)
+                            : ws;
+        if (planes) {
             // room for a decoded copy of W and enough rows for it to pay: both operands as
             // cell planes, main loop without any expansion
-            uint8_t *wplanes = static_cast<uint8_t *>(workspace) + base;
-            if (int rc = launch_decode_planes(codes, meta, M, K, ws, stream)) return rc;
+            const uint8_t *codes = static_cast<const uint8_t *>(a);
+            const uint32_t *meta = a_meta;
+            if (a_kind == HIF4_A_BF16_QUANTIZE) {
+                uint32_t *qm = reinterpret_cast<uint32_t *>(ws + align16((size_t)M * (size_t)K / 2));
+                if (int rc = launch_encode(a, M, K, lda, ws, qm, HIF4_ROUND_RNE, stream)) return rc;
+                codes = ws;
+                meta = qm;
+            }
+            uint8_t *wplanes = ws + base;
+            if (int rc = launch_decode_planes(codes, meta, M, K, adec, stream)) return rc;
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
-            return launch_gemm_planes(ws, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
+            return launch_gemm_planes(adec, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
-        if (int rc = launch_decode_cells(codes, meta, M, K, ws, stream)) return rc;
-        g.a = reinterpret_cast<const uint16_t *>(ws);
+        if (a_kind == HIF4_A_BF16_QUANTIZE) {
+            // quantise and decode in one pass: the packed activations are never needed in memory
+            if (int rc = launch_encode_to_cells(a, M, K, lda, adec, HIF4_ROUND_RNE, stream)) return rc;
+        } else {
+            if (int rc = launch_decode_cells(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
+        }
+        g.a = reinterpret_cast<const uint16_t *>(adec);
         g.lda = K;
     }
     g.w_codes = reinterpret_cast<const uint32_t *>(w_codes);

@@ -4,9 +4,10 @@
 // Why a second path: inside the tile kernel of hif4_gemm.hip every unit of W is expanded by
 // each of the M / 256 tiles of C that use it.  With many thousands of rows that repeated VALU
 // work (it lowers the clock the matrix pipeline runs at) costs more than decoding W once (2.56
-// bytes of traffic per weight), so here the exact BF16 values of A and of W (Eq. 2 of the HiF4 paper, Section II-A; at most six significant
-// bits each) are written to the workspace first and the main loop is a plain BF16 GEMM whose
-// partial sums are those of Eq. 4 (Section III-B) per 64-wide K step, accumulated in fp32.
+// bytes of traffic per weight), so here the exact BF16 values of A and of W (Eq. 2 of the HiF4
+// paper, Section II-A; at most six significant bits each) are written to the workspace first
+// and the main loop is a plain BF16 GEMM whose partial sums are those of Eq. 4 (Section III-B)
+// per 64-wide K step, accumulated in fp32.
 //
 // Layout of a decoded copy ("cell planes"): one 16-byte cell holds the 8 values of one group of
 // 8 along K in the order 0,2,1,3,4,6,5,7 (expand_chunk); cell (row, group g) sits at index

@@ -126,6 +126,55 @@ __global__ __launch_bounds__(256) void encode_kernel(const void *__restrict__ x,
     }
 }
 
+// Quantise-dequantise in one pass for the GEMM that converts its activations itself: the same
+// loads and the same Algorithm 1 as encode_kernel, but what is stored is the exact BF16 value of
+// every element of the resulting unit (Eq. 2), 8 per 16-byte cell in the cell order of the tile
+// GEMM, dense rows.  The packed unit never goes to memory.
+template <int MODE, bool CONTIG>
+__global__ __launch_bounds__(256) void encode_to_cells_kernel(const void *__restrict__ x, int64_t units, int64_t upr,
+                                                              int64_t ldx, uint4 *__restrict__ cells)
+{
+    constexpr int LPU = 4, NCH = 2;
+    const int l = (int)(threadIdx.x % LPU);
+    const int64_t u = (int64_t)blockIdx.x * (256 / LPU) + threadIdx.x / LPU;
+    const bool live = u < units;
+    const int64_t unit = live ? u : units - 1; // dead lanes redo the last unit and store nothing
+    int64_t e0;
+    if (CONTIG) {
+        e0 = unit * 64;
+    } else {
+        const int64_t row = unit / upr;
+        e0 = row * ldx + (unit - row * upr) * 64;
+    }
+    uint4 w[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) w[c] = load_chunk<IN_BF16, MODE, false>(x, e0 + 8 * (c * LPU + l));
+    uint32_t out[NCH];
+    const uint32_t m = encode_share<LPU, MODE>(w, l, out);
+    const uint32_t sbase = unit_scale_bits(m);
+    if (live) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) cells[unit * 8 + c * LPU + l] = expand_chunk(out[c], m, sbase, c * LPU + l);
+    }
+}
+
+int launch_encode_to_cells(const void *x, int64_t rows, int64_t K, int64_t ldx, void *cells, int mode, hipStream_t stream)
+{
+    const int64_t upr = K / 64, units = rows * upr;
+    if (units == 0) return HIF4_OK;
+    const dim3 grid((unsigned)((units + 63) / 64)), block(256);
+    uint4 *y = static_cast<uint4 *>(cells);
+    const bool contig = ldx == K;
+    if (mode == HIF4_ROUND_RNE) {
+        if (contig) hipLaunchKernelGGL((encode_to_cells_kernel<HIF4_ROUND_RNE, true>), grid, block, 0, stream, x, units, upr, ldx, y);
+        else hipLaunchKernelGGL((encode_to_cells_kernel<HIF4_ROUND_RNE, false>), grid, block, 0, stream, x, units, upr, ldx, y);
+    } else {
+        if (contig) hipLaunchKernelGGL((encode_to_cells_kernel<HIF4_ROUND_RHA, true>), grid, block, 0, stream, x, units, upr, ldx, y);
+        else hipLaunchKernelGGL((encode_to_cells_kernel<HIF4_ROUND_RHA, false>), grid, block, 0, stream, x, units, upr, ldx, y);
+    }
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
 // ------------------------------------------------------------------ decoder
 
 // One lane decodes CPT chunks of 8 elements; block b owns chunks [b*256*CPT, (b+1)*256*CPT).
