@@ -205,7 +205,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
         }
     };
     // MFMA number tm of quarter q (of the step whose scales are sc) on operand set fb
-    auto mfma = [&](int fb, int tm, int q, const Scales &sc) {
+    auto mfma = [&](int fb, int tm, [[maybe_unused]] int q, [[maybe_unused]] const Scales &sc) {
         f32x16_t &d = acc[tm / TN][tm % TN];
         const uint4 a = af[fb][tm / TN], b = bfr[fb][tm % TN];
         if constexpr (MX) {
