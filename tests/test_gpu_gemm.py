@@ -477,3 +477,43 @@ def test_gemm_weight_only_strided_rows(h, oracle, M, N, K):
     assert torch.equal(cbuf[:, :N], c) and (cbuf[:, N:] == -1.0).all()
     want = oracle.gemm_f64(synth.bits(a), oracle.dequantize(wc, wm))
     assert rel_fro(c.cpu().numpy().astype(np.float64), want) <= TOL
+
+
+def test_gemm_large_prefill_config_sampled(h, oracle):
+    """M=16384, N=28672, K=8192 (the large prefill configuration, as the benchmark launches it: activations
+    quantised inside the call, large workspace): a seeded sample of rows x columns against the oracle, and
+    the same call with the result leaving as HiF4 against the oracle's encoder on sampled rows."""
+    M, N, K = 16384, 28672, 8192
+    print(f"gemm sampled M={M} N={N} K={K}", flush=True)
+    dev = torch.device("cuda")
+    g = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 5)
+    a = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    for r in range(0, M, 4096):   # Student-t(4) scaled to unit variance
+        z = torch.randn((4096, K), generator=g, device=dev)
+        chi = torch.randn((4, 4096, K), generator=g, device=dev).pow(2).sum(0)
+        a[r:r + 4096] = (z / torch.sqrt(chi / 4.0) / np.sqrt(2.0)).to(torch.bfloat16)
+    del z, chi
+    w = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+    for r in range(0, N, 7168):
+        w[r:r + 7168] = (torch.randn((7168, K), generator=g, device=dev) * 0.015).to(torch.bfloat16)
+    wcd, wmd = h.hif4_quantize(w)
+    ws = torch.empty(h.hif4_gemm_workspace_bytes_decoded_w(h.HIF4_A_BF16_QUANTIZE, M, N, K), dtype=torch.uint8, device=dev)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_BF16, c=c, workspace=ws)
+    oc, om = h.hif4_gemm_to_hif4(h.HIF4_A_BF16_QUANTIZE, a, None, wcd, wmd, workspace=ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(55)
+    rows = np.sort(np.concatenate([rng.choice(M, 62, replace=False), [0, M - 1]]))
+    cols = np.sort(np.concatenate([rng.choice(N, 126, replace=False), [0, N - 1]]))
+    ri, ci = torch.from_numpy(rows).to(dev), torch.from_numpy(cols).to(dev)
+    # operands of the sample through the oracle: its own encoder on the sampled rows of A and of W
+    ac, am = oracle.quantize(synth.bits(a[ri].cpu()))
+    wc, wm = oracle.quantize(synth.bits(w[ci].cpu()))
+    assert (wcd[ci].cpu().numpy() == wc).all() and (wmd[ci].cpu().numpy().view(np.uint32) == wm).all()
+    want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc, wm))
+    got = c[ri][:, ci].double().cpu().numpy()
+    # BF16 output: one BF16 ulp of the exact value plus the fp32 summation error
+    assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-5 * np.abs(want).max()).all()
+    # HiF4 output of whole sampled rows: the oracle's encoder applied to the GPU's BF16 rows
+    ec, em = oracle.quantize(synth.bits(c[ri].cpu()))
+    assert (oc[ri].cpu().numpy() == ec).all() and (om[ri].cpu().numpy().view(np.uint32) == em).all()
