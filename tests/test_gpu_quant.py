@@ -210,3 +210,25 @@ def test_encode_from_strided_and_bf16(h, oracle):
     c1, m1 = h.hif4_quantize_from(xb)
     c2, m2 = h.hif4_quantize(xb)
     assert torch.equal(c1, c2) and torch.equal(m1, m2)
+
+
+def test_encode_decode_beyond_2_to_32_elements(h, oracle):
+    """A matrix of more than 2^32 elements (8.6 GB of BF16): element and byte offsets need 64 bits.
+    Rows from the start, the middle and the very end against the oracle."""
+    rows, K = (1 << 20) + 4096 + 3, 4096
+    print(f"encode/decode rows={rows} K={K}", flush=True)
+    g = torch.Generator(device="cuda").manual_seed(77)
+    x = torch.empty((rows, K), dtype=torch.bfloat16, device="cuda")
+    step = 1 << 16
+    for r in range(0, rows, step):
+        n = min(step, rows - r)
+        x[r:r + n] = (torch.randn((n, K), generator=g, device="cuda") * (1.0 + (r >> 16) % 7)).to(torch.bfloat16)
+    codes, meta = h.hif4_quantize(x)
+    y = h.hif4_dequantize(codes, meta)
+    torch.cuda.synchronize()
+    pick = np.array([0, 1, 524287, 524288, (1 << 20) - 1, 1 << 20, rows - 2, rows - 1])
+    pi = torch.from_numpy(pick).cuda()
+    wc, wm = oracle.quantize(synth.bits(x[pi].cpu()))
+    assert (codes[pi].cpu().numpy() == wc).all()
+    assert (meta[pi].cpu().numpy().view(np.uint32) == wm).all()
+    assert (synth.bits(y[pi].cpu()) == oracle.dequantize(wc, wm)).all()
