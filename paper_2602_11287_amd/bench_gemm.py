@@ -6,6 +6,15 @@ import numpy as np
 import torch
 
 
+# HBM bytes per launch of the GEMM kernel itself on the large shape, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (FETCH_SIZE x 1.99988, WRITE_SIZE x 1.0, the factors of a plain device copy): profiles/gemm_kernels_configs2-5.md
+_LARGE_TRAFFIC = {
+    "gemm_w4a4_quantize_inside_M16384_N28672_K8192": int((5506528.5 * 1.99988 + 926695.9) * 1024),
+    "gemm_w4a4_quantize_inside_small_workspace_M16384_N28672_K8192": int((2867353.1 * 1.99988 + 930192.4) * 1024),
+    "gemm_w4a4_to_hif4_M16384_N28672_K8192": int((5512739.1 * 1.99988 + 258048.0) * 1024),
+}
+
+
 def _timed(fn, n):
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -75,7 +84,8 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
         legs[name] = {"ms": round(ms, 4), "TFLOPs": round(tf, 1),
                       "roofline": {"bound": "mfma", "kernel": kernel, "achieved": round(tf, 1), "peak": mfma_peak_tflops,
                                    "unit": "TFLOP/s", "frac": round(tf / mfma_peak_tflops, 4),
-                                   "frac_of_mfma_only_loop": round(tf / bf16_ceiling, 4), "traffic": None}}
+                                   "frac_of_mfma_only_loop": round(tf / bf16_ceiling, 4),
+                                   "traffic": _LARGE_TRAFFIC.get(name)}}
 
     # ---- W4A4 prefill: M=4096, N=11008, K=4096, activations quantised inside the call
     M, N, K = 4096, 11008, 4096
