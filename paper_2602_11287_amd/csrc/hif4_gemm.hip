@@ -22,6 +22,7 @@
 // reads of a wave touch consecutive 16-byte cells.
 #include "hif4_emit.h"
 #include "hif4_expand.h"
+#include "hif4_grouped.h"
 
 #ifndef HIF4_GEMM_SCHED
 #define HIF4_GEMM_SCHED 1
@@ -91,41 +92,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_kernel(GemmArgs g)
         if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return; // padding of the super-tile grid
     }
     if (GROUPED) {
-        // Find the expert whose tiles contain m-tile number tile_m.  Every wave does the same
-        // search, 64 experts at a time: row
-        // counts from the device-side offsets, an inclusive scan of their tile counts across the
-        // lanes, a ballot for the first lane whose running count passes tile_m.
-        int e = -1;
-        row0 = 0;
-        rows_end = 0;
-        for (int base = 0, acc = 0; base < g.E; base += 64) {
-            const int ee = base + lane;
-            int lo = 0, hi = 0;
-            if (ee < g.E) {
-                lo = g.offs[ee];
-                hi = g.offs[ee + 1];
-            }
-            const int rows = hi - lo;
-            const int nt = (rows + BM - 1) / BM;
-            int incl = nt;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int v = __shfl_up(incl, d, 64);
-                if (lane >= d) incl += v;
-            }
-            const int total = __shfl(incl, 63, 64);
-            if (tile_m < acc + total) {
-                const int src = __ffsll((unsigned long long)__ballot(acc + incl > tile_m)) - 1;
-                e = base + src;
-                const int before = acc + __shfl(incl - nt, src, 64); // tiles of the experts ahead of e
-                row0 = __builtin_amdgcn_readfirstlane(__shfl(lo, src, 64) + (tile_m - before) * BM);
-                rows_end = __builtin_amdgcn_readfirstlane(__shfl(hi, src, 64));
-                break;
-            }
-            acc += total;
-        }
-        if (e < 0) return; // grid is an upper bound on the number of tiles
-        e = __builtin_amdgcn_readfirstlane(e);
+        int e;
+        if (!find_expert_tile<BM>(g.offs, g.E, tile_m, lane, e, row0, rows_end)) return;
         w_codes += (int64_t)e * g.N * (g.K / 8);
         w_meta += (int64_t)e * g.N * (g.K / 64);
     } else {
@@ -476,6 +444,11 @@ constexpr int64_t STREAM_MIN_COLUMNS = 10240;
 int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, uint32_t *c_meta,
                        int64_t ldc, int out_dtype, hipStream_t stream);
 
+bool colwave_fits(int64_t M, int64_t N, int64_t K);
+int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint32_t *w_meta, const int32_t *offs, int E,
+                        int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype, int rows_per_tile,
+                        hipStream_t stream);
+
 // Internal output kinds beyond HIF4_OUT_BF16 / HIF4_OUT_F32: the result as HiF4 (c = codes plane, c_meta).
 enum { OUT_HIF4_RNE = 16, OUT_HIF4_RHA = 17 };
 
@@ -544,6 +517,24 @@ size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t 
     return align16(base) + (size_t)N * (size_t)K * 2;
 }
 
+// A dense call between HiF4 operands with at most this many rows is one m-tile of that kernel.
+#ifndef HIF4_COLWAVE_MAX_ROWS
+#define HIF4_COLWAVE_MAX_ROWS 192
+#endif
+constexpr int64_t COLWAVE_MAX_ROWS = HIF4_COLWAVE_MAX_ROWS;
+#ifndef HIF4_COLWAVE_ROWS
+#define HIF4_COLWAVE_ROWS -1
+#endif
+// Rows of A per workgroup for the grouped kernel of hif4_gemm_colwave.hip, from the mean number of
+// rows per expert (the counts themselves live on the device): an expert should fit one m-tile, so that
+// its weights are expanded once, with room for the spread of a random routing.  0: use the tile kernel.
+static int colwave_rows(int64_t M, int E)
+{
+    if (HIF4_COLWAVE_ROWS >= 0) return HIF4_COLWAVE_ROWS;
+    const int64_t want = M / (E > 0 ? E : 1) * 11 / 8 + 8;
+    return want <= 64 ? 64 : want <= 128 ? 128 : want <= 192 ? 192 : 256;
+}
+
 // out_dtype: HIF4_OUT_BF16, HIF4_OUT_F32, or 16 + rounding mode for a HiF4 result (c = codes plane, c_meta = its
 // metadata plane, ldc unused; dense calls only).
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
@@ -603,6 +594,21 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (int rc = launch_decode_planes(codes, meta, M, K, adec, stream)) return rc;
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
             return launch_gemm_planes(adec, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
+        }
+        if ((offs ? colwave_rows(M, E) > 0 : M <= COLWAVE_MAX_ROWS) && colwave_fits(M, N, K) && !emit) {
+            // grouped, or so few rows that there is one m-tile: every weight meets those few rows only,
+            // so the kernel that expands W straight into MFMA operands takes the call
+            // (hif4_gemm_colwave.hip); A as cell planes
+            const uint8_t *codes = static_cast<const uint8_t *>(a);
+            const uint32_t *meta = a_meta;
+            if (a_kind == HIF4_A_BF16_QUANTIZE) {
+                uint32_t *qm = reinterpret_cast<uint32_t *>(ws + align16((size_t)M * (size_t)K / 2));
+                if (int rc = launch_encode(a, M, K, lda, ws, qm, HIF4_ROUND_RNE, stream)) return rc;
+                codes = ws;
+                meta = qm;
+            }
+            if (int rc = launch_decode_planes(codes, meta, M, K, adec, stream)) return rc;
+            return launch_gemm_colwave(adec, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : (int)M, stream);
         }
         if (a_kind == HIF4_A_BF16_QUANTIZE) {
             // quantise and decode in one pass: the packed activations are never needed in memory

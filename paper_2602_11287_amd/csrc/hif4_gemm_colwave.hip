@@ -1,0 +1,357 @@
+// HiF4 GEMM for tiles with few rows and many weights per row of A: the grouped (per-expert)
+// GEMM, where an expert's rows meet its whole weight matrix once.  C = A * W^T per expert, A as
+// exact BF16 values (decoded HiF4), W packed HiF4; each 64-wide K step of an output is the
+// unit dot product of Eq. 4 of the HiF4 paper (Section III-B), accumulated in fp32 on
+// v_mfma_f32_32x32x16_bf16.
+//
+// The work that counts here is expanding W (Eq. 2, Section II-A): every weight is used by the
+// few rows of one expert only, so the expansion cannot be amortised over many tiles as in the
+// dense kernels.  Hence the shape: a workgroup owns up to BM = 32 TMAX rows (a whole expert, if
+// it fits) and 256 columns; each of its 8 waves owns 32 of those columns over the whole of K
+// and expands their weights straight into the B operand registers of its MFMAs - every weight
+// is expanded once per m-tile, by one lane, and never passes through LDS as BF16.  The rows of
+// A are the same for all waves: a K step of them sits in LDS, [group of 8][row], brought in by
+// direct global -> LDS loads from the decoded copy of A ("cell planes", see hif4_gemm_cells.hip:
+// the 64 rows a wave moves at once are contiguous in memory) three steps ahead.  The packed
+// weights of a wave go through LDS as well, as bytes, lane-private: a ring of R steps filled by
+// the same kind of load, 16 bytes of codes and the metadata word per lane and step.  So every
+// global load of the loop is an LDS-writing one with a fixed count per wave and step, and one
+// s_waitcnt vmcnt(N) per step covers exactly the loads that step needs.
+//
+// K order: sub-step s (of 4, a K slab of 16) takes group 4 h + s of a unit's 8 groups of 8
+// from lane half h, for both operands, so a lane's 4 dwords of codes per unit are contiguous.
+// A K step of a wave: for each sub-step, up to TMAX MFMAs (one per 32-row block that has rows),
+// each followed by one slice of the expansion of the next sub-step's weights and by the LDS
+// read of that block's next A operand.  The step boundary (wait, barrier, loads of the step
+// three ahead) lies before the last sub-step, whose slices already belong to the next unit.
+#include <type_traits>
+
+#include "hif4_expand.h"
+#include "hif4_grouped.h"
+
+namespace hif4 {
+
+// LDS-writing loads (see hif4_gemm_cells.hip for why they are inline assembly: the compiler's
+// wait-count pass must not see them; the kernel counts them itself).  Address = 64-bit scalar base
+// + 32-bit byte offset per lane; lane l lands at lds_byte + 16 l (or + 4 l); lds_byte is wave-uniform.
+__device__ __forceinline__ uint64_t cw_uniform(uint64_t v) // a wave-uniform value, in scalar registers
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v), hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ void cw_load_to_lds_16(uint64_t base, uint32_t off, uint32_t lds_byte)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory");
+}
+__device__ __forceinline__ void cw_load_to_lds_4(uint64_t base, uint32_t off, uint32_t lds_byte)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory");
+}
+
+struct ColwaveArgs {
+    const uint4 *a_planes;   // decoded A: cell (row, group g of 8 along K) at g * M + row
+    const uint32_t *w_codes; // [E][N][K/8] dwords
+    const uint32_t *w_meta;  // [E][N][K/64]
+    const int32_t *offs;     // device int32[E+1], or nullptr: one matrix W for all M rows
+    void *c;
+    int64_t ldc;
+    int M, N, K, E;
+    int tiles_m, tiles_n;
+};
+
+// NW waves per workgroup (32 columns each), NB buffers of A, a ring of R steps of packed W.
+template <int NW, int NB, int R>
+struct ColwaveShape {
+    static constexpr size_t lds_bytes(int tmax)
+    {
+        const int rg = (32 * tmax + 63) / 64;
+        return (size_t)NB * 8 * 64 * rg * 16 + (size_t)R * NW * 64 * (16 + 4);
+    }
+};
+
+template <int TMAX, int NW, int NB, int R, int WPS, bool OUT_F32>
+__global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs g)
+{
+    constexpr int BM = 32 * TMAX, BN = 32 * NW;
+    constexpr int RG = (BM + 63) / 64;       // 64-row groups of a tile
+    constexpr int BMP = 64 * RG;             // rows of a buffer
+    constexpr int A_CELLS = 8 * BMP;         // cells per A buffer
+    constexpr int IA = (8 * RG + NW - 1) / NW; // A loads per wave and step
+    constexpr int PER_STEP = IA + 2;         // LDS-writing loads per wave and step
+    static_assert(R > NB && NB >= 2, "W(k + 1) must be older than A(k + 1)");
+    extern __shared__ uint4 lds[];
+    uint4 *lds_a = lds;                                  // [NB][8][BMP]
+    uint4 *lds_wc = lds + NB * A_CELLS;                  // [R][NW][64]
+    uint32_t *lds_wm = reinterpret_cast<uint32_t *>(lds_wc + R * NW * 64); // [R][NW][64]
+
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int half = lane / 32, l32 = lane % 32;
+
+    // ---- which tile: m-tiles are dealt to the 8 XCDs round-robin (block b runs on XCD b % 8), all
+    // n-tiles of an m-tile on one XCD, whose L2 then serves their common rows of A
+    // (with fewer than 8 m-tiles the n-tiles of one are spread over the XCDs instead)
+    const int bi = (int)(blockIdx.x / 8);
+    const bool deal_m = g.tiles_m >= 8;
+    const int tile_m = deal_m ? (bi / g.tiles_n) * 8 + (int)(blockIdx.x % 8) : (int)blockIdx.x / g.tiles_n;
+    const int tile_n = deal_m ? bi % g.tiles_n : (int)blockIdx.x % g.tiles_n;
+    if (tile_m >= g.tiles_m) return;
+    int row0, rows_end;
+    const uint32_t *w_codes = g.w_codes, *w_meta = g.w_meta;
+    if (g.offs) {
+        int e;
+        if (!find_expert_tile<BM>(g.offs, g.E, tile_m, lane, e, row0, rows_end)) return;
+        w_codes += (int64_t)e * g.N * (g.K / 8);
+        w_meta += (int64_t)e * g.N * (g.K / 64);
+    } else {
+        row0 = tile_m * BM;
+        rows_end = g.M;
+    }
+    const int col0 = tile_n * BN;
+    const int nk = g.K / 64;
+    // 32-row blocks of this tile that have rows
+    int live = (rows_end - row0 + 31) / 32;
+    live = __builtin_amdgcn_readfirstlane(live < TMAX ? live : TMAX);
+
+    // ---- load plan.  W: lane (n, h) = (l32, half) takes the 16 bytes of codes [16 h, 16 h + 16)
+    // of each unit of weight row col0 + 32 wave + n, and the unit's metadata word.  A: load
+    // id = wave * IA + i moves cell j = id / RG of rows rg * 64 .. + 63 (rg = id % RG); rows past the
+    // end of the matrix repeat its last row, loads past 8 RG repeat the last one (never read).
+    // Every address is a scalar base that moves with the K step plus a fixed 32-bit offset per lane
+    // (the host keeps the operands small enough for that).
+    int wrow = col0 + wave * 32 + l32;
+    wrow = wrow < g.N ? wrow : g.N - 1;
+    const uint32_t wc_off = (uint32_t)wrow * (uint32_t)(g.K / 2) + 16u * half;
+    const uint32_t wm_off = (uint32_t)wrow * (uint32_t)(nk * 4);
+    uint32_t a_off[IA], a_dst[IA];
+#pragma unroll
+    for (int i = 0; i < IA; ++i) {
+        int id = wave * IA + i;
+        id = id < 8 * RG ? id : 8 * RG - 1;
+        const int j = id / RG, rg = id % RG;
+        int row = row0 + rg * 64 + lane;
+        row = row < g.M ? row : g.M - 1;
+        a_off[i] = ((uint32_t)j * (uint32_t)g.M + (uint32_t)row) * 16u;
+        a_dst[i] = (uint32_t)__builtin_amdgcn_readfirstlane((j * BMP + rg * 64) * 16);
+    }
+    auto lds_byte_of = [](const void *p) { return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p; };
+    const uint32_t a_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_a));
+    const uint32_t wc_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_wc)) + (uint32_t)(wave * 64 * 16);
+    const uint32_t wm_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_wm)) + (uint32_t)(wave * 64 * 4);
+    const uint64_t a_step = (uint64_t)g.M * 128; // bytes of A planes per K step
+    const uint64_t wc_ptr = cw_uniform((uint64_t)(uintptr_t)w_codes), wm_ptr = cw_uniform((uint64_t)(uintptr_t)w_meta);
+    const uint64_t a_ptr = cw_uniform((uint64_t)(uintptr_t)g.a_planes);
+    // the loads of unit u into ring slot / buffer number `at`: steps past the end of K repeat the last one (never used)
+    auto issue_w = [&](int u, int at) {
+        const uint64_t uc = (uint64_t)(u < nk ? u : nk - 1);
+        cw_load_to_lds_16(wc_ptr + uc * 32, wc_off, wc_base + (uint32_t)(at * NW * 64 * 16));
+        cw_load_to_lds_4(wm_ptr + uc * 4, wm_off, wm_base + (uint32_t)(at * NW * 64 * 4));
+    };
+    auto issue_a = [&](int u, int at) {
+        const uint64_t base = a_ptr + (uint64_t)(u < nk ? u : nk - 1) * a_step;
+#pragma unroll
+        for (int i = 0; i < IA; ++i) cw_load_to_lds_16(base, a_off[i], a_base + (uint32_t)(at * A_CELLS * 16) + a_dst[i]);
+    };
+
+    f32x16_t acc[TMAX];
+#pragma unroll
+    for (int i = 0; i < TMAX; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+
+    // ---- the packed weights of the unit being expanded, as this lane needs them
+    struct UnitW {
+        uint32_t c[4];   // codes dwords 4 h .. 4 h + 3
+        uint32_t m8, m16; // the unit's level-2 and level-3 bits, shifted so that bit 0 belongs to group 4 h
+        uint32_t sbase;  // fp32 pattern of the unit scale
+    };
+    auto read_w = [&](UnitW &uw, int slot) {
+        const uint4 cw = lds_wc[(slot * NW + wave) * 64 + lane];
+        const uint32_t m = lds_wm[(slot * NW + wave) * 64 + lane];
+        uw.c[0] = cw.x, uw.c[1] = cw.y, uw.c[2] = cw.z, uw.c[3] = cw.w;
+        uw.m8 = m >> (8 + 4 * half);
+        uw.m16 = m >> (16 + 8 * half);
+        uw.sbase = unit_scale_bits(m);
+    };
+    auto begin = [&](const UnitW &uw, int d) {
+        ChunkState st;
+        const uint32_t e8 = (uw.m8 >> d) & 1u, e16a = (uw.m16 >> (2 * d)) & 1u, e16b = (uw.m16 >> (2 * d + 1)) & 1u;
+        st.sa = u2f(uw.sbase + ((e8 + e16a) << 23));
+        st.sb = u2f(uw.sbase + ((e8 + e16b) << 23));
+        st.c = uw.c[d];
+        st.lo = st.c & 0x07070707u;
+        st.hi = (st.c >> 4) & 0x07070707u;
+        asm volatile("" : "+v"(st.lo), "+v"(st.hi));
+        return st;
+    };
+
+    // ---- prologue.  After the barrier of step k the loop issues the group [A(k + NB), W(k + R)]; the
+    // same groups for k < 0 start the pipeline, so that the loads in flight are always the same ones.
+#pragma unroll
+    for (int u = 0; u < R - NB; ++u) issue_w(u, u);
+#pragma unroll
+    for (int k = -NB; k < 0; ++k) {
+        issue_a(k + NB, k + NB);
+        issue_w(k + R, k + R);
+    }
+    // A(0) and W(0) have landed once only the loads younger than A(0) are in flight
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(2 + (NB - 1) * PER_STEP) : "memory");
+    __syncthreads();
+
+    // The main loop, compiled once per number of row blocks that have rows (LIVE), so that its body
+    // is one straight run of instructions: the slices of the expansion stay between the MFMAs where
+    // they are put, and the waits for LDS reads count exactly.
+    auto run = [&](auto live_c) {
+        constexpr int LIVE = decltype(live_c)::value;
+        constexpr int SP = (5 + LIVE - 1) / LIVE; // expansion slices after each MFMA (5 per sub-step)
+        uint4 af[2][LIVE]; // A operands of two sub-steps, one per row block
+        uint4 bcur, bnext;
+        UnitW uw;
+        ChunkState cs;
+        auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+        // A operands of sub-step s from buffer `buf` into set `set`
+        auto a_frags = [&](int set, int buf, int s) {
+            const uint4 *src = lds_a + buf * A_CELLS + (4 * half + s) * BMP + l32;
+#pragma unroll
+            for (int i = 0; i < LIVE; ++i) af[set][i] = src[i * 32];
+        };
+        // One sub-step: request the A operands of the next one (sub-step ns of buffer nbuf), then the
+        // MFMAs on (af[set], bcur), each followed by a slice of the expansion of dword d of `uw`.
+        auto sub_step = [&](int set, int d, int nbuf, int ns) {
+            a_frags(set ^ 1, nbuf, ns);
+            fence();
+#pragma unroll
+            for (int i = 0; i < LIVE; ++i) {
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af[set][i]), __builtin_bit_cast(bf16x8_t, bcur), acc[i], 0, 0, 0);
+#pragma unroll
+                for (int sl = i * SP; sl < (i + 1) * SP; ++sl) {
+                    if (sl == 0) cs = begin(uw, d);
+                    else if (sl == 1) bnext.x = chunk_pair<0>(cs);
+                    else if (sl == 2) bnext.y = chunk_pair<1>(cs);
+                    else if (sl == 3) bnext.z = chunk_pair<2>(cs);
+                    else if (sl == 4) bnext.w = chunk_pair<3>(cs);
+                }
+                fence();
+            }
+            bcur = bnext;
+        };
+
+        read_w(uw, 0);
+        cs = begin(uw, 0);
+        bcur.x = chunk_pair<0>(cs);
+        bcur.y = chunk_pair<1>(cs);
+        bcur.z = chunk_pair<2>(cs);
+        bcur.w = chunk_pair<3>(cs);
+        bnext = bcur;
+        a_frags(0, 0, 0);
+
+        int buf = 0, slot = 0; // buffer of A(k), ring slot of W(k)
+        for (int k = 0; k < nk; ++k) {
+            const int nbuf = buf + 1 == NB ? 0 : buf + 1, nslot = (slot + 1) % R;
+            sub_step(0, 1, buf, 1);
+            sub_step(1, 2, buf, 2);
+            sub_step(0, 3, buf, 3);
+            // A(k + 1) and W(k + 1) have landed once only the loads younger than A(k + 1) are in flight
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"(2 + (NB - 2) * PER_STEP) : "memory");
+            __syncthreads(); // every wave holds its last operands of buffer `buf`, which may now be refilled
+            issue_a(k + NB, buf);
+            issue_w(k + R, slot);
+            read_w(uw, nslot);
+            sub_step(1, 0, nbuf, 0);
+            buf = nbuf;
+            slot = nslot;
+        }
+    };
+    static_assert(TMAX <= 8, "dispatch below");
+    switch (live) {
+    case 1: run(std::integral_constant<int, 1>{}); break;
+    case 2: run(std::integral_constant<int, 2>{}); break;
+    case 3: if constexpr (TMAX >= 3) run(std::integral_constant<int, 3>{}); break;
+    case 4: if constexpr (TMAX >= 4) run(std::integral_constant<int, 4>{}); break;
+    case 5: if constexpr (TMAX >= 5) run(std::integral_constant<int, 5>{}); break;
+    case 6: if constexpr (TMAX >= 6) run(std::integral_constant<int, 6>{}); break;
+    case 7: if constexpr (TMAX >= 7) run(std::integral_constant<int, 7>{}); break;
+    default: if constexpr (TMAX >= 8) run(std::integral_constant<int, 8>{}); break;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // no load may outlive the workgroup's LDS
+
+    // ---- epilogue: lane holds column l32 of each 32 x 32 block, rows 8 (r / 4) + 4 half + r % 4
+    const int col = col0 + wave * 32 + l32;
+#pragma unroll
+    for (int i = 0; i < TMAX; ++i) {
+        if (i >= live) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            if (row < rows_end && col < g.N) {
+                const float v = acc[i][r];
+                if (OUT_F32) static_cast<float *>(g.c)[(int64_t)row * g.ldc + col] = v;
+                else static_cast<uint16_t *>(g.c)[(int64_t)row * g.ldc + col] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
+            }
+        }
+    }
+}
+
+#ifndef HIF4_COLWAVE_NW
+#define HIF4_COLWAVE_NW 8
+#define HIF4_COLWAVE_NB 3
+#define HIF4_COLWAVE_R 4
+#define HIF4_COLWAVE_WPS 2
+#endif
+
+template <int TMAX>
+static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
+{
+    constexpr int NW = HIF4_COLWAVE_NW, NB = HIF4_COLWAVE_NB, R = HIF4_COLWAVE_R, WPS = HIF4_COLWAVE_WPS;
+    constexpr int BM = 32 * TMAX;
+    constexpr size_t lds_bytes = ColwaveShape<NW, NB, R>::lds_bytes(TMAX);
+    static_assert(lds_bytes <= 160 * 1024, "fits the LDS of one CU");
+    g.tiles_n = (g.N + 32 * NW - 1) / (32 * NW);
+    g.tiles_m = g.offs ? g.M / BM + g.E : (g.M + BM - 1) / BM; // grouped: upper bound of sum_e ceil(rows_e / BM)
+    const int64_t blocks = (int64_t)(g.tiles_m >= 8 ? (g.tiles_m + 7) / 8 * 8 : g.tiles_m) * g.tiles_n;
+    const dim3 grid((unsigned)blocks), block(64 * NW);
+    hipError_t e;
+    if (out_dtype == HIF4_OUT_F32) {
+        auto k = gemm_colwave_kernel<TMAX, NW, NB, R, WPS, true>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return HIF4_ERR_DEVICE;
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
+    } else {
+        auto k = gemm_colwave_kernel<TMAX, NW, NB, R, WPS, false>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return HIF4_ERR_DEVICE;
+        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
+    }
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+// The kernel addresses each operand as a scalar base plus a 32-bit byte offset per lane.
+bool colwave_fits(int64_t M, int64_t N, int64_t K)
+{
+    return M * 128 < ((int64_t)1 << 32) && N * (K / 2) < ((int64_t)1 << 32);
+}
+
+// a_planes: decoded A as cell planes (launch_decode_planes).  offs != nullptr: grouped, E experts;
+// rows_per_tile: 64, 128, 192 or 256 rows of A per workgroup.
+int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint32_t *w_meta, const int32_t *offs, int E,
+                        int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype, int rows_per_tile,
+                        hipStream_t stream)
+{
+    ColwaveArgs g;
+    g.a_planes = static_cast<const uint4 *>(a_planes);
+    g.w_codes = reinterpret_cast<const uint32_t *>(w_codes);
+    g.w_meta = w_meta;
+    g.offs = offs;
+    g.c = c;
+    g.ldc = ldc;
+    g.M = (int)M;
+    g.N = (int)N;
+    g.K = (int)K;
+    g.E = E;
+    if (rows_per_tile <= 64) return launch_colwave_t<2>(g, out_dtype, stream);
+    if (rows_per_tile <= 128) return launch_colwave_t<4>(g, out_dtype, stream);
+    if (rows_per_tile <= 192) return launch_colwave_t<6>(g, out_dtype, stream);
+    return launch_colwave_t<8>(g, out_dtype, stream);
+}
+
+} // namespace hif4

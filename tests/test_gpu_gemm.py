@@ -41,7 +41,9 @@ def quantized_operands(oracle, M, N, K, seed, a_outliers=True):
     return ab, (ac, am), (wc, wm)
 
 
-SHAPES = [(1, 1, 64), (32, 32, 64), (256, 256, 64), (257, 255, 128), (333, 520, 1024), (5, 1000, 192), (600, 70, 320)]
+SHAPES = [(1, 1, 64), (32, 32, 64), (256, 256, 64), (257, 255, 128), (333, 520, 1024), (5, 1000, 192), (600, 70, 320),
+          # up to 192 rows: one m-tile of the kernel that expands W into MFMA operands (32-row blocks, 256-column tiles)
+          (65, 257, 192), (129, 520, 320), (192, 300, 1088), (160, 33, 64)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
