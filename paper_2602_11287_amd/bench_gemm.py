@@ -58,6 +58,18 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     legs["mfma_only_loop_random_operands_TFLOPs"] = ceiling
     bf16_ceiling = ceiling["bf16_32x32x16"]
 
+    # ---- how MFMA and vector instructions share a SIMD (ns per slot of [MFMA ; n vector instructions] and wave):
+    # the model behind the kernels that expand weights next to the matrix pipeline
+    scratch2 = torch.empty(262144, dtype=torch.float32, device=dev)
+    issue = {}
+    for wps in (1, 2, 4):
+        for n_valu, mf in ((8, 0), (0, 1), (4, 1), (8, 1), (12, 1)):
+            slots = hif4.hif4ref_issue_loop(n_valu, mf, wps, 1024, scratch2)
+            ms = _timed(lambda: hif4.hif4ref_issue_loop(n_valu, mf, wps, 1024, scratch2), 10)
+            issue[f"waves_per_simd_{wps}_{'mfma_' if mf else ''}{n_valu}_valu"] = round(ms * 1e6 / slots, 2)
+    legs["issue_probe_ns_per_slot_and_wave"] = issue
+    del scratch2
+
     # ---- weight-only decode shape: M=16, N=4096, K=4096 (HBM-bound weight streaming)
     M, N, K = 16, 4096, 4096
     w = synth.weight_gaussian(N, K, 0.02, config=2, channel_scale=True).to(dev)
@@ -124,7 +136,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
     mfma_leg("grouped_gemm_w4a4_E64_rows8192_N2048_K7168", M, N, K,
              lambda: hif4.hif4_grouped_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, od, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-             "hif4::gemm_kernel<256,256,grouped>")
+             "hif4::gemm_colwave_kernel<6,8,3,4> (+ hif4::encode_to_planes_kernel)")
     nbytes = E * N * K // 64 * 36 + M * K * 2 + M * N * 2
     legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["GBps_algorithmic"] = round(
         nbytes / legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["ms"] / 1e6, 1)

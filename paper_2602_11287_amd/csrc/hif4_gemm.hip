@@ -436,6 +436,7 @@ __global__ void zero_kernel(void *c, int64_t M, int64_t N, int64_t ldc, int elem
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream);
 int launch_encode_to_cells(const void *x, int64_t rows, int64_t K, int64_t ldx, void *cells, int mode, hipStream_t stream);
+int launch_encode_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx, void *planes, int mode, hipStream_t stream);
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes, hipStream_t stream);
 int launch_gemm_stream(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N, int64_t K,
@@ -582,16 +583,12 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         if (planes) {
             // room for a decoded copy of W and enough rows for it to pay: both operands as
             // cell planes, main loop without any expansion
-            const uint8_t *codes = static_cast<const uint8_t *>(a);
-            const uint32_t *meta = a_meta;
-            if (a_kind == HIF4_A_BF16_QUANTIZE) {
-                uint32_t *qm = reinterpret_cast<uint32_t *>(ws + align16((size_t)M * (size_t)K / 2));
-                if (int rc = launch_encode(a, M, K, lda, ws, qm, HIF4_ROUND_RNE, stream)) return rc;
-                codes = ws;
-                meta = qm;
-            }
             uint8_t *wplanes = ws + base;
-            if (int rc = launch_decode_planes(codes, meta, M, K, adec, stream)) return rc;
+            if (a_kind == HIF4_A_BF16_QUANTIZE) {
+                if (int rc = launch_encode_to_planes(a, M, K, lda, adec, HIF4_ROUND_RNE, stream)) return rc;
+            } else {
+                if (int rc = launch_decode_planes(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
+            }
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
             return launch_gemm_planes(adec, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
@@ -599,15 +596,12 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             // grouped, or so few rows that there is one m-tile: every weight meets those few rows only,
             // so the kernel that expands W straight into MFMA operands takes the call
             // (hif4_gemm_colwave.hip); A as cell planes
-            const uint8_t *codes = static_cast<const uint8_t *>(a);
-            const uint32_t *meta = a_meta;
             if (a_kind == HIF4_A_BF16_QUANTIZE) {
-                uint32_t *qm = reinterpret_cast<uint32_t *>(ws + align16((size_t)M * (size_t)K / 2));
-                if (int rc = launch_encode(a, M, K, lda, ws, qm, HIF4_ROUND_RNE, stream)) return rc;
-                codes = ws;
-                meta = qm;
+                // quantise and decode in one pass: the packed activations are never needed in memory
+                if (int rc = launch_encode_to_planes(a, M, K, lda, adec, HIF4_ROUND_RNE, stream)) return rc;
+            } else {
+                if (int rc = launch_decode_planes(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
             }
-            if (int rc = launch_decode_planes(codes, meta, M, K, adec, stream)) return rc;
             return launch_gemm_colwave(adec, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : (int)M, stream);
         }
         if (a_kind == HIF4_A_BF16_QUANTIZE) {

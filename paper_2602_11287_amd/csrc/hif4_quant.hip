@@ -158,6 +158,43 @@ __global__ __launch_bounds__(256) void encode_to_cells_kernel(const void *__rest
     }
 }
 
+// The same, stored as "cell planes" (cell (row, group g of 8 along K) at index g * rows + row: the
+// layout the plane-fed GEMM kernels load straight into LDS).  A block takes one unit of 64
+// consecutive rows, four lanes per unit, so that the 16 lanes of a wave that hold the same group
+// write 256 consecutive bytes of its plane.
+template <int MODE>
+__global__ __launch_bounds__(256) void encode_to_planes_kernel(const void *__restrict__ x, int64_t rows, int64_t ldx,
+                                                               uint4 *__restrict__ planes)
+{
+    constexpr int LPU = 4, NCH = 2;
+    const int l = (int)(threadIdx.x % LPU);
+    const int64_t r = (int64_t)blockIdx.x * 64 + threadIdx.x / LPU, u = blockIdx.y;
+    const bool live = r < rows;
+    const int64_t row = live ? r : rows - 1; // dead lanes redo the last row and store nothing
+    const int64_t e0 = row * ldx + u * 64;
+    uint4 w[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) w[c] = load_chunk<IN_BF16, MODE, false>(x, e0 + 8 * (c * LPU + l));
+    uint32_t out[NCH];
+    const uint32_t m = encode_share<LPU, MODE>(w, l, out);
+    const uint32_t sbase = unit_scale_bits(m);
+    if (live) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) planes[(u * 8 + c * LPU + l) * rows + row] = expand_chunk(out[c], m, sbase, c * LPU + l);
+    }
+}
+
+int launch_encode_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx, void *planes, int mode, hipStream_t stream)
+{
+    const int64_t upr = K / 64;
+    if (rows == 0 || upr == 0) return HIF4_OK;
+    const dim3 grid((unsigned)((rows + 63) / 64), (unsigned)upr), block(256);
+    uint4 *y = static_cast<uint4 *>(planes);
+    if (mode == HIF4_ROUND_RNE) hipLaunchKernelGGL(encode_to_planes_kernel<HIF4_ROUND_RNE>, grid, block, 0, stream, x, rows, ldx, y);
+    else hipLaunchKernelGGL(encode_to_planes_kernel<HIF4_ROUND_RHA>, grid, block, 0, stream, x, rows, ldx, y);
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
 int launch_encode_to_cells(const void *x, int64_t rows, int64_t K, int64_t ldx, void *cells, int mode, hipStream_t stream)
 {
     const int64_t upr = K / 64, units = rows * upr;

@@ -145,6 +145,11 @@ def test_compare_tools_argument_errors(lib):
     assert lib.hif4cmp_sq_err_bf16(p, p, 4, 64, 64, 32, p, None) == h.HIF4_ERR_SHAPE          # ldy < K
     assert lib.hif4cmp_sq_err_bf16(p, p, 4, 64, 64, 64, None, None) == h.HIF4_ERR_NULL
     assert lib.hif4cmp_mxfp4_fake_quant(None, 0, 64, 64, None, None, None) == h.HIF4_OK
+    assert lib.hif4ref_issue_loop(5, 1, 2, 16, p, None) == h.HIF4_ERR_UNSUPPORTED          # n_valu not offered
+    assert lib.hif4ref_issue_loop(8, 1, 3, 16, p, None) == h.HIF4_ERR_UNSUPPORTED          # waves per SIMD
+    assert lib.hif4ref_issue_loop(8, 1, 2, -1, p, None) == h.HIF4_ERR_SHAPE
+    assert lib.hif4ref_issue_loop(8, 1, 2, 16, None, None) == h.HIF4_ERR_NULL
+    assert lib.hif4ref_mfma_loop(2, 16, p, None) == h.HIF4_ERR_UNSUPPORTED
 
 
 def test_gemm_to_hif4_argument_errors(lib):
