@@ -280,6 +280,23 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_kernel(GemmArgs g)
 
 // ------------------------------------------------------------------ skinny weight-only GEMM
 
+#ifndef HIF4_SKINNY_NBUF1
+#define HIF4_SKINNY_NBUF1 1
+#endif
+#ifndef HIF4_SKINNY_NBUF2
+#define HIF4_SKINNY_NBUF2 1
+#endif
+#ifndef HIF4_SKINNY_NBUF4
+#define HIF4_SKINNY_NBUF4 1
+#endif
+#ifndef HIF4_SKINNY_WAVES4
+#define HIF4_SKINNY_WAVES4 8
+#endif
+// waves per workgroup and pairs of units in flight per wave, by the number of 16-row blocks (measured
+// on MI355X: more pairs in flight cost registers, and occupancy is worth more)
+constexpr int skinny_waves(int mb) { return mb == 4 ? HIF4_SKINNY_WAVES4 : 8; }
+constexpr int skinny_nbuf(int mb) { return mb == 1 ? HIF4_SKINNY_NBUF1 : mb == 2 ? HIF4_SKINNY_NBUF2 : HIF4_SKINNY_NBUF4; }
+
 // C[M][N] = A[M][K] (BF16) * W[N][K]^T (HiF4) for M <= 16 * MB: bound by streaming W once
 // from HBM.  A workgroup owns 16 output columns; its waves split K into contiguous ranges and
 // add their partial tiles through LDS at the end.  v_mfma_f32_16x16x32_bf16: lane (n, q) =
@@ -290,20 +307,23 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_kernel(GemmArgs g)
 // MFMA t (0..3) of the pair then takes group 4 q + t of the pair's 16 groups of 8.  The
 // activations of the pair (16 MB rows x 256 bytes) are loaded with fully coalesced 16-byte
 // loads (16 lanes per row), written to a wave-private LDS slab [group][row] in cell order and
-// read back in the MFMA operand layout; no workgroup barrier is involved.  NBUF pairs are in
-// flight per wave (registers and slabs), because the kernel lives on memory latency.
+// read back in the MFMA operand layout; no workgroup barrier is involved.  One pair is in
+// flight per wave in registers while the pair before it is worked on: what hides the memory
+// latency is occupancy (about 80 registers and 4 KB of LDS per wave let three workgroups share
+// a CU; with four pairs in flight per wave and one workgroup per CU the same kernel was measured
+// 20 to 35 % slower).
 template <int MB, int WAVES, bool OUT_F32>
 __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const uint16_t *__restrict__ a, int64_t lda,
                                                                  const uint32_t *__restrict__ w_codes,
                                                                  const uint32_t *__restrict__ w_meta, void *c,
                                                                  int64_t ldc, int M, int N, int K)
 {
-    constexpr int NBUF = MB == 1 ? 4 : 2;
+    constexpr int NBUF = skinny_nbuf(MB);
     constexpr int ROWS = 16 * MB, RSTRIDE = ROWS + 1; // +1 cell: the 16 lanes of a row write 16 different banks
     constexpr int SLAB = 16 * RSTRIDE;                // cells per pair
     constexpr int NLD = ROWS / 4;                     // activation loads per lane and pair
     extern __shared__ uint4 lds[];
-    float *red = reinterpret_cast<float *>(lds + WAVES * NBUF * SLAB); // [WAVES][MB][256]
+    float *red = reinterpret_cast<float *>(lds); // [WAVES][MB][256], over the slabs once the main loop is through
 
     const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
     const int n_l = lane % 16, q = lane / 16;
@@ -314,7 +334,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const uint16_t 
     const int p_begin = wave * ppw, p_end = p_begin + ppw < npairs ? p_begin + ppw : npairs;
     const uint32_t *wrow = w_codes + (int64_t)colc * (K / 8);
     const uint32_t *mrow = w_meta + (int64_t)colc * upr;
-    uint4 *slab = lds + wave * NBUF * SLAB;
+    uint4 *slab = lds + wave * SLAB; // one slab per wave: a pair is written and read back before the next one is written
 
     struct InFlight {
         uint4 wc;
@@ -354,7 +374,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const uint16_t 
 #pragma unroll
         for (int i = 0; i < NBUF; ++i) {
             if (p + i < p_end) { // wave-uniform
-                uint4 *sl = slab + i * SLAB;
+                uint4 *sl = slab;
                 // lane (piece n_l, row 4r + q) -> cell [n_l][row]
 #pragma unroll
                 for (int r = 0; r < NLD; ++r) sl[n_l * RSTRIDE + 4 * r + q] = permute_bf16_cell(fl[i].a[r]);
@@ -377,6 +397,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const uint16_t 
             }
         }
     }
+    __syncthreads(); // every wave is through with its slab: the partial tiles go on top of them
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -400,8 +421,9 @@ template <int MB>
 static int launch_skinny(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N,
                          int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream)
 {
-    constexpr int WAVES = MB == 4 ? 4 : 8, NBUF = MB == 1 ? 4 : 2;
-    constexpr size_t lds_bytes = (size_t)WAVES * NBUF * 16 * (16 * MB + 1) * sizeof(uint4) + (size_t)WAVES * MB * 256 * sizeof(float);
+    constexpr int WAVES = skinny_waves(MB);
+    constexpr size_t slab_bytes = (size_t)WAVES * 16 * (16 * MB + 1) * sizeof(uint4), red_bytes = (size_t)WAVES * MB * 256 * sizeof(float);
+    constexpr size_t lds_bytes = slab_bytes > red_bytes ? slab_bytes : red_bytes;
     static_assert(lds_bytes <= 160 * 1024, "fits the LDS of one CU");
     const dim3 grid((unsigned)((N + 15) / 16)), block(64 * WAVES);
     const uint16_t *ap = static_cast<const uint16_t *>(a);
@@ -441,7 +463,10 @@ int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows
 int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes, hipStream_t stream);
 int launch_gemm_stream(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N, int64_t K,
                        void *c, int64_t ldc, int out_dtype, hipStream_t stream);
-constexpr int64_t STREAM_MIN_COLUMNS = 10240;
+#ifndef HIF4_STREAM_MIN_COLUMNS
+#define HIF4_STREAM_MIN_COLUMNS 12288
+#endif
+constexpr int64_t STREAM_MIN_COLUMNS = HIF4_STREAM_MIN_COLUMNS;
 int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, int64_t N, int64_t K, void *c, uint32_t *c_meta,
                        int64_t ldc, int out_dtype, hipStream_t stream);
 
@@ -555,9 +580,10 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     }
     if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64 && !emit) { // decode-shaped: stream the weights once
         // 33 to 64 rows against many columns: columns split over workgroups only, whole K per wave, the
-        // activations shared through LDS (hif4_gemm_stream.hip; measured 100 us against 191 us for
-        // 64 x 28672 x 8192).  With fewer rows or columns the split of K over the waves of a workgroup
-        // below is as fast or faster (both kernels are bound by the expansion arithmetic, not by HBM).
+        // activations shared through LDS (hif4_gemm_stream.hip; measured 96 us against 122 us for
+        // 64 x 28672 x 8192, 38 against 43 us at 14336 x 4096, 36 against 30 us at 11008 x 4096).  With
+        // fewer rows or columns the split of K over the waves of a workgroup below is as fast or faster
+        // (both kernels are bound by the expansion arithmetic, not by HBM).
         if (M > 32 && K % 128 == 0 && N >= STREAM_MIN_COLUMNS) return launch_gemm_stream(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         if (M <= 16) return launch_skinny<1>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         if (M <= 32) return launch_skinny<2>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);

@@ -26,13 +26,22 @@ __device__ __forceinline__ void stream_load_to_lds_16(const void *src, uint32_t 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte), "v"(src) : "memory");
 }
 
+#ifndef HIF4_STREAM_CP4
+#define HIF4_STREAM_CP4 2
+#endif
+#ifndef HIF4_STREAM_CP12
+#define HIF4_STREAM_CP12 4
+#endif
+// pairs of units per chunk of activations (one barrier per chunk), by the number of 16-row blocks
+constexpr int stream_chunk_pairs(int mb) { return mb > 2 ? HIF4_STREAM_CP4 : HIF4_STREAM_CP12; }
+
 template <int MB, bool OUT_F32>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(const uint16_t *__restrict__ a, int64_t lda,
                                                           const uint32_t *__restrict__ w_codes,
                                                           const uint32_t *__restrict__ w_meta, void *c, int64_t ldc,
                                                           int M, int N, int K)
 {
-    constexpr int CP = MB > 2 ? 2 : 4;         // pairs of units per chunk
+    constexpr int CP = stream_chunk_pairs(MB);         // pairs of units per chunk
     constexpr int CHUNK_CELLS = CP * MB * 256; // 16-byte cells of A per chunk: [pair][row block][16 groups][16 rows]
     constexpr int LOADS = CP * MB * 4;         // 64-cell direct loads per chunk, dealt to the 4 waves
     constexpr int LPW = LOADS / 4;
@@ -140,7 +149,7 @@ template <int MB>
 static int launch_stream_mb(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N,
                             int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream)
 {
-    constexpr int CP = MB > 2 ? 2 : 4;
+    constexpr int CP = stream_chunk_pairs(MB);
     constexpr size_t lds_bytes = (size_t)2 * CP * MB * 256 * sizeof(uint4);
     const dim3 grid((unsigned)((N + 63) / 64)), block(256);
     const uint16_t *ap = static_cast<const uint16_t *>(a);

@@ -400,10 +400,10 @@ def test_gemm_to_hif4_many_rows_and_k0(h, oracle):
     assert not cc.any() and not cm.any()
 
 
-@pytest.mark.parametrize("M,N,K", [(64, 10240, 1024), (33, 10250, 2048 + 128), (48, 12000, 512), (40, 16384, 128),
-                                   (16, 8192, 4096), (64, 10240, 192)])
+@pytest.mark.parametrize("M,N,K", [(64, 12288, 1024), (33, 12298, 2048 + 128), (48, 14000, 512), (40, 16384, 128),
+                                   (16, 8192, 4096), (64, 12288, 192)])
 def test_gemm_weight_only_wide_weights(h, oracle, M, N, K):
-    """33 to 64 rows against 10240 or more columns, K a multiple of 128: the column-split kernel, whole K per
+    """33 to 64 rows against 12288 or more columns, K a multiple of 128: the column-split kernel, whole K per
     wave, activations through LDS by direct loads.  (The last two shapes stay on the other kernel.)"""
     print(f"weight-only streaming M={M} N={N} K={K}", flush=True)
     rng = np.random.default_rng(M * 7 + N)
@@ -461,7 +461,7 @@ def test_grouped_gemm_many_experts(h, oracle):
     assert rel_fro(got, want) <= TOL, rel_fro(got, want)
 
 
-@pytest.mark.parametrize("M,N,K", [(16, 272, 256), (40, 10240, 256)])
+@pytest.mark.parametrize("M,N,K", [(16, 272, 256), (40, 12288, 256), (64, 300, 256)])
 def test_gemm_weight_only_strided_rows(h, oracle, M, N, K):
     """Row strides larger than the row length for A and C in the two few-row kernels; nothing is written
     between the rows of C."""
