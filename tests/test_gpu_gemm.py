@@ -519,3 +519,35 @@ def test_gemm_large_prefill_config_sampled(h, oracle):
     # HiF4 output of whole sampled rows: the oracle's encoder applied to the GPU's BF16 rows
     ec, em = oracle.quantize(synth.bits(c[ri].cpu()))
     assert (oc[ri].cpu().numpy() == ec).all() and (om[ri].cpu().numpy().view(np.uint32) == em).all()
+
+
+def test_few_row_and_grouped_kernel_strided_output(h, oracle):
+    """The kernel that takes dense calls of at most 192 rows and grouped calls (HiF4 x HiF4): row stride of C
+    larger than N, BF16 and fp32 results, nothing written between the rows or past an expert's last row."""
+    M, N, K = 150, 290, 320
+    ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 4242)
+    want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc, wm))
+    acd, amd = dev_packed(ac, am)
+    wcd, wmd = dev_packed(wc, wm)
+    for dt, od in ((torch.float32, h.HIF4_OUT_F32), (torch.bfloat16, h.HIF4_OUT_BF16)):
+        cbuf = torch.full((M, N + 22), -1.0, dtype=dt, device="cuda")
+        h.hif4_gemm(h.HIF4_A_HIF4, acd, amd, wcd, wmd, out_dtype=od, c=cbuf[:, :N])
+        torch.cuda.synchronize()
+        assert (cbuf[:, N:] == -1.0).all()
+        got = cbuf[:, :N].double().cpu().numpy()
+        tol = TOL if dt == torch.float32 else 2.0 ** -8
+        assert rel_fro(got, want) <= tol, rel_fro(got, want)
+    # grouped: two experts sharing one weight matrix shape, rows 0..89 and 90..149, strided C
+    E = 2
+    offs = np.array([0, 90, M], np.int32)
+    w2c = np.concatenate([wc, wc[::-1]]).reshape(E, N, K // 2)
+    w2m = np.concatenate([wm, wm[::-1]]).reshape(E, N, K // 64)
+    adec = oracle.dequantize(ac, am)
+    want_g = np.concatenate([oracle.gemm_f64(adec[:90], oracle.dequantize(wc, wm)),
+                             oracle.gemm_f64(adec[90:], oracle.dequantize(wc[::-1].copy(), wm[::-1].copy()))])
+    cbuf = torch.full((M, N + 10), -1.0, dtype=torch.float32, device="cuda")
+    h.hif4_grouped_gemm(h.HIF4_A_HIF4, acd, amd, *dev_packed(np.ascontiguousarray(w2c), np.ascontiguousarray(w2m)),
+                        torch.from_numpy(offs).cuda(), out_dtype=h.HIF4_OUT_F32, c=cbuf[:, :N])
+    torch.cuda.synchronize()
+    assert (cbuf[:, N:] == -1.0).all()
+    assert rel_fro(cbuf[:, :N].double().cpu().numpy(), want_g) <= TOL
