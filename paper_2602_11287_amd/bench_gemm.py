@@ -79,10 +79,25 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     f = lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_KEEP, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c)
     for _ in range(warmup):
         f()
-    ms = _timed(f, steps * 10)
+    ms_host = _timed(f, steps * 10)  # one Python call per launch: paced by the host, not by the GPU
+    # the same launches from a HIP graph (50 per replay): what the GPU itself takes per call
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        f()
+        torch.cuda.current_stream().synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(50):
+                f()
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    ms = _timed(graph.replay, max(steps, 5)) / 50
+    del graph
     nbytes = N * K // 64 * 36 + M * K * 2 + M * N * 2
     legs["gemm_weight_only_M16_N4096_K4096"] = {
-        "us": round(ms * 1e3, 2), "GBps": round(nbytes / ms / 1e6, 1), "GFLOP": round(2 * M * N * K / 1e9, 3),
+        "us": round(ms * 1e3, 2), "us_per_python_call": round(ms_host * 1e3, 2),
+        "GBps": round(nbytes / ms / 1e6, 1), "GFLOP": round(2 * M * N * K / 1e9, 3),
         "roofline": {"bound": "hbm", "kernel": "hif4::gemm_skinny_kernel<1,8>", "achieved": round(nbytes / ms / 1e6, 1),
                      "peak": hbm_peak_gbps, "unit": "GB/s", "frac": round(nbytes / ms / 1e6 / hbm_peak_gbps, 4),
                      "traffic": None}}
@@ -107,14 +122,20 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     del w
     ac, am = hif4.hif4_quantize(a)
     c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-    ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
-    planes, tiles = "hif4::gemm_planes_kernel<256,256,2,4>", "hif4::gemm_kernel<256,256,2,4>"
+    # the workspace with room for a decoded copy of W: both operands decoded once, plain BF16 main loop
+    ws = torch.empty(hif4.hif4_gemm_workspace_bytes_decoded_w(hif4.HIF4_A_BF16_QUANTIZE, M, N, K), dtype=torch.uint8, device=dev)
+    ws_small = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
+    planes, tiles = "hif4::gemm_planes16_kernel<256,256,2,4>", "hif4::gemm_kernel<256,256,2,4>"
     mfma_leg("gemm_w4a4_quantize_inside_M4096_N11008_K4096", M, N, K,
              lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
+             planes)
+    mfma_leg("gemm_w4a4_quantize_inside_small_workspace_M4096_N11008_K4096", M, N, K,
+             lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws_small),
              tiles)
     mfma_leg("gemm_w4a4_prepacked_M4096_N11008_K4096", M, N, K,
              lambda: hif4.hif4_gemm(hif4.HIF4_A_HIF4, ac, am, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-             tiles)
+             planes)
+    del ws_small
     mc, ms_, = hif4.hif4ref_mxfp4_pack(a)
     wq = hif4.hif4ref_mxfp4_pack(hif4.hif4_dequantize(wc, wm))       # any weights of that shape: speed only
     ms = _timed(lambda: hif4.hif4ref_mxfp4_gemm(mc, ms_, wq[0], wq[1], c=c), steps)

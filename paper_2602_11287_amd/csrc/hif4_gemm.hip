@@ -530,11 +530,14 @@ size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
 
 // From this many rows of A on, a dense GEMM between two HiF4 operands decodes W once into the
 // workspace as well (if the caller gave room for it) and runs the kernel of hif4_gemm_cells.hip
-// instead of expanding W inside the main loop.  Measured on MI355X: the main loop without any
-// expansion is 3 to 5 % faster (same matrix-pipeline occupancy, higher clock because the VALUs
-// idle), and the pre-pass that decodes W costs 2.56 bytes per weight once per call, which that
-// margin covers from about 8192 rows on (at 4096 rows the two paths tie).
-constexpr int64_t DECODED_W_MIN_ROWS = 8192;
+// instead of expanding W inside the main loop.  Measured on MI355X: that main loop (on
+// v_mfma_f32_16x16x32_bf16, nothing but matrix work) is 10 to 17 % faster than the one that expands W,
+// and the pre-pass that decodes W costs 2.56 bytes per weight once per call, which that margin covers
+// from about 4096 rows on (+6 to 10 % there; at 2048 rows the two paths tie).
+#ifndef HIF4_DECODED_W_MIN_ROWS
+#define HIF4_DECODED_W_MIN_ROWS 4096
+#endif
+constexpr int64_t DECODED_W_MIN_ROWS = HIF4_DECODED_W_MIN_ROWS;
 
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
 {

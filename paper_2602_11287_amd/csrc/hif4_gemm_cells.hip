@@ -297,6 +297,158 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
 }
 
 
+// The same GEMM on v_mfma_f32_16x16x32_bf16.  On this chip the matrix pipeline is limited by
+// power under real operand bits, and the 16 x 16 x 32 form sustains more than the 32 x 32 x 16
+// form (measured with MFMA-only loops on random bits: 2.0 against 1.7-1.8 PFLOP/s): twice the K
+// per instruction means half the accumulator traffic per flop.  Same tile, staging and block
+// mapping as above; a wave's 128 x 64 part is 8 x 4 tiles of 16 x 16.  Lane (n, q) = (lane % 16,
+// lane / 16) takes row n and cell 4 hs + q of a K step's 8 cells for half step hs (32 of K).
+// A half step is two phases of 16 MFMAs (tile rows 0..3, then 4..7); phase P requests its
+// operands from LDS and runs the MFMAs of phase P - 1, so the barrier between two K steps again
+// falls between the last phase's operand reads and its MFMAs.
+template <int BM, int BN, int WM, int WN, bool OUT_F32, int EMIT = -1>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmArgs g)
+{
+    constexpr int NW = WM * WN;
+    constexpr int TM = BM / WM / 16, TN = BN / WN / 16; // 16 x 16 tiles per wave
+    static_assert(TM == 8 && TN == 4, "two phases of four tile rows per half step");
+    constexpr int W_BASE = 8 * BM, CELLS = 8 * (BM + BN);
+    constexpr int IA = 8 * BM / 64 / NW, IW = 8 * BN / 64 / NW;
+    extern __shared__ uint4 lds[]; // 2 buffers x CELLS
+
+    const int tid = threadIdx.x;
+    const int wave = tid / 64, lane = tid % 64;
+    const int wm = wave / WN, wn = wave % WN;
+
+    constexpr int GM = 4, GN = 8, XCDS = 8; // see gemm_planes_kernel
+    const int per_xcd = (int)(gridDim.x / XCDS);
+    const int t = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
+    const int sn = (g.tiles_n + GN - 1) / GN;
+    const int stile = t / (GM * GN), within = t % (GM * GN);
+    const int tile_n = (stile % sn) * GN + within % GN;
+    const int tile_m = (stile / sn) * GM + within / GN;
+    if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return;
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    const int nk = g.K / 64;
+
+    const uint4 *a_src[IA], *w_src[IW];
+    int a_dst[IA], w_dst[IW];
+#pragma unroll
+    for (int i = 0; i < IA; ++i) {
+        const int id = wave * IA + i, j = id / (BM / 64), rb = id % (BM / 64);
+        int row = row0 + rb * 64 + lane;
+        row = row < g.M ? row : g.M - 1;
+        a_src[i] = g.a + (int64_t)j * g.M + row;
+        a_dst[i] = j * BM + rb * 64;
+    }
+#pragma unroll
+    for (int i = 0; i < IW; ++i) {
+        const int id = wave * IW + i, j = id / (BN / 64), rb = id % (BN / 64);
+        int row = col0 + rb * 64 + lane;
+        row = row < g.N ? row : g.N - 1;
+        w_src[i] = g.w + (int64_t)j * g.N + row;
+        w_dst[i] = W_BASE + j * BN + rb * 64;
+    }
+    const int64_t a_step = (int64_t)8 * g.M, w_step = (int64_t)8 * g.N;
+    auto stage = [&](uint4 *buf) {
+        const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_offset(buf));
+#pragma unroll
+        for (int i = 0; i < IA; ++i) {
+            load_to_lds_16(a_src[i], base + (uint32_t)__builtin_amdgcn_readfirstlane(a_dst[i] * 16));
+            a_src[i] += a_step;
+        }
+#pragma unroll
+        for (int i = 0; i < IW; ++i) {
+            load_to_lds_16(w_src[i], base + (uint32_t)__builtin_amdgcn_readfirstlane(w_dst[i] * 16));
+            w_src[i] += w_step;
+        }
+    };
+    auto staged_wait = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+
+    f32x4_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
+
+    const int q = lane / 16, n = lane % 16;
+    // operands of two phases (4 tile rows of A each) and of two half steps (4 tile columns of W each);
+    // the sets the first phase works on start as zeros
+    uint4 af[2][4], bfr[2][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af[1][i] = bfr[1][i] = make_uint4(0, 0, 0, 0);
+    auto mfma_phase = [&](int ph) { // the 16 MFMAs of phase ph = 2 hs + ab: tile rows 4 ab .. 4 ab + 3, operands of half step hs
+        const int hs = ph / 2, ab = ph % 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[4 * ab + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, af[ph & 1][i]), __builtin_bit_cast(bf16x8_t, bfr[hs & 1][j]),
+                                                                             acc[4 * ab + i][j], 0, 0, 0);
+    };
+    auto k_step = [&](const uint4 *cur) {
+        const uint4 *abase = cur + wm * (BM / WM) + n;
+        const uint4 *bbase = cur + W_BASE + wn * (BN / WN) + n;
+#pragma unroll
+        for (int ph = 0; ph < 4; ++ph) {
+            const int hs = ph / 2, ab = ph % 2, j = 4 * hs + q;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) af[ph & 1][i] = abase[j * BM + (4 * ab + i) * 16];
+            if (ab == 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) bfr[hs & 1][i] = bbase[j * BN + i * 16];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_phase((ph + 3) & 3);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    int cur = 0, nxt = CELLS;
+    stage(lds);
+    staged_wait();
+    __syncthreads();
+    for (int ks = 0; ks < nk; ++ks) {
+        if (ks + 1 < nk) stage(lds + nxt); // every wave is past its reads of that buffer (the barrier above)
+        k_step(lds + cur);
+        staged_wait();
+        __syncthreads();
+        const int t2 = cur;
+        cur = nxt;
+        nxt = t2;
+    }
+    mfma_phase(3); // the last phase of the last step
+
+    if constexpr (EMIT >= 0) {
+        emit_hif4_tile16<BM, BN, WM, WN, EMIT>(acc, lds, row0, g.M, col0, g.N, static_cast<uint32_t *>(g.c), g.c_meta);
+        return;
+    }
+    // ---- epilogue: lane holds column n of each 16 x 16 tile, rows 4 q + r
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+            const int col = col0 + wn * (BN / WN) + jn * 16 + n;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = row0 + wm * (BM / WM) + i * 16 + 4 * q + r;
+                if (row < g.M && col < g.N) {
+                    const float v = acc[i][jn][r];
+                    if (OUT_F32) {
+                        static_cast<float *>(g.c)[(int64_t)row * g.ldc + col] = v;
+                    } else {
+                        static_cast<uint16_t *>(g.c)[(int64_t)row * g.ldc + col] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
+                    }
+                }
+            }
+        }
+    }
+}
+
+#ifndef HIF4_PLANES_MFMA16
+#define HIF4_PLANES_MFMA16 1
+#endif
+
 template <bool MX>
 static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int out_dtype, hipStream_t stream)
 {
@@ -316,6 +468,9 @@ static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int o
             static_assert(emit_bytes <= 160 * 1024, "fits the LDS of one CU");
             auto k = out_dtype == 16 + HIF4_ROUND_RNE ? gemm_planes_kernel<BM, BN, WM, WN, false, false, HIF4_ROUND_RNE>
                                                        : gemm_planes_kernel<BM, BN, WM, WN, false, false, HIF4_ROUND_RHA>;
+            if (HIF4_PLANES_MFMA16)
+                k = out_dtype == 16 + HIF4_ROUND_RNE ? gemm_planes16_kernel<BM, BN, WM, WN, false, HIF4_ROUND_RNE>
+                                                     : gemm_planes16_kernel<BM, BN, WM, WN, false, HIF4_ROUND_RHA>;
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)emit_bytes);
             if (e != hipSuccess) return HIF4_ERR_DEVICE;
             hipLaunchKernelGGL(k, grid, block, emit_bytes, stream, g);
@@ -324,11 +479,13 @@ static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int o
     }
     if (out_dtype == HIF4_OUT_F32) {
         auto k = gemm_planes_kernel<BM, BN, WM, WN, true, MX>;
+        if (!MX && HIF4_PLANES_MFMA16) k = gemm_planes16_kernel<BM, BN, WM, WN, true>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     } else {
         auto k = gemm_planes_kernel<BM, BN, WM, WN, false, MX>;
+        if (!MX && HIF4_PLANES_MFMA16) k = gemm_planes16_kernel<BM, BN, WM, WN, false>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);

@@ -272,9 +272,9 @@ def test_grouped_gemm_moe_config_sampled(h, oracle):
 
 @pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
 def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
-    """From 8192 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
-    HiF4 operands decode W once instead of inside the main loop: same products in the same order, so the
-    same bits as with the small workspace, and both within tolerance of the oracle."""
+    """From 4096 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
+    HiF4 operands decode W once instead of inside the main loop: the same exact products, added in fp32 in
+    another grouping, so the two results agree far inside the tolerance, and both are within it of the oracle."""
     M, N, K = 8192 + 77, 300, 320
     print(f"gemm decoded-W path kind={kind} M={M} N={N} K={K}", flush=True)
     ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 977)
@@ -293,7 +293,7 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
     small = h.hif4_gemm_workspace_bytes(a_kind, M, K)
     big = h.hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
     assert big == small if kind == "keep" else big >= small + N * K * 2  # BF16 activations: the packed-W kernel only
-    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 8191, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 8191, K)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 4095, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 4095, K)
     ws_small = torch.empty(max(small, 16), dtype=torch.uint8, device="cuda")
     ws_big = torch.empty(max(big, 16), dtype=torch.uint8, device="cuda")
     c_small = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, workspace=ws_small)
@@ -303,7 +303,8 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
     got = c_big.cpu().numpy().astype(np.float64)
     assert rel_fro(got, want) <= TOL, rel_fro(got, want)
     assert rel_fro(c_small.cpu().numpy().astype(np.float64), want) <= TOL
-    assert torch.equal(c_small, c_big) and torch.equal(c_default, c_big)
+    assert torch.equal(c_default, c_big)
+    assert rel_fro(c_small.cpu().numpy().astype(np.float64), got) <= 1e-6
 
 
 def test_gemm_many_rows_many_tiles_sampled(h, oracle):
@@ -380,7 +381,7 @@ def test_gemm_to_hif4_equals_gemm_then_quantize(h, oracle, kind, M, N, K, mode):
 
 
 def test_gemm_to_hif4_many_rows_and_k0(h, oracle):
-    """Through the decoded-operand kernel (8192+ rows, large workspace), and the empty sum."""
+    """Through the decoded-operand kernel (4096+ rows, large workspace), and the empty sum."""
     M, N, K = 8192 + 40, 192, 256
     ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 99)
     wcd, wmd = dev_packed(wc, wm)
