@@ -69,8 +69,9 @@ int hif4ref_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_
  * Measurement aid: 256 workgroups of 8 waves each run `iters` rounds of 8 independent MFMAs on
  * operands with random bit patterns and nothing else, i.e. 2048 * iters * 8 instructions of
  * 32768 flop (kind 0: v_mfma_f32_32x32x16_bf16) or 131072 flop (kind 1: the FP4 form of
- * v_mfma_scale_f32_32x32x64_f8f6f4).  Timed by the benchmark, it gives the rate the matrix
- * pipeline sustains under its power limit, the ceiling next to which GEMM rates are read.
+ * v_mfma_scale_f32_32x32x64_f8f6f4); kind 2 runs 16 v_mfma_f32_16x16x32_bf16 per round, the same
+ * flops as kind 0.  Timed by the benchmark, it gives the rate the matrix pipeline sustains under
+ * its power limit, the ceiling next to which GEMM rates are read.
  *   out  device, 131072 floats, receives checksums nobody needs
  */
 int hif4ref_mfma_loop(int kind, int iters, float *out, void *stream);

@@ -231,7 +231,7 @@ int hif4ref_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_
 
 int hif4ref_mfma_loop(int kind, int iters, float *out, void *stream)
 {
-    if (kind != 0 && kind != 1) return HIF4_ERR_UNSUPPORTED;
+    if (kind != 0 && kind != 1 && kind != 2) return HIF4_ERR_UNSUPPORTED;
     if (iters < 0 || iters > (1 << 24)) return HIF4_ERR_SHAPE;
     if (!out) return HIF4_ERR_NULL;
     if (!aligned(out, 4)) return HIF4_ERR_ALIGN;

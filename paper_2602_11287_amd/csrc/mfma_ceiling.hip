@@ -103,10 +103,39 @@ int launch_issue_loop(int n_valu, int with_mfma, int waves_per_simd, int iters, 
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 
+// KIND 2 of the MFMA-only loop: v_mfma_f32_16x16x32_bf16, sixteen accumulators of 16 x 16 per wave and
+// iteration (the same flops per iteration as the eight 32 x 32 x 16 of KIND 0).
+__global__ __launch_bounds__(512) void mfma_loop16_kernel(float *out, int iters, uint32_t seed)
+{
+    f32x4_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
+    uint32_t s = seed + threadIdx.x * 7919u + blockIdx.x * 104729u;
+    uint4 av[4], bv[4];
+    constexpr uint32_t keep = 0xBFFFBFFFu; // magnitudes at or below 2
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        av[i] = make_uint4(lcg(s) & keep, lcg(s) & keep, lcg(s) & keep, lcg(s) & keep);
+        bv[i] = make_uint4(lcg(s) & keep, lcg(s) & keep, lcg(s) & keep, lcg(s) & keep);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[i / 4]), __builtin_bit_cast(bf16x8_t, bv[i % 4]), acc[i], 0, 0, 0);
+    }
+    float t = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t += acc[i][r];
+    out[blockIdx.x * 512 + threadIdx.x] = t;
+}
+
 int launch_mfma_loop(int kind, int iters, float *out, hipStream_t stream)
 {
     const dim3 grid(256), block(512);
     if (kind == 0) hipLaunchKernelGGL(mfma_loop_kernel<0>, grid, block, 0, stream, out, iters, 1u);
+    else if (kind == 2) hipLaunchKernelGGL(mfma_loop16_kernel, grid, block, 0, stream, out, iters, 1u);
     else hipLaunchKernelGGL(mfma_loop_kernel<1>, grid, block, 0, stream, out, iters, 1u);
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }

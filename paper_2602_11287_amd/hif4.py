@@ -290,7 +290,7 @@ def hif4ref_mfma_loop(kind, iters, out, stream=None):
     """out: CUDA float32 [131072]; returns the flop count of the launch."""
     assert out.is_cuda and out.dtype == torch.float32 and out.numel() >= 131072
     _check(load().hif4ref_mfma_loop(int(kind), int(iters), _ptr(out), _stream(stream)), "hif4ref_mfma_loop")
-    return 2048 * int(iters) * 8 * (32768 if kind == 0 else 131072)
+    return 2048 * int(iters) * 8 * (131072 if kind == 1 else 32768)
 
 
 def hif4ref_issue_loop(n_valu, with_mfma, waves_per_simd, iters, out, stream=None):

@@ -149,7 +149,7 @@ def test_compare_tools_argument_errors(lib):
     assert lib.hif4ref_issue_loop(8, 1, 3, 16, p, None) == h.HIF4_ERR_UNSUPPORTED          # waves per SIMD
     assert lib.hif4ref_issue_loop(8, 1, 2, -1, p, None) == h.HIF4_ERR_SHAPE
     assert lib.hif4ref_issue_loop(8, 1, 2, 16, None, None) == h.HIF4_ERR_NULL
-    assert lib.hif4ref_mfma_loop(2, 16, p, None) == h.HIF4_ERR_UNSUPPORTED
+    assert lib.hif4ref_mfma_loop(3, 16, p, None) == h.HIF4_ERR_UNSUPPORTED
 
 
 def test_gemm_to_hif4_argument_errors(lib):

@@ -138,4 +138,6 @@ def test_issue_probe_runs(h):
             assert torch.isfinite(out[:256 * 256 * wps]).all()
     scratch = torch.empty(131072, dtype=torch.float32, device="cuda")
     assert h.hif4ref_mfma_loop(0, 4, scratch) == 2048 * 4 * 8 * 32768
+    assert h.hif4ref_mfma_loop(2, 4, scratch) == 2048 * 4 * 8 * 32768
+    assert h.hif4ref_mfma_loop(1, 4, scratch) == 2048 * 4 * 8 * 131072
     torch.cuda.synchronize()
