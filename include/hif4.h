@@ -165,13 +165,13 @@ int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t
 size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K);
 
 /*
- * Optional larger workspace for hif4_gemm (not the grouped call) between two HiF4 operands
- * (a_kind 0 or 1).  When M is large every unit of W is decoded by many tiles of C; given this
- * many bytes, hif4_gemm decodes W once per call into the workspace (2 more bytes per weight)
- * and runs its main loop on the decoded values of both operands.  The products are the same
+ * Optional larger workspace for hif4_gemm (not the grouped call).  When M is large every unit
+ * of W is decoded by many tiles of C; given this many bytes, hif4_gemm decodes W once per call
+ * into the workspace (2 more bytes per weight; for a_kind 2 also a reordered copy of A, 2 bytes
+ * per element) and runs its main loop on the decoded values of both operands.  The products are the same
  * and exact; the fp32 additions are grouped differently, so results agree to fp32 summation
  * accuracy, not always bit for bit.  Equals hif4_gemm_workspace_bytes() when M is too small for
- * this to pay (below 4096 rows) and for a_kind 2.  A workspace between the two sizes is used as
+ * this to pay (below 4096 rows).  A workspace between the two sizes is used as
  * the smaller one.  Host function.
  */
 size_t hif4_gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);

@@ -461,6 +461,7 @@ int launch_encode_to_cells(const void *x, int64_t rows, int64_t K, int64_t ldx, 
 int launch_encode_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx, void *planes, int mode, hipStream_t stream);
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes, hipStream_t stream);
+int launch_bf16_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx, void *planes, hipStream_t stream);
 int launch_gemm_stream(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N, int64_t K,
                        void *c, int64_t ldc, int out_dtype, hipStream_t stream);
 #ifndef HIF4_STREAM_MIN_COLUMNS
@@ -542,7 +543,8 @@ constexpr int64_t DECODED_W_MIN_ROWS = HIF4_DECODED_W_MIN_ROWS;
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
 {
     const size_t base = gemm_workspace_bytes(a_kind, M, K);
-    if (a_kind == HIF4_A_BF16_KEEP || M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
+    if (M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
+    if (a_kind == HIF4_A_BF16_KEEP) return align16((size_t)M * (size_t)K * 2) + (size_t)N * (size_t)K * 2; // A as planes, W decoded
     return align16(base) + (size_t)N * (size_t)K * 2;
 }
 
@@ -598,6 +600,15 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     GemmArgs g;
     bool a_cell = true;
     if (a_kind == HIF4_A_BF16_KEEP) {
+        const size_t a_bytes = align16((size_t)M * (size_t)K * 2);
+        if (!offs && M >= DECODED_W_MIN_ROWS && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
+            workspace_bytes >= a_bytes + (size_t)N * (size_t)K * 2) {
+            // weight-only with many rows and room in the workspace: the plane-fed kernel here too
+            uint8_t *ws = static_cast<uint8_t *>(workspace);
+            if (int rc = launch_bf16_to_planes(a, M, K, lda, ws, stream)) return rc;
+            if (int rc = launch_decode_planes(w_codes, w_meta, N, K, ws + a_bytes, stream)) return rc;
+            return launch_gemm_planes(ws, ws + a_bytes, M, N, K, c, c_meta, ldc, out_dtype, stream);
+        }
         g.a = static_cast<const uint16_t *>(a);
         g.lda = lda;
         a_cell = false;

@@ -65,6 +65,26 @@ __global__ __launch_bounds__(256) void decode_planes_kernel(const uint32_t *__re
     }
 }
 
+// Plain BF16 rows (the activations of a weight-only call) -> the same cell planes.  Block = 64 rows x
+// 8 groups of 8 (one 128-byte line of every row); thread (row, group) permutes one cell.
+__global__ __launch_bounds__(512) void bf16_to_planes_kernel(const uint16_t *__restrict__ x, int64_t rows, int64_t ldx,
+                                                             uint4 *__restrict__ planes)
+{
+    const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x % 64;
+    const int64_t g = (int64_t)blockIdx.y * 8 + threadIdx.x / 64;
+    if (row >= rows) return;
+    planes[g * rows + row] = permute_bf16_cell(*reinterpret_cast<const uint4 *>(x + row * ldx + g * 8));
+}
+
+int launch_bf16_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx, void *planes, hipStream_t stream)
+{
+    if (rows == 0 || K == 0) return HIF4_OK;
+    const dim3 grid((unsigned)((rows + 63) / 64), (unsigned)(K / 64)), block(512);
+    hipLaunchKernelGGL(bf16_to_planes_kernel, grid, block, 0, stream, static_cast<const uint16_t *>(x), rows, ldx,
+                       static_cast<uint4 *>(planes));
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
 int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes,
                          hipStream_t stream)
 {

@@ -292,7 +292,7 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
             a_kind, a_dev, am_dev = h.HIF4_A_BF16_QUANTIZE, a_bf16, None
     small = h.hif4_gemm_workspace_bytes(a_kind, M, K)
     big = h.hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
-    assert big == small if kind == "keep" else big >= small + N * K * 2  # BF16 activations: the packed-W kernel only
+    assert big >= small + N * K * 2 + (M * K * 2 if kind == "keep" else 0)  # BF16 activations: a reordered copy of A as well
     assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 4095, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 4095, K)
     ws_small = torch.empty(max(small, 16), dtype=torch.uint8, device="cuda")
     ws_big = torch.empty(max(big, 16), dtype=torch.uint8, device="cuda")
