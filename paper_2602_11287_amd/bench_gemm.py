@@ -6,12 +6,22 @@ import numpy as np
 import torch
 
 
-# HBM bytes per launch of the GEMM kernel itself on the large shape, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (FETCH_SIZE x 1.99988, WRITE_SIZE x 1.0, the factors of a plain device copy): profiles/gemm_kernels_configs2-5.md
-_LARGE_TRAFFIC = {
-    "gemm_w4a4_quantize_inside_M16384_N28672_K8192": int((5506528.5 * 1.99988 + 926695.9) * 1024),
-    "gemm_w4a4_quantize_inside_small_workspace_M16384_N28672_K8192": int((2867353.1 * 1.99988 + 930192.4) * 1024),
-    "gemm_w4a4_to_hif4_M16384_N28672_K8192": int((5512739.1 * 1.99988 + 258048.0) * 1024),
+# HBM bytes per launch of the GEMM kernel itself (pre-passes not included), from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE in KiB per dispatch (FETCH_SIZE x 1.99988, WRITE_SIZE x 1.0, the factors of a plain device copy):
+# profiles/gemm_kernels_configs2-5.md
+def _kib(fetch, write):
+    return int((fetch * 1.99988 + write) * 1024)
+
+
+_TRAFFIC = {
+    "gemm_weight_only_M16_N4096_K4096": _kib(5146.5, 128.0),
+    "gemm_w4a4_quantize_inside_M4096_N11008_K4096": _kib(274558.5, 88143.1),
+    "gemm_w4a4_prepacked_M4096_N11008_K4096": _kib(274558.5, 88143.1),
+    "gemm_w4a4_quantize_inside_small_workspace_M4096_N11008_K4096": _kib(147985.0, 89805.7),
+    "grouped_gemm_w4a4_E64_rows8192_N2048_K7168": _kib(356610.4, 32768.0),
+    "gemm_w4a4_quantize_inside_M16384_N28672_K8192": _kib(5505218.2, 918472.8),
+    "gemm_w4a4_quantize_inside_small_workspace_M16384_N28672_K8192": _kib(2867346.8, 930189.2),
+    "gemm_w4a4_to_hif4_M16384_N28672_K8192": _kib(5512239.6, 258048.0),
 }
 
 
@@ -100,7 +110,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
         "GBps": round(nbytes / ms / 1e6, 1), "GFLOP": round(2 * M * N * K / 1e9, 3),
         "roofline": {"bound": "hbm", "kernel": "hif4::gemm_skinny_kernel<1,8>", "achieved": round(nbytes / ms / 1e6, 1),
                      "peak": hbm_peak_gbps, "unit": "GB/s", "frac": round(nbytes / ms / 1e6 / hbm_peak_gbps, 4),
-                     "traffic": None}}
+                     "traffic": _TRAFFIC.get("gemm_weight_only_M16_N4096_K4096")}}
     del w, wc, wm
 
     def mfma_leg(name, M, N, K, fn, kernel):
@@ -112,7 +122,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
                       "roofline": {"bound": "mfma", "kernel": kernel, "achieved": round(tf, 1), "peak": mfma_peak_tflops,
                                    "unit": "TFLOP/s", "frac": round(tf / mfma_peak_tflops, 4),
                                    "frac_of_mfma_only_loop": round(tf / bf16_ceiling, 4),
-                                   "traffic": _LARGE_TRAFFIC.get(name)}}
+                                   "traffic": _TRAFFIC.get(name)}}
 
     # ---- W4A4 prefill: M=4096, N=11008, K=4096, activations quantised inside the call
     M, N, K = 4096, 11008, 4096
