@@ -1,5 +1,6 @@
 // HiF4 GEMM for tiles with few rows and many weights per row of A: the grouped (per-expert)
-// GEMM, where an expert's rows meet its whole weight matrix once.  C = A * W^T per expert, A as
+// GEMM, where an expert's rows meet its whole weight matrix once, and dense calls of at most 192
+// rows.  C = A * W^T per expert, A as
 // exact BF16 values (decoded HiF4), W packed HiF4; each 64-wide K step of an output is the
 // unit dot product of Eq. 4 of the HiF4 paper (Section III-B), accumulated in fp32 on
 // v_mfma_f32_32x32x16_bf16.
@@ -12,7 +13,7 @@
 // is expanded once per m-tile, by one lane, and never passes through LDS as BF16.  The rows of
 // A are the same for all waves: a K step of them sits in LDS, [group of 8][row], brought in by
 // direct global -> LDS loads from the decoded copy of A ("cell planes", see hif4_gemm_cells.hip:
-// the 64 rows a wave moves at once are contiguous in memory) three steps ahead.  The packed
+// the 64 rows a wave moves at once are contiguous in memory) NB steps ahead.  The packed
 // weights of a wave go through LDS as well, as bytes, lane-private: a ring of R steps filled by
 // the same kind of load, 16 bytes of codes and the metadata word per lane and step.  So every
 // global load of the loop is an LDS-writing one with a fixed count per wave and step, and one
@@ -20,10 +21,17 @@
 //
 // K order: sub-step s (of 4, a K slab of 16) takes group 4 h + s of a unit's 8 groups of 8
 // from lane half h, for both operands, so a lane's 4 dwords of codes per unit are contiguous.
-// A K step of a wave: for each sub-step, up to TMAX MFMAs (one per 32-row block that has rows),
-// each followed by one slice of the expansion of the next sub-step's weights and by the LDS
-// read of that block's next A operand.  The step boundary (wait, barrier, loads of the step
-// three ahead) lies before the last sub-step, whose slices already belong to the next unit.
+// A K step of a wave: for each sub-step, the LDS reads of the next sub-step's A operands, then up
+// to TMAX MFMAs (one per 32-row block that has rows), each followed by one slice of the expansion
+// of the next sub-step's weights.  The step boundary (wait, barrier, loads of the step NB ahead)
+// lies before the last sub-step, whose slices already belong to the next unit.
+//
+// What bounds it on MI355X (measured with the instruction-issue probe of mfma_ceiling.hip): a wave
+// issues one vector instruction per 7-8 cycles, a SIMD one per 4, and an MFMA costs about 8 cycles
+// of that port next to its 32 in the matrix pipeline.  The expansion is 37 vector instructions per
+// 8 weights, so with the two waves per SIMD that the accumulators leave room for, the loop is bound
+// by vector instruction issue: everything that is not expansion is kept out of the vector ALUs
+// (scalar address arithmetic, loads straight into LDS, one wait per sub-step).
 #include <type_traits>
 
 #include "hif4_expand.h"
