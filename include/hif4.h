@@ -153,7 +153,9 @@ int hif4_gemm_to_hif4(int a_kind, const void *a, const uint32_t *a_meta, int64_t
  * W[e] (w_codes [E][N][K/2], w_meta [E][N][K/64]).  offs is a DEVICE int32[E+1] array,
  * non-decreasing, offs[0] == 0, offs[E] == total_rows; it is read by the kernels only,
  * so no host synchronisation happens.  Experts with no rows are skipped.  Other
- * arguments as hif4_gemm with M = total_rows.
+ * arguments as hif4_gemm with M = total_rows.  For a_kind 2 no workspace is needed; given
+ * one of at least total_rows * K * 2 bytes (16-byte aligned) the call keeps a reordered copy
+ * of A there and runs the faster kernel of the other two kinds.
  */
 int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
                       const uint8_t *w_codes, const uint32_t *w_meta,

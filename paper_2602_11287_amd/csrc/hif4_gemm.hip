@@ -609,6 +609,12 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, ws + a_bytes, stream)) return rc;
             return launch_gemm_planes(ws, ws + a_bytes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
+        if (offs && colwave_rows(M, E) > 0 && colwave_fits(M, N, K) && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
+            workspace_bytes >= (size_t)M * (size_t)K * 2) {
+            // grouped weight-only with room for a reordered copy of A: the kernel of the HiF4 x HiF4 grouped calls
+            if (int rc = launch_bf16_to_planes(a, M, K, lda, workspace, stream)) return rc;
+            return launch_gemm_colwave(workspace, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, colwave_rows(M, E), stream);
+        }
         g.a = static_cast<const uint16_t *>(a);
         g.lda = lda;
         a_cell = false;

@@ -215,6 +215,8 @@ def hif4_grouped_gemm(a_kind, a, a_meta, w_codes, w_meta, offs, out_dtype=HIF4_O
     if c is None:
         c = torch.empty((M, N), dtype=torch.bfloat16 if out_dtype == HIF4_OUT_BF16 else torch.float32, device=a.device)
     need = hif4_gemm_workspace_bytes(a_kind, M, K)
+    if a_kind == HIF4_A_BF16_KEEP:
+        need = M * K * 2  # optional: room for a reordered copy of A selects the faster kernel
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
     wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()

@@ -231,10 +231,15 @@ def test_grouped_gemm_weight_only(h, oracle):
     wdec = oracle.dequantize(wc, wm)
     want = np.concatenate([oracle.gemm_f64(ab[offs[e]:offs[e + 1]], wdec[e * N:(e + 1) * N]) for e in range(E)])
     wcd, wmd = dev_packed(wc.reshape(E, N, K // 2), wm.reshape(E, N, K // 64))
-    c = h.hif4_grouped_gemm(h.HIF4_A_BF16_KEEP, synth.from_bits(ab).cuda(), None, wcd, wmd,
-                            torch.from_numpy(offs).cuda(), out_dtype=h.HIF4_OUT_F32)
+    ad = synth.from_bits(ab).cuda()
+    c = h.hif4_grouped_gemm(h.HIF4_A_BF16_KEEP, ad, None, wcd, wmd, torch.from_numpy(offs).cuda(), out_dtype=h.HIF4_OUT_F32)
+    # without room for a reordered copy of A (the workspace is optional for this kind): the other kernel
+    tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
+    c2 = h.hif4_grouped_gemm(h.HIF4_A_BF16_KEEP, ad, None, wcd, wmd, torch.from_numpy(offs).cuda(), out_dtype=h.HIF4_OUT_F32,
+                             workspace=tiny)
     torch.cuda.synchronize()
     assert rel_fro(c.cpu().numpy().astype(np.float64), want) <= TOL
+    assert rel_fro(c2.cpu().numpy().astype(np.float64), want) <= TOL
 
 
 def test_grouped_gemm_moe_config_sampled(h, oracle):
