@@ -173,7 +173,8 @@ size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K)
  * per element) and runs its main loop on the decoded values of both operands.  The products are the same
  * and exact; the fp32 additions are grouped differently, so results agree to fp32 summation
  * accuracy, not always bit for bit.  Equals hif4_gemm_workspace_bytes() when M is too small for
- * this to pay (below 4096 rows).  A workspace between the two sizes is used as
+ * this to pay (below 4096 rows), except for a_kind 2 with 65 to 192 rows, where M * K * 2
+ * bytes for a reordered copy of A select a faster kernel.  A workspace between the two sizes is used as
  * the smaller one.  Host function.
  */
 size_t hif4_gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);

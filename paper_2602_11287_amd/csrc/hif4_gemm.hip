@@ -540,19 +540,22 @@ size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
 #endif
 constexpr int64_t DECODED_W_MIN_ROWS = HIF4_DECODED_W_MIN_ROWS;
 
-size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
-{
-    const size_t base = gemm_workspace_bytes(a_kind, M, K);
-    if (M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
-    if (a_kind == HIF4_A_BF16_KEEP) return align16((size_t)M * (size_t)K * 2) + (size_t)N * (size_t)K * 2; // A as planes, W decoded
-    return align16(base) + (size_t)N * (size_t)K * 2;
-}
-
 // A dense call between HiF4 operands with at most this many rows is one m-tile of that kernel.
 #ifndef HIF4_COLWAVE_MAX_ROWS
 #define HIF4_COLWAVE_MAX_ROWS 192
 #endif
 constexpr int64_t COLWAVE_MAX_ROWS = HIF4_COLWAVE_MAX_ROWS;
+
+size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
+{
+    const size_t base = gemm_workspace_bytes(a_kind, M, K);
+    // weight-only with 65 .. 192 rows: room for a reordered copy of A selects the kernel of hif4_gemm_colwave.hip
+    if (a_kind == HIF4_A_BF16_KEEP && M > 64 && M <= COLWAVE_MAX_ROWS && N > 0 && K > 0) return (size_t)M * (size_t)K * 2;
+    if (M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
+    if (a_kind == HIF4_A_BF16_KEEP) return align16((size_t)M * (size_t)K * 2) + (size_t)N * (size_t)K * 2; // A as planes, W decoded
+    return align16(base) + (size_t)N * (size_t)K * 2;
+}
+
 #ifndef HIF4_COLWAVE_ROWS
 #define HIF4_COLWAVE_ROWS -1
 #endif
@@ -609,11 +612,12 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, ws + a_bytes, stream)) return rc;
             return launch_gemm_planes(ws, ws + a_bytes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
-        if (offs && colwave_rows(M, E) > 0 && colwave_fits(M, N, K) && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
-            workspace_bytes >= (size_t)M * (size_t)K * 2) {
-            // grouped weight-only with room for a reordered copy of A: the kernel of the HiF4 x HiF4 grouped calls
+        if ((offs ? colwave_rows(M, E) > 0 : M <= COLWAVE_MAX_ROWS) && !emit && colwave_fits(M, N, K) && workspace &&
+            (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 && workspace_bytes >= (size_t)M * (size_t)K * 2) {
+            // weight-only, grouped or with at most 192 rows, and room for a reordered copy of A: the kernel of
+            // the HiF4 x HiF4 calls of those shapes
             if (int rc = launch_bf16_to_planes(a, M, K, lda, workspace, stream)) return rc;
-            return launch_gemm_colwave(workspace, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, colwave_rows(M, E), stream);
+            return launch_gemm_colwave(workspace, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : (int)M, stream);
         }
         g.a = static_cast<const uint16_t *>(a);
         g.lda = lda;

@@ -557,3 +557,21 @@ def test_few_row_and_grouped_kernel_strided_output(h, oracle):
     torch.cuda.synchronize()
     assert (cbuf[:, N:] == -1.0).all()
     assert rel_fro(cbuf[:, :N].double().cpu().numpy(), want_g) <= TOL
+
+
+def test_gemm_weight_only_few_rows_optional_workspace(h, oracle):
+    """65 to 192 rows, BF16 activations: with the optional workspace (the binding's default) the call runs the
+    column-per-wave kernel on a reordered copy of A, without it the tile kernel; both against the oracle."""
+    M, N, K = 130, 520, 448
+    ab, _, (wc, wm) = quantized_operands(oracle, M, N, K, 9001)
+    want = oracle.gemm_f64(ab, oracle.dequantize(wc, wm))
+    a = synth.from_bits(ab).cuda()
+    wcd, wmd = dev_packed(wc, wm)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(h.HIF4_A_BF16_KEEP, M, N, K) == M * K * 2
+    assert h.hif4_gemm_workspace_bytes(h.HIF4_A_BF16_KEEP, M, K) == 0
+    c_ws = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    c_no = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32,
+                       workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert rel_fro(c_ws.cpu().numpy().astype(np.float64), want) <= TOL
+    assert rel_fro(c_no.cpu().numpy().astype(np.float64), want) <= TOL
