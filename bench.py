@@ -196,7 +196,8 @@ def main():
         xb = synth.bits(base)
         oracle.quantize(xb[:64])  # warm
         reps, spent = 0, 0.0
-        while spent < 10.0 and reps < 8:
+        # bounded sample: about 1.5 s of wall time on all host threads (some 20 core-seconds of oracle work)
+        while spent < 1.5 and reps < 512:
             t = time.perf_counter()
             wc, wm = oracle.quantize(xb)
             oracle.dequantize(wc, wm)
