@@ -306,11 +306,16 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
 #define HIF4_COLWAVE_R 4
 #define HIF4_COLWAVE_WPS 2
 #endif
+// waves per workgroup of a dense call (one expert, at most 192 rows): the grid is N / (32 NW)
+// workgroups, and half as many columns per workgroup fill the chip better at every width measured
+#ifndef HIF4_COLWAVE_NW_DENSE
+#define HIF4_COLWAVE_NW_DENSE 4
+#endif
 
-template <int TMAX>
+template <int TMAX, int NW>
 static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
 {
-    constexpr int NW = HIF4_COLWAVE_NW, NB = HIF4_COLWAVE_NB, R = HIF4_COLWAVE_R, WPS = HIF4_COLWAVE_WPS;
+    constexpr int NB = HIF4_COLWAVE_NB, R = HIF4_COLWAVE_R, WPS = HIF4_COLWAVE_WPS;
     constexpr int BM = 32 * TMAX;
     constexpr size_t lds_bytes = ColwaveShape<NW, NB, R>::lds_bytes(TMAX);
     static_assert(lds_bytes <= 160 * 1024, "fits the LDS of one CU");
@@ -356,10 +361,16 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
     g.N = (int)N;
     g.K = (int)K;
     g.E = E;
-    if (rows_per_tile <= 64) return launch_colwave_t<2>(g, out_dtype, stream);
-    if (rows_per_tile <= 128) return launch_colwave_t<4>(g, out_dtype, stream);
-    if (rows_per_tile <= 192) return launch_colwave_t<6>(g, out_dtype, stream);
-    return launch_colwave_t<8>(g, out_dtype, stream);
+    constexpr int NWG = HIF4_COLWAVE_NW, NWD = HIF4_COLWAVE_NW_DENSE;
+    if (!offs && rows_per_tile <= 192) {
+        if (rows_per_tile <= 64) return launch_colwave_t<2, NWD>(g, out_dtype, stream);
+        if (rows_per_tile <= 128) return launch_colwave_t<4, NWD>(g, out_dtype, stream);
+        return launch_colwave_t<6, NWD>(g, out_dtype, stream);
+    }
+    if (rows_per_tile <= 64) return launch_colwave_t<2, NWG>(g, out_dtype, stream);
+    if (rows_per_tile <= 128) return launch_colwave_t<4, NWG>(g, out_dtype, stream);
+    if (rows_per_tile <= 192) return launch_colwave_t<6, NWG>(g, out_dtype, stream);
+    return launch_colwave_t<8, NWG>(g, out_dtype, stream);
 }
 
 } // namespace hif4
