@@ -67,33 +67,41 @@ struct ColwaveArgs {
     int tiles_m, tiles_n;
 };
 
-// NW waves per workgroup (32 columns each), NB buffers of A, a ring of R steps of packed W.
-template <int NW, int NB, int R>
+// NW waves per workgroup in KS groups of NW / KS (a group takes one KS-th of K, a wave 32 columns of
+// it), NB buffers of A, a ring of R steps of packed W.
+template <int NW, int KS, int NB, int R>
 struct ColwaveShape {
     static constexpr size_t lds_bytes(int tmax)
     {
         const int rg = (32 * tmax + 63) / 64;
-        return (size_t)NB * 8 * 64 * rg * 16 + (size_t)R * NW * 64 * (16 + 4);
+        return (size_t)NB * KS * 8 * 64 * rg * 16 + (size_t)R * NW * 64 * (16 + 4);
     }
 };
 
-template <int TMAX, int NW, int NB, int R, int WPS, bool OUT_F32>
+// KS > 1 (dense calls only): the waves of a workgroup split K as well - wave group kw takes the
+// units [kw K/64/KS, (kw + 1) K/64/KS) - and their partial sums meet in LDS after the loop.  With few
+// rows and not many columns there are too few 32-column strips to give every SIMD its two waves,
+// and a wave alone cannot issue faster than it does; K is the only other axis to cut.
+template <int TMAX, int NW, int KS, int NB, int R, int WPS, bool OUT_F32>
 __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs g)
 {
-    constexpr int BM = 32 * TMAX, BN = 32 * NW;
+    constexpr int NWC = NW / KS;             // waves (32-column strips) across a tile
+    constexpr int BM = 32 * TMAX, BN = 32 * NWC;
     constexpr int RG = (BM + 63) / 64;       // 64-row groups of a tile
     constexpr int BMP = 64 * RG;             // rows of a buffer
-    constexpr int A_CELLS = 8 * BMP;         // cells per A buffer
-    constexpr int IA = (8 * RG + NW - 1) / NW; // A loads per wave and step
+    constexpr int A_CELLS = 8 * BMP;         // cells of one K step of A
+    constexpr int IA = (KS * 8 * RG + NW - 1) / NW; // A loads per wave and step
     constexpr int PER_STEP = IA + 2;         // LDS-writing loads per wave and step
     static_assert(R > NB && NB >= 2, "W(k + 1) must be older than A(k + 1)");
+    static_assert(NW % KS == 0, "whole wave groups");
     extern __shared__ uint4 lds[];
-    uint4 *lds_a = lds;                                  // [NB][8][BMP]
-    uint4 *lds_wc = lds + NB * A_CELLS;                  // [R][NW][64]
+    uint4 *lds_a = lds;                                  // [NB][KS][8][BMP]
+    uint4 *lds_wc = lds + NB * KS * A_CELLS;             // [R][NW][64]
     uint32_t *lds_wm = reinterpret_cast<uint32_t *>(lds_wc + R * NW * 64); // [R][NW][64]
 
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int cw = wave % NWC, kw = wave / NWC; // column strip and K part of this wave
     const int half = lane / 32, l32 = lane % 32;
 
     // ---- which tile: m-tiles are dealt to the 8 XCDs round-robin (block b runs on XCD b % 8), all
@@ -116,31 +124,33 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
         rows_end = g.M;
     }
     const int col0 = tile_n * BN;
-    const int nk = g.K / 64;
+    const int nk = g.K / 64 / KS; // K steps of a wave (the host gives KS > 1 only a K it divides)
+    const int u0 = kw * nk;       // its first unit
     // 32-row blocks of this tile that have rows
     int live = (rows_end - row0 + 31) / 32;
     live = __builtin_amdgcn_readfirstlane(live < TMAX ? live : TMAX);
 
     // ---- load plan.  W: lane (n, h) = (l32, half) takes the 16 bytes of codes [16 h, 16 h + 16)
-    // of each unit of weight row col0 + 32 wave + n, and the unit's metadata word.  A: load
-    // id = wave * IA + i moves cell j = id / RG of rows rg * 64 .. + 63 (rg = id % RG); rows past the
-    // end of the matrix repeat its last row, loads past 8 RG repeat the last one (never read).
+    // of each unit of weight row col0 + 32 cw + n, and the unit's metadata word.  A: load
+    // id = wave * IA + i moves, for wave group ks = id / (8 RG), cell j = id / RG % 8 of rows
+    // rg * 64 .. + 63 (rg = id % RG); rows past the end of the matrix repeat its last row, loads past
+    // 8 RG KS repeat the last one.
     // Every address is a scalar base that moves with the K step plus a fixed 32-bit offset per lane
     // (the host keeps the operands small enough for that).
-    int wrow = col0 + wave * 32 + l32;
+    int wrow = col0 + cw * 32 + l32;
     wrow = wrow < g.N ? wrow : g.N - 1;
-    const uint32_t wc_off = (uint32_t)wrow * (uint32_t)(g.K / 2) + 16u * half;
-    const uint32_t wm_off = (uint32_t)wrow * (uint32_t)(nk * 4);
+    const uint32_t wc_off = (uint32_t)wrow * (uint32_t)(g.K / 2) + 16u * half + (uint32_t)u0 * 32u;
+    const uint32_t wm_off = (uint32_t)wrow * (uint32_t)(g.K / 16) + (uint32_t)u0 * 4u;
     uint32_t a_off[IA], a_dst[IA];
 #pragma unroll
     for (int i = 0; i < IA; ++i) {
         int id = wave * IA + i;
-        id = id < 8 * RG ? id : 8 * RG - 1;
-        const int j = id / RG, rg = id % RG;
+        id = id < KS * 8 * RG ? id : KS * 8 * RG - 1;
+        const int ks = id / (8 * RG), j = id / RG % 8, rg = id % RG;
         int row = row0 + rg * 64 + lane;
         row = row < g.M ? row : g.M - 1;
-        a_off[i] = ((uint32_t)j * (uint32_t)g.M + (uint32_t)row) * 16u;
-        a_dst[i] = (uint32_t)__builtin_amdgcn_readfirstlane((j * BMP + rg * 64) * 16);
+        a_off[i] = ((uint32_t)(ks * nk * 8 + j) * (uint32_t)g.M + (uint32_t)row) * 16u;
+        a_dst[i] = (uint32_t)__builtin_amdgcn_readfirstlane(((ks * 8 + j) * BMP + rg * 64) * 16);
     }
     auto lds_byte_of = [](const void *p) { return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p; };
     const uint32_t a_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_a));
@@ -158,7 +168,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     auto issue_a = [&](int u, int at) {
         const uint64_t base = a_ptr + (uint64_t)(u < nk ? u : nk - 1) * a_step;
 #pragma unroll
-        for (int i = 0; i < IA; ++i) cw_load_to_lds_16(base, a_off[i], a_base + (uint32_t)(at * A_CELLS * 16) + a_dst[i]);
+        for (int i = 0; i < IA; ++i) cw_load_to_lds_16(base, a_off[i], a_base + (uint32_t)(at * KS * A_CELLS * 16) + a_dst[i]);
     };
 
     f32x16_t acc[TMAX];
@@ -219,7 +229,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
         auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
         // A operands of sub-step s from buffer `buf` into set `set`
         auto a_frags = [&](int set, int buf, int s) {
-            const uint4 *src = lds_a + buf * A_CELLS + (4 * half + s) * BMP + l32;
+            const uint4 *src = lds_a + (buf * KS + kw) * A_CELLS + (4 * half + s) * BMP + l32;
 #pragma unroll
             for (int i = 0; i < LIVE; ++i) af[set][i] = src[i * 32];
         };
@@ -283,8 +293,40 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // no load may outlive the workgroup's LDS
 
+    // ---- KS > 1: the partial sums of wave groups 1 .. KS - 1 go through LDS (all loads have landed and
+    // all operands are read once every wave is past the barrier) to group 0, lane for lane
+    if constexpr (KS > 1) {
+        static_assert((size_t)(KS - 1) * NWC * TMAX * 4096 <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX), "partial sums fit the buffers");
+        float4 *red = reinterpret_cast<float4 *>(lds); // [kw - 1][cw][block][4][lane]
+        __syncthreads();
+        if (kw > 0) {
+            float4 *dst = red + (size_t)((kw - 1) * NWC + cw) * TMAX * 256 + lane;
+#pragma unroll
+            for (int i = 0; i < TMAX; ++i) {
+                if (i >= live) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) dst[(i * 4 + q) * 64] = make_float4(acc[i][4 * q], acc[i][4 * q + 1], acc[i][4 * q + 2], acc[i][4 * q + 3]);
+            }
+        }
+        __syncthreads();
+        if (kw > 0) return;
+#pragma unroll
+        for (int p = 0; p < KS - 1; ++p) {
+            const float4 *src = red + (size_t)(p * NWC + cw) * TMAX * 256 + lane;
+#pragma unroll
+            for (int i = 0; i < TMAX; ++i) {
+                if (i >= live) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = src[(i * 4 + q) * 64];
+                    acc[i][4 * q] += v.x, acc[i][4 * q + 1] += v.y, acc[i][4 * q + 2] += v.z, acc[i][4 * q + 3] += v.w;
+                }
+            }
+        }
+    }
+
     // ---- epilogue: lane holds column l32 of each 32 x 32 block, rows 8 (r / 4) + 4 half + r % 4
-    const int col = col0 + wave * 32 + l32;
+    const int col = col0 + cw * 32 + l32;
 #pragma unroll
     for (int i = 0; i < TMAX; ++i) {
         if (i >= live) continue;
@@ -306,31 +348,32 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
 #define HIF4_COLWAVE_R 4
 #define HIF4_COLWAVE_WPS 2
 #endif
-// waves per workgroup of a dense call (one expert, at most 192 rows): the grid is N / (32 NW)
-// workgroups, and half as many columns per workgroup fill the chip better at every width measured
+// waves per workgroup of a dense call (one expert, at most 192 rows) that does not split K: the grid is
+// N / (32 NW) workgroups, and half as many columns per workgroup fill the chip better at every width measured
 #ifndef HIF4_COLWAVE_NW_DENSE
 #define HIF4_COLWAVE_NW_DENSE 4
 #endif
-
-template <int TMAX, int NW>
+template <int TMAX, int NW, int KS>
 static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
 {
-    constexpr int NB = HIF4_COLWAVE_NB, R = HIF4_COLWAVE_R, WPS = HIF4_COLWAVE_WPS;
-    constexpr int BM = 32 * TMAX;
-    constexpr size_t lds_bytes = ColwaveShape<NW, NB, R>::lds_bytes(TMAX);
+    // three buffers of A and four steps of W where LDS has room for them, else two and three
+    constexpr bool DEEP = ColwaveShape<NW, KS, HIF4_COLWAVE_NB, HIF4_COLWAVE_R>::lds_bytes(TMAX) <= 160 * 1024;
+    constexpr int NB = DEEP ? HIF4_COLWAVE_NB : 2, R = DEEP ? HIF4_COLWAVE_R : 3, WPS = HIF4_COLWAVE_WPS;
+    constexpr int BM = 32 * TMAX, BN = 32 * NW / KS;
+    constexpr size_t lds_bytes = ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX);
     static_assert(lds_bytes <= 160 * 1024, "fits the LDS of one CU");
-    g.tiles_n = (g.N + 32 * NW - 1) / (32 * NW);
+    g.tiles_n = (g.N + BN - 1) / BN;
     g.tiles_m = g.offs ? g.M / BM + g.E : (g.M + BM - 1) / BM; // grouped: upper bound of sum_e ceil(rows_e / BM)
     const int64_t blocks = (int64_t)(g.tiles_m >= 8 ? (g.tiles_m + 7) / 8 * 8 : g.tiles_m) * g.tiles_n;
     const dim3 grid((unsigned)blocks), block(64 * NW);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_colwave_kernel<TMAX, NW, NB, R, WPS, true>;
+        auto k = gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, true>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     } else {
-        auto k = gemm_colwave_kernel<TMAX, NW, NB, R, WPS, false>;
+        auto k = gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, false>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
@@ -341,7 +384,7 @@ static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
 // The kernel addresses each operand as a scalar base plus a 32-bit byte offset per lane.
 bool colwave_fits(int64_t M, int64_t N, int64_t K)
 {
-    return M * 128 < ((int64_t)1 << 32) && N * (K / 2) < ((int64_t)1 << 32);
+    return M * 128 < ((int64_t)1 << 32) && N * (K / 2) < ((int64_t)1 << 32) && (M > 192 || M * K * 2 < ((int64_t)1 << 32));
 }
 
 // a_planes: decoded A as cell planes (launch_decode_planes).  offs != nullptr: grouped, E experts;
@@ -363,14 +406,41 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
     g.E = E;
     constexpr int NWG = HIF4_COLWAVE_NW, NWD = HIF4_COLWAVE_NW_DENSE;
     if (!offs && rows_per_tile <= 192) {
-        if (rows_per_tile <= 64) return launch_colwave_t<2, NWD>(g, out_dtype, stream);
-        if (rows_per_tile <= 128) return launch_colwave_t<4, NWD>(g, out_dtype, stream);
-        return launch_colwave_t<6, NWD>(g, out_dtype, stream);
+        const int64_t strips = (N + 31) / 32, nk = K / 64;
+        // K parts per workgroup (4, 2 or 1; 192-row tiles: LDS holds 2) and waves (4 or 8): the most parts
+        // whose workgroups still run in one round (one workgroup per CU), with 4 waves rather than 8 when
+        // both do - measured: twice the CUs beat twice the waves per CU.  Parts divide K's units and keep
+        // at least 8 steps each.
+        int ks = rows_per_tile > 128 ? 2 : 4, nw = NWD;
+#ifdef HIF4_COLWAVE_FORCE_KS
+        ks = HIF4_COLWAVE_FORCE_KS < ks ? HIF4_COLWAVE_FORCE_KS : ks, nw = HIF4_COLWAVE_FORCE_NW;
+        while (ks > 1 && (nk % ks != 0 || nk / ks < 4)) ks /= 2;
+        if (ks == 1) nw = NWD;
+#else
+        for (; ks > 1; ks /= 2) {
+            if (nk % ks != 0 || nk / ks < 8) continue;
+            if (strips * ks <= 4 * 256) { nw = 4; break; }
+            if (strips * ks <= 8 * 256) { nw = 8; break; }
+        }
+        if (ks == 1) nw = NWD;
+#endif
+#define HIF4_CW_CASE(T, W, S) if (nw == W && ks == S) return launch_colwave_t<T, W, S>(g, out_dtype, stream)
+        if (rows_per_tile <= 64) {
+            HIF4_CW_CASE(2, 8, 4); HIF4_CW_CASE(2, 8, 2); HIF4_CW_CASE(2, 4, 4); HIF4_CW_CASE(2, 4, 2);
+            return launch_colwave_t<2, NWD, 1>(g, out_dtype, stream);
+        }
+        if (rows_per_tile <= 128) {
+            HIF4_CW_CASE(4, 8, 4); HIF4_CW_CASE(4, 8, 2); HIF4_CW_CASE(4, 4, 4); HIF4_CW_CASE(4, 4, 2);
+            return launch_colwave_t<4, NWD, 1>(g, out_dtype, stream);
+        }
+        HIF4_CW_CASE(6, 8, 2); HIF4_CW_CASE(6, 4, 2);
+        return launch_colwave_t<6, NWD, 1>(g, out_dtype, stream);
+#undef HIF4_CW_CASE
     }
-    if (rows_per_tile <= 64) return launch_colwave_t<2, NWG>(g, out_dtype, stream);
-    if (rows_per_tile <= 128) return launch_colwave_t<4, NWG>(g, out_dtype, stream);
-    if (rows_per_tile <= 192) return launch_colwave_t<6, NWG>(g, out_dtype, stream);
-    return launch_colwave_t<8, NWG>(g, out_dtype, stream);
+    if (rows_per_tile <= 64) return launch_colwave_t<2, NWG, 1>(g, out_dtype, stream);
+    if (rows_per_tile <= 128) return launch_colwave_t<4, NWG, 1>(g, out_dtype, stream);
+    if (rows_per_tile <= 192) return launch_colwave_t<6, NWG, 1>(g, out_dtype, stream);
+    return launch_colwave_t<8, NWG, 1>(g, out_dtype, stream);
 }
 
 } // namespace hif4

@@ -43,7 +43,11 @@ def quantized_operands(oracle, M, N, K, seed, a_outliers=True):
 
 SHAPES = [(1, 1, 64), (32, 32, 64), (256, 256, 64), (257, 255, 128), (333, 520, 1024), (5, 1000, 192), (600, 70, 320),
           # up to 192 rows: one m-tile of the kernel that expands W into MFMA operands (32-row blocks, 256-column tiles)
-          (65, 257, 192), (129, 520, 320), (192, 300, 1088), (160, 33, 64)]
+          (65, 257, 192), (129, 520, 320), (192, 300, 1088), (160, 33, 64),
+          # the same kernel with K split over the waves of a workgroup (K/64 divisible by 2 or 4 and at least 8
+          # steps per part): 64-, 128- and 192-row tiles, 4 or 2 parts, 4 waves (narrow N) or 8 (wide N)
+          (33, 100, 2048), (40, 100, 1024), (100, 100, 2048), (128, 257, 1024), (150, 96, 1024),
+          (20, 8300, 2048), (100, 8300, 2048), (10, 16500, 1024), (70, 16500, 1024), (150, 16500, 1024)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -557,6 +561,23 @@ def test_few_row_and_grouped_kernel_strided_output(h, oracle):
     torch.cuda.synchronize()
     assert (cbuf[:, N:] == -1.0).all()
     assert rel_fro(cbuf[:, :N].double().cpu().numpy(), want_g) <= TOL
+
+
+@pytest.mark.parametrize("M,N,K", [(100, 100, 2048), (150, 300, 1024), (30, 8300, 2048)])
+def test_gemm_few_rows_k_split_other_kinds(h, oracle, M, N, K):
+    """The few-row kernel with K split inside the workgroup, reached by the other two kinds of A: quantised in the
+    call (fused encode-to-planes pre-pass) and plain BF16 with the optional workspace."""
+    ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 4242 + M)
+    wd = oracle.dequantize(wc, wm)
+    a = synth.from_bits(ab).cuda()
+    wcd, wmd = dev_packed(wc, wm)
+    cq = h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    assert rel_fro(cq.cpu().numpy().astype(np.float64), oracle.gemm_f64(oracle.dequantize(ac, am), wd)) <= TOL
+    if M > 64:
+        ck = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+        torch.cuda.synchronize()
+        assert rel_fro(ck.cpu().numpy().astype(np.float64), oracle.gemm_f64(ab, wd)) <= TOL
 
 
 def test_gemm_weight_only_few_rows_optional_workspace(h, oracle):
