@@ -18,6 +18,8 @@
 // the same kind of load, 16 bytes of codes and the metadata word per lane and step.  So every
 // global load of the loop is an LDS-writing one with a fixed count per wave and step, and one
 // s_waitcnt vmcnt(N) per step covers exactly the loads that step needs.
+// (Dense calls have one expert's worth of workgroups only; there the launcher takes 4 waves per
+// workgroup and lets groups of waves split K, see the kernel's template arguments.)
 //
 // K order: sub-step s (of 4, a K slab of 16) takes group 4 h + s of a unit's 8 groups of 8
 // from lane half h, for both operands, so a lane's 4 dwords of codes per unit are contiguous.
