@@ -137,7 +137,11 @@ int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
  * round it, and every row of C is then converted by Algorithm 1 (Section II-B) with units of 64
  * consecutive columns, i.e. along the axis the next linear layer reduces over (the paper converts
  * every linear layer's input before its matrix product, Section IV).  The planes equal
- * hif4_quantize(result of hif4_gemm with HIF4_OUT_BF16) bit for bit; C never crosses HBM as BF16.
+ * hif4_quantize(result of hif4_gemm with HIF4_OUT_BF16) bit for bit where hif4_gemm runs the same
+ * main loop (more than 2048 rows, or ceil(N/32) * ceil(M/128) > 2048 with more than 192 rows, and the
+ * same workspace size); for the small shapes that hif4_gemm gives to its few-row kernel the fp32
+ * additions are grouped differently, so a BF16 value may now and then round the other way.
+ * C never crosses HBM as BF16.
  *   c_codes  out  uint8 [M][N/2], c_meta out uint32 [M][N/64];  N a multiple of 64
  * Other arguments, workspace and errors as hif4_gemm.
  */
@@ -173,8 +177,9 @@ size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K)
  * per element) and runs its main loop on the decoded values of both operands.  The products are the same
  * and exact; the fp32 additions are grouped differently, so results agree to fp32 summation
  * accuracy, not always bit for bit.  Equals hif4_gemm_workspace_bytes() when M is too small for
- * this to pay (below 4096 rows), except for a_kind 2 with 65 to 192 rows, where M * K * 2
- * bytes for a reordered copy of A select a faster kernel.  A workspace between the two sizes is used as
+ * this to pay (below 4096 rows), except for a_kind 2 with more than 64 rows on the shapes of the
+ * few-row kernel (up to 192 rows, or up to 2048 rows with ceil(N/32) * ceil(M/128) <= 2048), where
+ * M * K * 2 bytes for a reordered copy of A select that kernel.  A workspace between the two sizes is used as
  * the smaller one.  Host function.
  */
 size_t hif4_gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);

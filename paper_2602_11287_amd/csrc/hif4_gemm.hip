@@ -545,12 +545,39 @@ constexpr int64_t DECODED_W_MIN_ROWS = HIF4_DECODED_W_MIN_ROWS;
 #define HIF4_COLWAVE_MAX_ROWS 192
 #endif
 constexpr int64_t COLWAVE_MAX_ROWS = HIF4_COLWAVE_MAX_ROWS;
+// Rows of A per workgroup of that kernel for a dense call, 0: not its case.  Up to 192 rows: one tile.
+// Beyond, every m-tile expands W again, which pays only while the whole call is small: at most
+// HIF4_COLWAVE_DENSE_STRIPS (32-column strip, 128-row tile) pairs, i.e. one round of two waves per SIMD
+// (measured against the tile kernel at 256 to 1024 rows and 2048 to 28672 columns).  Tiles of 128 rows
+// while those pairs leave SIMDs idle, else the tile height (128, 192, 256) that covers M with the
+// least padding, the fewest tiles among equals.
+#ifndef HIF4_COLWAVE_DENSE_STRIPS
+#define HIF4_COLWAVE_DENSE_STRIPS 2048
+#endif
+static int colwave_dense_rows(int64_t M, int64_t N)
+{
+    if (M <= COLWAVE_MAX_ROWS) return (int)M;
+    const int64_t s128 = (N + 31) / 32 * ((M + 127) / 128);
+    if (s128 > HIF4_COLWAVE_DENSE_STRIPS || M > 2048) return 0;
+#ifdef HIF4_COLWAVE_DENSE_TILE
+    return HIF4_COLWAVE_DENSE_TILE;
+#endif
+    if (s128 <= 1024) return 128;
+    int best = 128;
+    int64_t best_pad = (M + 127) / 128 * 128 - M, best_tiles = (M + 127) / 128;
+    for (int rows = 192; rows <= 256; rows += 64) {
+        const int64_t tiles = (M + rows - 1) / rows, pad = tiles * rows - M;
+        if (pad < best_pad || (pad == best_pad && tiles < best_tiles)) best = rows, best_pad = pad, best_tiles = tiles;
+    }
+    return best;
+}
 
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
 {
     const size_t base = gemm_workspace_bytes(a_kind, M, K);
-    // weight-only with 65 .. 192 rows: room for a reordered copy of A selects the kernel of hif4_gemm_colwave.hip
-    if (a_kind == HIF4_A_BF16_KEEP && M > 64 && M <= COLWAVE_MAX_ROWS && N > 0 && K > 0) return (size_t)M * (size_t)K * 2;
+    // weight-only with more than 64 rows in the range of the kernel of hif4_gemm_colwave.hip: room for a reordered
+    // copy of A selects it
+    if (a_kind == HIF4_A_BF16_KEEP && M > 64 && N > 0 && K > 0 && colwave_dense_rows(M, N) > 0) return (size_t)M * (size_t)K * 2;
     if (M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
     if (a_kind == HIF4_A_BF16_KEEP) return align16((size_t)M * (size_t)K * 2) + (size_t)N * (size_t)K * 2; // A as planes, W decoded
     return align16(base) + (size_t)N * (size_t)K * 2;
@@ -612,12 +639,12 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, ws + a_bytes, stream)) return rc;
             return launch_gemm_planes(ws, ws + a_bytes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
-        if ((offs ? colwave_rows(M, E) > 0 : M <= COLWAVE_MAX_ROWS) && !emit && colwave_fits(M, N, K) && workspace &&
+        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && !emit && colwave_fits(M, N, K) && workspace &&
             (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 && workspace_bytes >= (size_t)M * (size_t)K * 2) {
-            // weight-only, grouped or with at most 192 rows, and room for a reordered copy of A: the kernel of
+            // weight-only, grouped or a small dense call (colwave_dense_rows), and room for a reordered copy of A: the kernel of
             // the HiF4 x HiF4 calls of those shapes
             if (int rc = launch_bf16_to_planes(a, M, K, lda, workspace, stream)) return rc;
-            return launch_gemm_colwave(workspace, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : (int)M, stream);
+            return launch_gemm_colwave(workspace, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
         }
         g.a = static_cast<const uint16_t *>(a);
         g.lda = lda;
@@ -642,8 +669,8 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
             return launch_gemm_planes(adec, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
-        if ((offs ? colwave_rows(M, E) > 0 : M <= COLWAVE_MAX_ROWS) && colwave_fits(M, N, K) && !emit) {
-            // grouped, or so few rows that there is one m-tile: every weight meets those few rows only,
+        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K) && !emit) {
+            // grouped, or a dense call of few rows (one m-tile, or a few on a small N): every weight meets few rows only,
             // so the kernel that expands W straight into MFMA operands takes the call
             // (hif4_gemm_colwave.hip); A as cell planes
             if (a_kind == HIF4_A_BF16_QUANTIZE) {
@@ -652,7 +679,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             } else {
                 if (int rc = launch_decode_planes(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
             }
-            return launch_gemm_colwave(adec, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : (int)M, stream);
+            return launch_gemm_colwave(adec, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
         }
         if (a_kind == HIF4_A_BF16_QUANTIZE) {
             // quantise and decode in one pass: the packed activations are never needed in memory

@@ -386,7 +386,7 @@ static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
 // The kernel addresses each operand as a scalar base plus a 32-bit byte offset per lane.
 bool colwave_fits(int64_t M, int64_t N, int64_t K)
 {
-    return M * 128 < ((int64_t)1 << 32) && N * (K / 2) < ((int64_t)1 << 32) && (M > 192 || M * K * 2 < ((int64_t)1 << 32));
+    return M * 128 < ((int64_t)1 << 32) && N * (K / 2) < ((int64_t)1 << 32) && M * K * 2 < ((int64_t)1 << 32);
 }
 
 // a_planes: decoded A as cell planes (launch_decode_planes).  offs != nullptr: grouped, E experts;
@@ -407,12 +407,12 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
     g.K = (int)K;
     g.E = E;
     constexpr int NWG = HIF4_COLWAVE_NW, NWD = HIF4_COLWAVE_NW_DENSE;
-    if (!offs && rows_per_tile <= 192) {
-        const int64_t strips = (N + 31) / 32, nk = K / 64;
-        // K parts per workgroup (4, 2 or 1; 192-row tiles: LDS holds 2) and waves (4 or 8): the most parts
-        // whose workgroups still run in one round (one workgroup per CU), with 4 waves rather than 8 when
-        // both do - measured: twice the CUs beat twice the waves per CU.  Parts divide K's units and keep
-        // at least 8 steps each.
+    if (!offs) {
+        const int64_t strips = (N + 31) / 32 * ((M + rows_per_tile - 1) / rows_per_tile), nk = K / 64;
+        // K parts per workgroup (4, 2 or 1; tiles of more than 128 rows: LDS holds 2) and waves (4 or 8): the
+        // most parts whose workgroups still run in one round (one workgroup per CU), with 4 waves rather than
+        // 8 when both do - measured: twice the CUs beat twice the waves per CU.  Parts divide K's units and
+        // keep at least 8 steps each.
         int ks = rows_per_tile > 128 ? 2 : 4, nw = NWD;
 #ifdef HIF4_COLWAVE_FORCE_KS
         ks = HIF4_COLWAVE_FORCE_KS < ks ? HIF4_COLWAVE_FORCE_KS : ks, nw = HIF4_COLWAVE_FORCE_NW;
@@ -435,8 +435,12 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
             HIF4_CW_CASE(4, 8, 4); HIF4_CW_CASE(4, 8, 2); HIF4_CW_CASE(4, 4, 4); HIF4_CW_CASE(4, 4, 2);
             return launch_colwave_t<4, NWD, 1>(g, out_dtype, stream);
         }
-        HIF4_CW_CASE(6, 8, 2); HIF4_CW_CASE(6, 4, 2);
-        return launch_colwave_t<6, NWD, 1>(g, out_dtype, stream);
+        if (rows_per_tile <= 192) {
+            HIF4_CW_CASE(6, 8, 2); HIF4_CW_CASE(6, 4, 2);
+            return launch_colwave_t<6, NWD, 1>(g, out_dtype, stream);
+        }
+        HIF4_CW_CASE(8, 8, 2); HIF4_CW_CASE(8, 4, 2);
+        return launch_colwave_t<8, NWD, 1>(g, out_dtype, stream);
 #undef HIF4_CW_CASE
     }
     if (rows_per_tile <= 64) return launch_colwave_t<2, NWG, 1>(g, out_dtype, stream);
