@@ -111,6 +111,23 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
         "roofline": {"bound": "hbm", "kernel": "hif4::gemm_skinny_kernel<1,8>", "achieved": round(nbytes / ms / 1e6, 1),
                      "peak": hbm_peak_gbps, "unit": "GB/s", "frac": round(nbytes / ms / 1e6 / hbm_peak_gbps, 4),
                      "traffic": _TRAFFIC.get("gemm_weight_only_M16_N4096_K4096")}}
+    # the same weights against more rows (W4A4, activations quantised inside the call): the few-row kernel with K
+    # split over wave groups, then several m-tiles of it, then the tile kernel; the vendor BF16 GEMM on the same
+    # shape beside each
+    sweep = {}
+    for Ms in (32, 128, 512, 1024, 2048):
+        a_s = _randn_bf16((Ms, K), 1.0, gen, dev)
+        c_s = torch.empty((Ms, N), dtype=torch.bfloat16, device=dev)
+        ws_s = torch.empty(max(16, hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, Ms, K)), dtype=torch.uint8, device=dev)
+        fs = lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a_s, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c_s, workspace=ws_s)
+        fv = lambda: torch.matmul(a_s, w.t(), out=c_s)
+        for fn in (fs, fv):
+            for _ in range(2):
+                fn()
+        us, us_v = _timed(fs, max(steps, 10)) * 1e3, _timed(fv, max(steps, 10)) * 1e3
+        sweep[f"M{Ms}"] = {"us": round(us, 1), "TFLOPs": round(2.0 * Ms * N * K / us / 1e6, 1), "vendor_bf16_us": round(us_v, 1)}
+        del a_s, c_s, ws_s
+    legs["gemm_w4a4_quantize_inside_rows_sweep_N4096_K4096"] = sweep
     del w, wc, wm
 
     def mfma_leg(name, M, N, K, fn, kernel):
