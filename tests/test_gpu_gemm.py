@@ -609,6 +609,32 @@ def test_gemm_few_rows_k_split_other_kinds(h, oracle, M, N, K):
         assert rel_fro(ck.cpu().numpy().astype(np.float64), oracle.gemm_f64(ab, wd)) <= TOL
 
 
+@pytest.mark.parametrize("M,N,K", [(512, 4096, 4096), (1024, 2048, 7168), (384, 11008, 4096), (250, 28672, 2048)])
+def test_gemm_few_row_kernel_several_m_tiles_sampled(h, oracle, M, N, K):
+    """Small dense calls of more than 192 rows run as several m-tiles of the few-row kernel (tiles of 128, 192 or
+    256 rows, with or without K split): a seeded sample of rows x columns including both ends, activations
+    quantised in the call, and the weight-only kind on the same kernel."""
+    gen = torch.Generator().manual_seed(1000 + M)
+    a = torch.randn((M, K), generator=gen).to(torch.bfloat16)
+    w = (torch.randn((N, K), generator=gen) * 0.02).to(torch.bfloat16)
+    wcd, wmd = h.hif4_quantize(w.cuda())
+    wc, wm = wcd.cpu().numpy(), wmd.cpu().numpy().view(np.uint32)
+    c = h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, a.cuda(), None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(h.HIF4_A_BF16_KEEP, M, N, K) == M * K * 2
+    ck = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a.cuda(), None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(M)
+    rows = np.sort(np.concatenate([rng.choice(M, 62, replace=False), [0, M - 1]]))
+    cols = np.sort(np.concatenate([rng.choice(N, 126, replace=False), [0, N - 1]]))
+    wdec = oracle.dequantize(wc[cols], wm[cols])
+    ac, am = oracle.quantize(synth.bits(a)[rows])
+    pick = lambda t: t[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
+    want = oracle.gemm_f64(oracle.dequantize(ac, am), wdec)
+    assert rel_fro(pick(c), want) <= TOL, rel_fro(pick(c), want)
+    want_k = oracle.gemm_f64(synth.bits(a)[rows], wdec)
+    assert rel_fro(pick(ck), want_k) <= TOL, rel_fro(pick(ck), want_k)
+
+
 def test_gemm_weight_only_few_rows_optional_workspace(h, oracle):
     """65 to 192 rows, BF16 activations: with the optional workspace (the binding's default) the call runs the
     column-per-wave kernel on a reordered copy of A, without it the tile kernel; both against the oracle."""
