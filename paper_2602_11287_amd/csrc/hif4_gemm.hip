@@ -312,7 +312,9 @@ constexpr int skinny_nbuf(int mb) { return mb == 1 ? HIF4_SKINNY_NBUF1 : mb == 2
 // latency is occupancy (about 80 registers and 4 KB of LDS per wave let three workgroups share
 // a CU; with four pairs in flight per wave and one workgroup per CU the same kernel was measured
 // 20 to 35 % slower).
-template <int MB, int WAVES, bool OUT_F32>
+// A_CELL: the rows of `a` already hold every group of 8 in cell order (the library's decoded copy of HiF4
+// activations, see launch_decode_cells): no permutation on the way in.
+template <int MB, int WAVES, bool OUT_F32, bool A_CELL = false>
 __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const uint16_t *__restrict__ a, int64_t lda,
                                                                  const uint32_t *__restrict__ w_codes,
                                                                  const uint32_t *__restrict__ w_meta, void *c,
@@ -377,7 +379,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const uint16_t 
                 uint4 *sl = slab;
                 // lane (piece n_l, row 4r + q) -> cell [n_l][row]
 #pragma unroll
-                for (int r = 0; r < NLD; ++r) sl[n_l * RSTRIDE + 4 * r + q] = permute_bf16_cell(fl[i].a[r]);
+                for (int r = 0; r < NLD; ++r) sl[n_l * RSTRIDE + 4 * r + q] = A_CELL ? fl[i].a[r] : permute_bf16_cell(fl[i].a[r]);
                 const uint4 wc = fl[i].wc;
                 const uint32_t m = fl[i].m;
                 issue(fl[i], p + i + NBUF);
@@ -417,7 +419,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const uint16_t 
     }
 }
 
-template <int MB>
+template <int MB, bool A_CELL = false>
 static int launch_skinny(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N,
                          int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream)
 {
@@ -430,12 +432,12 @@ static int launch_skinny(const void *a, int64_t lda, const uint8_t *w_codes, con
     const uint32_t *wc = reinterpret_cast<const uint32_t *>(w_codes);
     hipError_t e;
     if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_skinny_kernel<MB, WAVES, true>;
+        auto k = gemm_skinny_kernel<MB, WAVES, true, A_CELL>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, ap, lda, wc, w_meta, c, ldc, (int)M, (int)N, (int)K);
     } else {
-        auto k = gemm_skinny_kernel<MB, WAVES, false>;
+        auto k = gemm_skinny_kernel<MB, WAVES, false, A_CELL>;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, ap, lda, wc, w_meta, c, ldc, (int)M, (int)N, (int)K);
@@ -545,6 +547,18 @@ constexpr int64_t DECODED_W_MIN_ROWS = HIF4_DECODED_W_MIN_ROWS;
 #define HIF4_COLWAVE_MAX_ROWS 192
 #endif
 constexpr int64_t COLWAVE_MAX_ROWS = HIF4_COLWAVE_MAX_ROWS;
+// Up to 64 rows, two kernels can take a dense call whatever the kind of A (each after a pre-pass that puts A
+// into its form): the one that splits K over the waves of 16-column workgroups (gemm_skinny_kernel) and the
+// one that expands W into MFMA operands per 32-column strip (hif4_gemm_colwave.hip).  Measured from HIP graphs
+// (us, pre-pass included, first kernel : second): 16 x 4096 x 4096 9 : 19, 64 x 4096 x 4096 15 : 19,
+// 32 x 11008 x 4096 21 : 22, 64 x 11008 x 4096 34 : 25, 16 x 28672 x 8192 51 : 65, 32 x 28672 x 8192 72 : 67,
+// 64 x 28672 x 8192 101 : 74 - the first wins on few rows or few weights.
+static bool few_rows_prefer_k_split(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t weights = N * K;
+    return M <= 16 || (M <= 32 && weights <= ((int64_t)48 << 20)) || (M <= 64 && weights <= ((int64_t)24 << 20));
+}
+
 // Rows of A per workgroup of that kernel for a dense call, 0: not its case.  Up to 192 rows: one tile.
 // Beyond, every m-tile expands W again, which pays only while the whole call is small: at most
 // HIF4_COLWAVE_DENSE_STRIPS (32-column strip, 128-row tile) pairs, i.e. one round of two waves per SIMD
@@ -577,7 +591,8 @@ size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t 
     const size_t base = gemm_workspace_bytes(a_kind, M, K);
     // weight-only with more than 64 rows in the range of the kernel of hif4_gemm_colwave.hip: room for a reordered
     // copy of A selects it
-    if (a_kind == HIF4_A_BF16_KEEP && M > 64 && N > 0 && K > 0 && colwave_dense_rows(M, N) > 0) return (size_t)M * (size_t)K * 2;
+    if (a_kind == HIF4_A_BF16_KEEP && N > 0 && K > 0 && (M > 64 ? colwave_dense_rows(M, N) > 0 : M > 0 && !few_rows_prefer_k_split(M, N, K)))
+        return (size_t)M * (size_t)K * 2;
     if (M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
     if (a_kind == HIF4_A_BF16_KEEP) return align16((size_t)M * (size_t)K * 2) + (size_t)N * (size_t)K * 2; // A as planes, W decoded
     return align16(base) + (size_t)N * (size_t)K * 2;
@@ -613,7 +628,9 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         }
         return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
     }
-    if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64 && !emit) { // decode-shaped: stream the weights once
+    if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64 && !emit &&
+        (few_rows_prefer_k_split(M, N, K) || !colwave_fits(M, N, K) || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 15) != 0 ||
+         workspace_bytes < (size_t)M * (size_t)K * 2)) { // decode-shaped: stream the weights once
         // 33 to 64 rows against many columns: columns split over workgroups only, whole K per wave, the
         // activations shared through LDS (hif4_gemm_stream.hip; measured 96 us against 122 us for
         // 64 x 28672 x 8192, 38 against 43 us at 14336 x 4096, 36 against 30 us at 11008 x 4096).  With
@@ -668,6 +685,18 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             }
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
             return launch_gemm_planes(adec, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
+        }
+        if (!offs && !emit && M <= 64 && few_rows_prefer_k_split(M, N, K)) {
+            // few rows against not too many weights: the kernel of the weight-only decode shape, fed with the exact
+            // BF16 values of the HiF4 activations (cell order, dense rows)
+            if (a_kind == HIF4_A_BF16_QUANTIZE) {
+                if (int rc = launch_encode_to_cells(a, M, K, lda, adec, HIF4_ROUND_RNE, stream)) return rc;
+            } else {
+                if (int rc = launch_decode_cells(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
+            }
+            if (M <= 16) return launch_skinny<1, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+            if (M <= 32) return launch_skinny<2, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+            return launch_skinny<4, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         }
         if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K) && !emit) {
             // grouped, or a dense call of few rows (one m-tile, or a few on a small N): every weight meets few rows only,

@@ -47,7 +47,10 @@ SHAPES = [(1, 1, 64), (32, 32, 64), (256, 256, 64), (257, 255, 128), (333, 520, 
           # the same kernel with K split over the waves of a workgroup (K/64 divisible by 2 or 4 and at least 8
           # steps per part): 64-, 128- and 192-row tiles, 4 or 2 parts, 4 waves (narrow N) or 8 (wide N)
           (33, 100, 2048), (40, 100, 1024), (100, 100, 2048), (128, 257, 1024), (150, 96, 1024),
-          (20, 8300, 2048), (100, 8300, 2048), (10, 16500, 1024), (70, 16500, 1024), (150, 16500, 1024)]
+          (20, 8300, 2048), (100, 8300, 2048), (10, 16500, 1024), (70, 16500, 1024), (150, 16500, 1024),
+          # up to 64 rows that kernel takes the call only against many weights (more than 24 Mi from 33 rows, 48 Mi
+          # from 17); below, HiF4 activations go through the K-split kernel of the weight-only decode shape
+          (40, 8300, 4096), (40, 8192, 3584), (40, 13200, 1920), (40, 16500, 1920)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -592,7 +595,7 @@ def test_few_row_and_grouped_kernel_strided_output(h, oracle):
     assert rel_fro(cbuf[:, :N].double().cpu().numpy(), want_g) <= TOL
 
 
-@pytest.mark.parametrize("M,N,K", [(100, 100, 2048), (150, 300, 1024), (30, 8300, 2048)])
+@pytest.mark.parametrize("M,N,K", [(100, 100, 2048), (150, 300, 1024), (30, 8300, 2048), (48, 7000, 4096), (64, 300, 192)])
 def test_gemm_few_rows_k_split_other_kinds(h, oracle, M, N, K):
     """The few-row kernel with K split inside the workgroup, reached by the other two kinds of A: quantised in the
     call (fused encode-to-planes pre-pass) and plain BF16 with the optional workspace."""
@@ -603,7 +606,7 @@ def test_gemm_few_rows_k_split_other_kinds(h, oracle, M, N, K):
     cq = h.hif4_gemm(h.HIF4_A_BF16_QUANTIZE, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
     torch.cuda.synchronize()
     assert rel_fro(cq.cpu().numpy().astype(np.float64), oracle.gemm_f64(oracle.dequantize(ac, am), wd)) <= TOL
-    if M > 64:
+    if h.hif4_gemm_workspace_bytes_decoded_w(h.HIF4_A_BF16_KEEP, M, N, K) == M * K * 2:  # the few-row kernel's shapes
         ck = h.hif4_gemm(h.HIF4_A_BF16_KEEP, a, None, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
         torch.cuda.synchronize()
         assert rel_fro(ck.cpu().numpy().astype(np.float64), oracle.gemm_f64(ab, wd)) <= TOL
