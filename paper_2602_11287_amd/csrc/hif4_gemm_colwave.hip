@@ -424,7 +424,9 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
             if (strips * ks <= 4 * 256) { nw = 4; break; }
             if (strips * ks <= 8 * 256) { nw = 8; break; }
         }
-        if (ks == 1) nw = NWD;
+        // no split: 4 waves per workgroup, unless their workgroups need a second round and are too big to share a
+        // CU (tiles of more than 128 rows) - then 8 waves, half as many workgroups
+        if (ks == 1) nw = (strips <= 4 * 256 || rows_per_tile <= 128) ? NWD : NWG;
 #endif
 #define HIF4_CW_CASE(T, W, S) if (nw == W && ks == S) return launch_colwave_t<T, W, S>(g, out_dtype, stream)
         if (rows_per_tile <= 64) {
@@ -436,10 +438,10 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
             return launch_colwave_t<4, NWD, 1>(g, out_dtype, stream);
         }
         if (rows_per_tile <= 192) {
-            HIF4_CW_CASE(6, 8, 2); HIF4_CW_CASE(6, 4, 2);
+            HIF4_CW_CASE(6, 8, 2); HIF4_CW_CASE(6, 4, 2); HIF4_CW_CASE(6, NWG, 1);
             return launch_colwave_t<6, NWD, 1>(g, out_dtype, stream);
         }
-        HIF4_CW_CASE(8, 8, 2); HIF4_CW_CASE(8, 4, 2);
+        HIF4_CW_CASE(8, 8, 2); HIF4_CW_CASE(8, 4, 2); HIF4_CW_CASE(8, NWG, 1);
         return launch_colwave_t<8, NWD, 1>(g, out_dtype, stream);
 #undef HIF4_CW_CASE
     }

@@ -50,7 +50,9 @@ SHAPES = [(1, 1, 64), (32, 32, 64), (256, 256, 64), (257, 255, 128), (333, 520, 
           (20, 8300, 2048), (100, 8300, 2048), (10, 16500, 1024), (70, 16500, 1024), (150, 16500, 1024),
           # up to 64 rows that kernel takes the call only against many weights (more than 24 Mi from 33 rows, 48 Mi
           # from 17); below, HiF4 activations go through the K-split kernel of the weight-only decode shape
-          (40, 8300, 4096), (40, 8192, 3584), (40, 13200, 1920), (40, 16500, 1920)]
+          (40, 8300, 4096), (40, 8192, 3584), (40, 13200, 1920), (40, 16500, 1920),
+          # a 192-row tile, an odd number of units (no K split) and more than 1024 strips: 8 waves per workgroup
+          (150, 33000, 576)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
