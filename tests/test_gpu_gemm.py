@@ -640,6 +640,53 @@ def test_gemm_few_row_kernel_several_m_tiles_sampled(h, oracle, M, N, K):
     assert rel_fro(pick(ck), want_k) <= TOL, rel_fro(pick(ck), want_k)
 
 
+def test_gemm_random_shapes_every_kind_and_workspace(h, oracle):
+    """A seeded sweep over shapes that straddle every row-count boundary of the dispatch (16, 32, 64, 128, 192, 256
+    rows and beyond), ragged N, K of 1 to 24 units, all three kinds of A, both output types, the smallest, the
+    default and no workspace, strided A and C: each result against the fp64 oracle."""
+    rng = np.random.default_rng(20260711)
+    edges = [1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 400]
+    for case in range(48):
+        M = int(rng.choice(edges)) if case % 2 == 0 else int(rng.integers(1, 420))
+        N = int(rng.integers(1, 700))
+        K = 64 * int(rng.integers(1, 25))
+        kind = (h.HIF4_A_HIF4, h.HIF4_A_BF16_QUANTIZE, h.HIF4_A_BF16_KEEP)[case % 3]
+        f32 = bool(rng.integers(0, 2))
+        ws_mode = int(rng.integers(0, 3))  # 0: default (the optional larger one), 1: the smallest that is legal, 2: none where legal
+        print(f"case {case}: M={M} N={N} K={K} kind={kind} f32={f32} ws={ws_mode}", flush=True)
+        ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 7000 + case)
+        wcd, wmd = dev_packed(wc, wm)
+        wdec = oracle.dequantize(wc, wm)
+        pad = int(rng.integers(0, 2)) * 64
+        if kind == h.HIF4_A_HIF4:
+            a_dev, am_dev = dev_packed(ac, am)
+            want = oracle.gemm_f64(oracle.dequantize(ac, am), wdec)
+        else:
+            abuf = torch.zeros((M, K + pad), dtype=torch.bfloat16, device="cuda")
+            abuf[:, :K] = synth.from_bits(ab).cuda()
+            a_dev, am_dev = abuf[:, :K], None
+            want = oracle.gemm_f64(oracle.dequantize(ac, am) if kind == h.HIF4_A_BF16_QUANTIZE else ab, wdec)
+        need = h.hif4_gemm_workspace_bytes(kind, M, K)
+        ws = None
+        if ws_mode == 1 or (ws_mode == 2 and need):
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        elif ws_mode == 2:
+            ws = torch.empty(16, dtype=torch.uint8, device="cuda")[:0]
+        dt = torch.float32 if f32 else torch.bfloat16
+        cbuf = torch.full((M, N + 3), -7.0, dtype=dt, device="cuda")
+        h.hif4_gemm(kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32 if f32 else h.HIF4_OUT_BF16, c=cbuf[:, :N], workspace=ws)
+        torch.cuda.synchronize()
+        assert (cbuf[:, N:] == -7.0).all(), "columns beyond N untouched"
+        got = cbuf[:, :N].double().cpu().numpy()
+        if f32:
+            assert rel_fro(got, want) <= TOL, (case, rel_fro(got, want))
+        else:
+            wb = synth.bits(torch.from_numpy(want).to(torch.bfloat16)).astype(np.int32)
+            gb = synth.bits(cbuf[:, :N].contiguous().cpu()).astype(np.int32)
+            key = lambda b: np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+            assert np.abs(key(gb) - key(wb)).max() <= 1, case
+
+
 def test_gemm_weight_only_few_rows_optional_workspace(h, oracle):
     """65 to 192 rows, BF16 activations: with the optional workspace (the binding's default) the call runs the
     column-per-wave kernel on a reordered copy of A, without it the tile kernel; both against the oracle."""
