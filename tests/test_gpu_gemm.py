@@ -178,6 +178,50 @@ def test_grouped_gemm(h, oracle, counts):
     assert torch.equal(c, cq)
 
 
+def test_grouped_gemm_random_routings(h, oracle):
+    """A seeded sweep of the grouped call: 1 to 12 experts with 0 to 330 rows each (so the mean row count selects every
+    tile height of the few-row kernel, and single experts overflow a tile), ragged N, 1 to 12 units of K, all kinds
+    of A, the weight-only kind with and without its optional workspace, strided output."""
+    rng = np.random.default_rng(424242)
+    for case in range(30):
+        E = int(rng.integers(1, 13))
+        top = int(rng.choice([20, 70, 140, 200, 330]))
+        counts = rng.integers(0, top + 1, E)
+        if case % 5 == 0:
+            counts[rng.integers(0, E)] = 0
+        M, N, K = int(counts.sum()), int(rng.integers(1, 400)), 64 * int(rng.integers(1, 13))
+        if M == 0:
+            counts[0], M = 3, 3
+        kind = (h.HIF4_A_HIF4, h.HIF4_A_BF16_QUANTIZE, h.HIF4_A_BF16_KEEP)[case % 3]
+        with_ws = bool(rng.integers(0, 2))
+        print(f"case {case}: counts={counts.tolist()} N={N} K={K} kind={kind} ws={with_ws}", flush=True)
+        offs = np.zeros(E + 1, np.int32)
+        offs[1:] = np.cumsum(counts)
+        ab, (ac, am), _ = quantized_operands(oracle, M, 1, K, 31000 + case)
+        w = rng.standard_normal((E * N, K)) * 0.02
+        wc, wm = oracle.quantize(synth.bits(torch.from_numpy(w).to(torch.bfloat16)))
+        aval = ab if kind == h.HIF4_A_BF16_KEEP else oracle.dequantize(ac, am)
+        wdec = oracle.dequantize(wc, wm)
+        want = np.zeros((M, N))
+        for e in range(E):
+            if counts[e]:
+                want[offs[e]:offs[e + 1]] = oracle.gemm_f64(aval[offs[e]:offs[e + 1]], wdec[e * N:(e + 1) * N])
+        wcd, wmd = dev_packed(wc.reshape(E, N, K // 2), wm.reshape(E, N, K // 64))
+        od = torch.from_numpy(offs).cuda()
+        if kind == h.HIF4_A_HIF4:
+            a_dev, am_dev = dev_packed(ac, am)
+        else:
+            a_dev, am_dev = synth.from_bits(ab).cuda(), None
+        ws = None
+        if kind == h.HIF4_A_BF16_KEEP and not with_ws:
+            ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+        cbuf = torch.full((M, N + 5), 3.0, dtype=torch.float32, device="cuda")
+        h.hif4_grouped_gemm(kind, a_dev, am_dev, wcd, wmd, od, out_dtype=h.HIF4_OUT_F32, c=cbuf[:, :N], workspace=ws)
+        torch.cuda.synchronize()
+        assert (cbuf[:, N:] == 3.0).all()
+        assert rel_fro(cbuf[:, :N].double().cpu().numpy(), want) <= TOL, case
+
+
 def test_gemm_prefill_shape_sampled(h, oracle):
     """M=4096, N=11008, K=4096 (the W4A4 prefill configuration): a seeded sample of rows x columns."""
     M, N, K = 4096, 11008, 4096
