@@ -472,11 +472,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
 template <bool MX>
 static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int out_dtype, hipStream_t stream)
 {
-#ifdef HIF4_PLANES_BM
-    constexpr int BM = MX ? 256 : HIF4_PLANES_BM, BN = MX ? 256 : HIF4_PLANES_BN, WM = MX ? 2 : HIF4_PLANES_BM / 128, WN = MX ? 4 : HIF4_PLANES_BN / 64;
-#else
-    constexpr int BM = 256, BN = 256, WM = 2, WN = 4; // 8 waves of 128 x 64: measured faster than 4 waves of 128 x 128
-#endif
+    // 8 waves of 128 x 64: measured faster than 4 waves of 128 x 128 (also on 16 x 16 x 32 MFMAs with 256 accumulator
+    // registers per lane and the barrier between the two halves of a K step: 4 to 9 % slower), and smaller
+    // workgroup tiles (128 x 128 to 256 x 128) do not help calls of 256 to 4096 rows either
+    constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     g.M = (int)M;
     g.N = (int)N;
     g.K = (int)K;
