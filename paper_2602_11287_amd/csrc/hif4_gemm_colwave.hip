@@ -1,6 +1,6 @@
 // HiF4 GEMM for tiles with few rows and many weights per row of A: the grouped (per-expert)
-// GEMM, where an expert's rows meet its whole weight matrix once, and dense calls of at most 192
-// rows.  C = A * W^T per expert, A as
+// GEMM, where an expert's rows meet its whole weight matrix once, dense calls of at most 192
+// rows, and small dense calls of a few m-tiles.  C = A * W^T per expert, A as
 // exact BF16 values (decoded HiF4), W packed HiF4; each 64-wide K step of an output is the
 // unit dot product of Eq. 4 of the HiF4 paper (Section III-B), accumulated in fp32 on
 // v_mfma_f32_32x32x16_bf16.
@@ -350,7 +350,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
 #define HIF4_COLWAVE_R 4
 #define HIF4_COLWAVE_WPS 2
 #endif
-// waves per workgroup of a dense call (one expert, at most 192 rows) that does not split K: the grid is
+// waves per workgroup of a dense call (one matrix W, few m-tiles) that does not split K: the grid is
 // N / (32 NW) workgroups, and half as many columns per workgroup fill the chip better at every width measured
 #ifndef HIF4_COLWAVE_NW_DENSE
 #define HIF4_COLWAVE_NW_DENSE 4
