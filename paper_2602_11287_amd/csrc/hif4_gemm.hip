@@ -294,7 +294,10 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_kernel(GemmArgs g)
 #endif
 // waves per workgroup and pairs of units in flight per wave, by the number of 16-row blocks (measured
 // on MI355X: more pairs in flight cost registers, and occupancy is worth more)
-constexpr int skinny_waves(int mb) { return mb == 4 ? HIF4_SKINNY_WAVES4 : 8; }
+#ifndef HIF4_SKINNY_WAVES12
+#define HIF4_SKINNY_WAVES12 8
+#endif
+constexpr int skinny_waves(int mb) { return mb == 4 ? HIF4_SKINNY_WAVES4 : HIF4_SKINNY_WAVES12; }
 constexpr int skinny_nbuf(int mb) { return mb == 1 ? HIF4_SKINNY_NBUF1 : mb == 2 ? HIF4_SKINNY_NBUF2 : HIF4_SKINNY_NBUF4; }
 
 // C[M][N] = A[M][K] (BF16) * W[N][K]^T (HiF4) for M <= 16 * MB: bound by streaming W once
