@@ -204,6 +204,24 @@ def main():
             spent += time.perf_counter() - t
             reps += 1
         cpu_gbps = reps * 2 * (rows1 * K // 64) * BYTES_PER_UNIT / spent / 1e9
+        # the same on one thread (128 rows a time, about 0.3 s), and the fp64 GEMM oracle on a 256 x 256 block over K
+        n_all = oracle.num_threads()
+        oracle.set_num_threads(1)
+        reps1, spent1 = 0, 0.0
+        while spent1 < 0.3 and reps1 < 64:
+            t = time.perf_counter()
+            oracle.dequantize(*oracle.quantize(xb[:128]))
+            spent1 += time.perf_counter() - t
+            reps1 += 1
+        cpu1_gbps = reps1 * 2 * (128 * K // 64) * BYTES_PER_UNIT / spent1 / 1e9
+        blk = oracle.dequantize(wc[:256], wm[:256])
+        t = time.perf_counter()
+        oracle.gemm_f64(blk, blk)
+        gemm1 = 2.0 * 256 * 256 * K / (time.perf_counter() - t) / 1e9
+        oracle.set_num_threads(n_all)
+        t = time.perf_counter()
+        oracle.gemm_f64(blk, blk)
+        gemm_all = 2.0 * 256 * 256 * K / (time.perf_counter() - t) / 1e9
         # quantisation error of the three 4-bit block formats on the same matrix (CPU, oracle side), and
         # the GPU's encode+decode of that matrix against the oracle's
         from oracle import bfp4_comparators as cmp
@@ -219,7 +237,10 @@ def main():
             and (synth.bits(y[:rows1].cpu()) == oracle.dequantize(wc, wm)).all())
         out["cpu_baseline"] = {"value": round(cpu_gbps, 4), "unit": "GB/s", "cores": oracle.num_threads(),
                                "kind": "oracle",
-                               "sample": f"{reps} x encode+decode of one 1024x4096 matrix (65536 units), OpenMP over rows"}
+                               "sample": f"{reps} x encode+decode of one 1024x4096 matrix (65536 units), OpenMP over rows",
+                               "one_thread_GBps": round(cpu1_gbps, 4),
+                               "gemm_f64_oracle_GFLOPs": {"one_thread": round(gemm1, 2), "all_threads": round(gemm_all, 2),
+                                                          "sample": f"256 x 256 x {K} block of decoded units"}}
 
     print(json.dumps(out), flush=True)
 
