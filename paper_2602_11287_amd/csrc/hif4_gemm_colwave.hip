@@ -51,11 +51,11 @@ __device__ __forceinline__ uint64_t cw_uniform(uint64_t v) // a wave-uniform val
 }
 __device__ __forceinline__ void cw_load_to_lds_16(uint64_t base, uint32_t off, uint32_t lds_byte)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory", "m0");
 }
 __device__ __forceinline__ void cw_load_to_lds_4(uint64_t base, uint32_t off, uint32_t lds_byte)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory", "m0");
 }
 
 struct ColwaveArgs {
