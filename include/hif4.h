@@ -125,6 +125,9 @@ int hif4_dequantize(const uint8_t *codes, const uint32_t *meta, int64_t rows, in
  *                   planes before that); kind 2 needs none and it may be NULL.  Its contents
  *                   after the call are unspecified.
  * M == 0 or N == 0 is a no-op; K == 0 writes zeros.
+ * Which kernel runs depends on a_kind, M, N, K and the workspace size only, and every kernel adds
+ * its products in a fixed order (no atomics): equal calls give equal bits; calls that differ in
+ * those agree to fp32 summation accuracy.
  */
 int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
               const uint8_t *w_codes, const uint32_t *w_meta,
