@@ -141,10 +141,9 @@ int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
  * consecutive columns, i.e. along the axis the next linear layer reduces over (the paper converts
  * every linear layer's input before its matrix product, Section IV).  The planes equal
  * hif4_quantize(result of hif4_gemm with HIF4_OUT_BF16) bit for bit where hif4_gemm runs the same
- * main loop (more than 2048 rows, or ceil(N/32) * ceil(M/128) > 2048 with more than 192 rows, and the
- * same workspace size); for the small shapes that hif4_gemm gives to its few-row kernel the fp32
- * additions are grouped differently, so a BF16 value may now and then round the other way.
- * C never crosses HBM as BF16.
+ * main loop with the same split of K, which it does from 65 rows on given the same workspace size;
+ * up to 64 rows hif4_gemm may take another kernel, whose fp32 additions are grouped differently, so
+ * that a BF16 value may now and then round the other way.  C never crosses HBM as BF16.
  *   c_codes  out  uint8 [M][N/2], c_meta out uint32 [M][N/64];  N a multiple of 64
  * Other arguments, workspace and errors as hif4_gemm.
  */

@@ -2,7 +2,7 @@
 // layer): the fp32 tile in the MFMA accumulators is rounded to BF16 exactly as the BF16 output
 // would be, parked in LDS row-major, and encoded by Algorithm 1 of the HiF4 paper (Section II-B)
 // with the arithmetic of the streaming encoder.  The result equals hif4_quantize applied to the
-// BF16 output of the same GEMM, bit for bit, without C crossing HBM as BF16.
+// BF16 output of the same main loop, bit for bit, without C crossing HBM as BF16.
 #pragma once
 #include "hif4_encode.h"
 
@@ -28,14 +28,17 @@ __device__ __forceinline__ void emit_encode_parked(const uint16_t *tile, int row
     const int64_t n8 = N / 8, n64 = N / 64;
 #pragma unroll 1
     for (int u0 = 0; u0 < UNITS; u0 += UPP) {
-        const int u = u0 + tid / 4, row = u / UPR, ucol = u % UPR;
+        int u = u0 + tid / 4;
+        const bool in_tile = UNITS % UPP == 0 || u < UNITS; // a tile with fewer units than a pass takes: the rest idle
+        u = in_tile ? u : UNITS - 1;
+        const int row = u / UPR, ucol = u % UPR;
         uint4 w[2];
 #pragma unroll
         for (int c = 0; c < 2; ++c) w[c] = *reinterpret_cast<const uint4 *>(tile + row * RS + ucol * 64 + (c * 4 + l) * 8);
         uint32_t out[2];
         const uint32_t m = encode_share<4, MODE>(w, l, out);
         const int grow = row0 + row, gunit = col0 / 64 + ucol;
-        if (grow < rows_end && gunit < n64) {
+        if (in_tile && grow < rows_end && gunit < n64) {
 #pragma unroll
             for (int c = 0; c < 2; ++c) c_codes[grow * n8 + gunit * 8 + c * 4 + l] = out[c];
             if (l == 0) c_meta[grow * n64 + gunit] = m;

@@ -478,7 +478,7 @@ int launch_gemm_planes(const void *a_planes, const void *w_planes, int64_t M, in
 
 bool colwave_fits(int64_t M, int64_t N, int64_t K);
 int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint32_t *w_meta, const int32_t *offs, int E,
-                        int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype, int rows_per_tile,
+                        int64_t M, int64_t N, int64_t K, void *c, uint32_t *c_meta, int64_t ldc, int out_dtype, int rows_per_tile,
                         hipStream_t stream);
 
 // Internal output kinds beyond HIF4_OUT_BF16 / HIF4_OUT_F32: the result as HiF4 (c = codes plane, c_meta).
@@ -659,12 +659,12 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, ws + a_bytes, stream)) return rc;
             return launch_gemm_planes(ws, ws + a_bytes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
-        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && !emit && colwave_fits(M, N, K) && workspace &&
+        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && (!emit || !offs) && colwave_fits(M, N, K) && workspace &&
             (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 && workspace_bytes >= (size_t)M * (size_t)K * 2) {
             // weight-only, grouped or a small dense call (colwave_dense_rows), and room for a reordered copy of A: the kernel of
             // the HiF4 x HiF4 calls of those shapes
             if (int rc = launch_bf16_to_planes(a, M, K, lda, workspace, stream)) return rc;
-            return launch_gemm_colwave(workspace, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
+            return launch_gemm_colwave(workspace, w_codes, w_meta, offs, E, M, N, K, c, c_meta, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
         }
         g.a = static_cast<const uint16_t *>(a);
         g.lda = lda;
@@ -701,7 +701,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (M <= 32) return launch_skinny<2, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
             return launch_skinny<4, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         }
-        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K) && !emit) {
+        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K) && (!emit || !offs)) {
             // grouped, or a dense call of few rows (one m-tile, or a few on a small N): every weight meets few rows only,
             // so the kernel that expands W straight into MFMA operands takes the call
             // (hif4_gemm_colwave.hip); A as cell planes
@@ -711,7 +711,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             } else {
                 if (int rc = launch_decode_planes(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
             }
-            return launch_gemm_colwave(adec, w_codes, w_meta, offs, E, M, N, K, c, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
+            return launch_gemm_colwave(adec, w_codes, w_meta, offs, E, M, N, K, c, c_meta, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
         }
         if (a_kind == HIF4_A_BF16_QUANTIZE) {
             // quantise and decode in one pass: the packed activations are never needed in memory

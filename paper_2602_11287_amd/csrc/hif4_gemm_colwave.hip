@@ -36,6 +36,7 @@
 // (scalar address arithmetic, loads straight into LDS, one wait per sub-step).
 #include <type_traits>
 
+#include "hif4_emit.h"
 #include "hif4_expand.h"
 #include "hif4_grouped.h"
 
@@ -64,10 +65,14 @@ struct ColwaveArgs {
     const uint32_t *w_meta;  // [E][N][K/64]
     const int32_t *offs;     // device int32[E+1], or nullptr: one matrix W for all M rows
     void *c;
+    uint32_t *c_meta; // HiF4 result (dense calls): c is its codes plane [M][N/2], this its metadata plane [M][N/64]
     int64_t ldc;
     int M, N, K, E;
     int tiles_m, tiles_n;
 };
+
+// what the kernel writes: BF16, fp32, or the result as HiF4 with units along N (rounding mode OUT - COLWAVE_EMIT)
+enum { COLWAVE_BF16 = 0, COLWAVE_F32 = 1, COLWAVE_EMIT = 2 };
 
 // NW waves per workgroup in KS groups of NW / KS (a group takes one KS-th of K, a wave 32 columns of
 // it), NB buffers of A, a ring of R steps of packed W.
@@ -84,9 +89,10 @@ struct ColwaveShape {
 // units [kw K/64/KS, (kw + 1) K/64/KS) - and their partial sums meet in LDS after the loop.  With few
 // rows and not many columns there are too few 32-column strips to give every SIMD its two waves,
 // and a wave alone cannot issue faster than it does; K is the only other axis to cut.
-template <int TMAX, int NW, int KS, int NB, int R, int WPS, bool OUT_F32>
+template <int TMAX, int NW, int KS, int NB, int R, int WPS, int OUT>
 __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs g)
 {
+    constexpr bool OUT_F32 = OUT == COLWAVE_F32, EMIT = OUT >= COLWAVE_EMIT;
     constexpr int NWC = NW / KS;             // waves (32-column strips) across a tile
     constexpr int BM = 32 * TMAX, BN = 32 * NWC;
     constexpr int RG = (BM + 63) / 64;       // 64-row groups of a tile
@@ -311,20 +317,46 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
             }
         }
         __syncthreads();
-        if (kw > 0) return;
+        if (!EMIT && kw > 0) return; // (a HiF4 result is encoded by all waves, see below)
+        if (kw == 0) {
 #pragma unroll
-        for (int p = 0; p < KS - 1; ++p) {
-            const float4 *src = red + (size_t)(p * NWC + cw) * TMAX * 256 + lane;
+            for (int p = 0; p < KS - 1; ++p) {
+                const float4 *src = red + (size_t)(p * NWC + cw) * TMAX * 256 + lane;
+#pragma unroll
+                for (int i = 0; i < TMAX; ++i) {
+                    if (i >= live) continue;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 v = src[(i * 4 + q) * 64];
+                        acc[i][4 * q] += v.x, acc[i][4 * q + 1] += v.y, acc[i][4 * q + 2] += v.z, acc[i][4 * q + 3] += v.w;
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- result as HiF4 (hif4_emit.h): the tile, rounded to BF16 as the BF16 output would be, is parked in LDS
+    // row-major by the waves that hold it, then every thread of the workgroup encodes units of 64 columns
+    if constexpr (EMIT) {
+        static_assert(BN % 64 == 0, "whole units across a tile");
+        static_assert(emit_lds_bytes<BM, BN>() <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX), "the parked tile fits the buffers");
+        constexpr int RS = BN + 8; // row stride in BF16 elements
+        uint16_t *tile = reinterpret_cast<uint16_t *>(lds);
+        __syncthreads(); // all operand reads and loads are done (KS > 1: and group 0 has read the partial sums)
+        if (kw == 0) {
 #pragma unroll
             for (int i = 0; i < TMAX; ++i) {
                 if (i >= live) continue;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = src[(i * 4 + q) * 64];
-                    acc[i][4 * q] += v.x, acc[i][4 * q + 1] += v.y, acc[i][4 * q + 2] += v.z, acc[i][4 * q + 3] += v.w;
+                for (int r = 0; r < 16; ++r) {
+                    const uint32_t u = f2u(acc[i][r]);
+                    tile[(i * 32 + 8 * (r / 4) + 4 * half + (r % 4)) * RS + cw * 32 + l32] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
                 }
             }
         }
+        __syncthreads();
+        emit_encode_parked<BM, BN, 64 * NW, OUT - COLWAVE_EMIT>(tile, row0, rows_end, col0, g.N, static_cast<uint32_t *>(g.c), g.c_meta);
+        return;
     }
 
     // ---- epilogue: lane holds column l32 of each 32 x 32 block, rows 8 (r / 4) + 4 half + r % 4
@@ -355,7 +387,8 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
 #ifndef HIF4_COLWAVE_NW_DENSE
 #define HIF4_COLWAVE_NW_DENSE 4
 #endif
-template <int TMAX, int NW, int KS>
+// EMIT_OK: also instantiate the kernels that write the result as HiF4 (dense shapes only)
+template <int TMAX, int NW, int KS, bool EMIT_OK = false>
 static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
 {
     // three buffers of A and four steps of W where LDS has room for them, else two and three
@@ -368,18 +401,19 @@ static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
     g.tiles_m = g.offs ? g.M / BM + g.E : (g.M + BM - 1) / BM; // grouped: upper bound of sum_e ceil(rows_e / BM)
     const int64_t blocks = (int64_t)(g.tiles_m >= 8 ? (g.tiles_m + 7) / 8 * 8 : g.tiles_m) * g.tiles_n;
     const dim3 grid((unsigned)blocks), block(64 * NW);
-    hipError_t e;
-    if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, true>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return HIF4_ERR_DEVICE;
+    auto launch = [&](auto k) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) return false;
         hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
-    } else {
-        auto k = gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, false>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return HIF4_ERR_DEVICE;
-        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
-    }
+        return true;
+    };
+    bool ok;
+    if (out_dtype == HIF4_OUT_F32) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_F32>);
+    else if (out_dtype == HIF4_OUT_BF16) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_BF16>);
+    else if constexpr (EMIT_OK && BN % 64 == 0) { // 16 + rounding mode: the result as HiF4 (dense calls, the launcher below picks shapes that allow it)
+        ok = out_dtype == 16 + HIF4_ROUND_RNE ? launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RNE>)
+                                              : launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RHA>);
+    } else return HIF4_ERR_UNSUPPORTED;
+    if (!ok) return HIF4_ERR_DEVICE;
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 
@@ -391,8 +425,10 @@ bool colwave_fits(int64_t M, int64_t N, int64_t K)
 
 // a_planes: decoded A as cell planes (launch_decode_planes).  offs != nullptr: grouped, E experts;
 // rows_per_tile: 64, 128, 192 or 256 rows of A per workgroup.
+// out_dtype: HIF4_OUT_BF16, HIF4_OUT_F32, or (dense calls, N a multiple of 64) 16 + rounding mode for a HiF4 result:
+// c = codes plane, c_meta = its metadata plane, ldc unused.
 int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint32_t *w_meta, const int32_t *offs, int E,
-                        int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype, int rows_per_tile,
+                        int64_t M, int64_t N, int64_t K, void *c, uint32_t *c_meta, int64_t ldc, int out_dtype, int rows_per_tile,
                         hipStream_t stream)
 {
     ColwaveArgs g;
@@ -401,6 +437,7 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
     g.w_meta = w_meta;
     g.offs = offs;
     g.c = c;
+    g.c_meta = c_meta;
     g.ldc = ldc;
     g.M = (int)M;
     g.N = (int)N;
@@ -409,40 +446,35 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
     constexpr int NWG = HIF4_COLWAVE_NW, NWD = HIF4_COLWAVE_NW_DENSE;
     if (!offs) {
         const int64_t strips = (N + 31) / 32 * ((M + rows_per_tile - 1) / rows_per_tile), nk = K / 64;
+        const bool emit = out_dtype >= 16;
         // K parts per workgroup (4, 2 or 1; tiles of more than 128 rows: LDS holds 2) and waves (4 or 8): the
         // most parts whose workgroups still run in one round (one workgroup per CU), with 4 waves rather than
         // 8 when both do - measured: twice the CUs beat twice the waves per CU.  Parts divide K's units and
         // keep at least 8 steps each.
         int ks = rows_per_tile > 128 ? 2 : 4, nw = NWD;
-#ifdef HIF4_COLWAVE_FORCE_KS
-        ks = HIF4_COLWAVE_FORCE_KS < ks ? HIF4_COLWAVE_FORCE_KS : ks, nw = HIF4_COLWAVE_FORCE_NW;
-        while (ks > 1 && (nk % ks != 0 || nk / ks < 4)) ks /= 2;
-        if (ks == 1) nw = NWD;
-#else
         for (; ks > 1; ks /= 2) {
             if (nk % ks != 0 || nk / ks < 8) continue;
-            if (strips * ks <= 4 * 256) { nw = 4; break; }
+            if (strips * ks <= 4 * 256 && !(emit && ks == 4)) { nw = 4; break; } // (a HiF4 result needs 64 columns per workgroup)
             if (strips * ks <= 8 * 256) { nw = 8; break; }
         }
         // no split: 4 waves per workgroup, unless their workgroups need a second round and are too big to share a
         // CU (tiles of more than 128 rows) - then 8 waves, half as many workgroups
         if (ks == 1) nw = (strips <= 4 * 256 || rows_per_tile <= 128) ? NWD : NWG;
-#endif
-#define HIF4_CW_CASE(T, W, S) if (nw == W && ks == S) return launch_colwave_t<T, W, S>(g, out_dtype, stream)
+#define HIF4_CW_CASE(T, W, S) if (nw == W && ks == S) return launch_colwave_t<T, W, S, true>(g, out_dtype, stream)
         if (rows_per_tile <= 64) {
             HIF4_CW_CASE(2, 8, 4); HIF4_CW_CASE(2, 8, 2); HIF4_CW_CASE(2, 4, 4); HIF4_CW_CASE(2, 4, 2);
-            return launch_colwave_t<2, NWD, 1>(g, out_dtype, stream);
+            return launch_colwave_t<2, NWD, 1, true>(g, out_dtype, stream);
         }
         if (rows_per_tile <= 128) {
             HIF4_CW_CASE(4, 8, 4); HIF4_CW_CASE(4, 8, 2); HIF4_CW_CASE(4, 4, 4); HIF4_CW_CASE(4, 4, 2);
-            return launch_colwave_t<4, NWD, 1>(g, out_dtype, stream);
+            return launch_colwave_t<4, NWD, 1, true>(g, out_dtype, stream);
         }
         if (rows_per_tile <= 192) {
             HIF4_CW_CASE(6, 8, 2); HIF4_CW_CASE(6, 4, 2); HIF4_CW_CASE(6, NWG, 1);
-            return launch_colwave_t<6, NWD, 1>(g, out_dtype, stream);
+            return launch_colwave_t<6, NWD, 1, true>(g, out_dtype, stream);
         }
         HIF4_CW_CASE(8, 8, 2); HIF4_CW_CASE(8, 4, 2); HIF4_CW_CASE(8, NWG, 1);
-        return launch_colwave_t<8, NWD, 1>(g, out_dtype, stream);
+        return launch_colwave_t<8, NWD, 1, true>(g, out_dtype, stream);
 #undef HIF4_CW_CASE
     }
     if (rows_per_tile <= 64) return launch_colwave_t<2, NWG, 1>(g, out_dtype, stream);

@@ -440,11 +440,13 @@ def test_gemm_to_hif4_equals_gemm_then_quantize(h, oracle, kind, M, N, K, mode):
 
 
 @pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
-@pytest.mark.parametrize("M,N,K", [(70, 1024, 1088), (300, 320, 512)])
+@pytest.mark.parametrize("M,N,K", [(70, 1024, 1088), (300, 320, 512), (100, 256, 2048), (150, 384, 1024), (16, 128, 512),
+                                   (40, 8320, 4096), (600, 4096, 1024)])
 def test_gemm_to_hif4_small_shapes(h, oracle, kind, M, N, K):
-    """Shapes that hif4_gemm gives to its few-row kernel, whose fp32 additions are grouped differently from the
-    emitting call's: the emitted planes are Algorithm 1 of BF16 values that agree with hif4_gemm's to fp32 summation
-    accuracy, so nearly every unit is identical, and decoded they lie within HiF4's error of the fp64 product."""
+    """Shapes on which the emitting call runs the few-row kernel (one or several m-tiles, with and without K split,
+    its epilogue parking the tile in LDS).  hif4_gemm may run another kernel there (up to 64 rows) or the same one
+    with other wave counts, so the BF16 values agree to fp32 summation accuracy only: nearly every unit is identical,
+    and decoded the result lies within HiF4's error of the fp64 product."""
     ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 515 + M)
     wcd, wmd = dev_packed(wc, wm)
     if kind == "keep":
