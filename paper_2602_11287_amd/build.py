@@ -1,4 +1,5 @@
 """Compile libhif4 (hand-written HIP, gfx950 only) in-tree with hipcc."""
+import concurrent.futures
 import glob
 import os
 import subprocess
@@ -19,9 +20,7 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False, extra=()) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", LIB, *sources()]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -31,6 +30,24 @@ def build(verbose: bool = False, extra=()) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out, flush=True)
+
+
+def build(verbose: bool = False, extra=()) -> str:
+    """One hipcc -c per source, side by side (the kernels with many instantiations take most of a minute each),
+    then one link.  Objects go to _build/, which is not tracked."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    jobs = []
+    for src in sources():
+        obj = os.path.join(objdir, os.path.basename(src)[:-4] + ".o")
+        jobs.append((obj, [hipcc, *flags, *extra, "-c", "-o", obj, src]))
+    workers = max(1, min(len(jobs), 8, os.cpu_count() or 1))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as pool:
+        for fut in [pool.submit(_run, cmd, verbose) for _, cmd in jobs]:
+            fut.result()
+    _run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB, *[o for o, _ in jobs]], verbose)
     return LIB
 
 
