@@ -73,4 +73,30 @@ __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 __device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 
+// 16-byte and 4-byte global accesses, optionally non-temporal (streaming data that this kernel does not reuse).
+template <bool NT>
+__device__ __forceinline__ uint4 load16(const void *p)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 *q = static_cast<const u32x4 *>(p);
+    u32x4 v = NT ? __builtin_nontemporal_load(q) : *q;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <bool NT>
+__device__ __forceinline__ void store16(void *p, uint4 v)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 t = { v.x, v.y, v.z, v.w };
+    if (NT) __builtin_nontemporal_store(t, static_cast<u32x4 *>(p));
+    else *static_cast<u32x4 *>(p) = t;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store4(uint32_t *p, uint32_t v)
+{
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
 } // namespace hif4

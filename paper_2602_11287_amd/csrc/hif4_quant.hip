@@ -14,31 +14,6 @@ namespace hif4 {
 
 // ------------------------------------------------------------------ encoder
 
-template <bool NT>
-__device__ __forceinline__ uint4 load16(const void *p)
-{
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 *q = static_cast<const u32x4 *>(p);
-    u32x4 v = NT ? __builtin_nontemporal_load(q) : *q;
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
-template <bool NT>
-__device__ __forceinline__ void store16(void *p, uint4 v)
-{
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    u32x4 t = { v.x, v.y, v.z, v.w };
-    if (NT) __builtin_nontemporal_store(t, static_cast<u32x4 *>(p));
-    else *static_cast<u32x4 *>(p) = t;
-}
-
-template <bool NT>
-__device__ __forceinline__ void store4(uint32_t *p, uint32_t v)
-{
-    if (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
 // Input element types of the encoder.  FP16 and FP32 inputs are first rounded to BF16 by the
 // rounding mode of the conversion (Section II-B: other high-precision formats follow the same
 // procedure; Algorithm 1 itself is written on BF16), then take the same path.
@@ -180,7 +155,7 @@ __global__ __launch_bounds__(256) void encode_to_planes_kernel(const void *__res
     const uint32_t sbase = unit_scale_bits(m);
     if (live) {
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) planes[(u * 8 + c * LPU + l) * rows + row] = expand_chunk(out[c], m, sbase, c * LPU + l);
+        for (int c = 0; c < NCH; ++c) store16<true>(&planes[(u * 8 + c * LPU + l) * rows + row], expand_chunk(out[c], m, sbase, c * LPU + l)); // streaming: see decode_planes_kernel
     }
 }
 
