@@ -539,9 +539,9 @@ size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
 // instead of expanding W inside the main loop.  Measured on MI355X: that main loop (on
 // v_mfma_f32_16x16x32_bf16, nothing but matrix work) is 10 to 17 % faster than the one that expands W,
 // and the pre-pass that decodes W costs 2.56 bytes per weight once per call, which that margin covers
-// from about 4096 rows on (+6 to 10 % there; at 2048 rows the two paths tie).
+// from about 3300 rows on (+6 to 10 % at 4096 rows, +6 to 8 % at 3584, mixed at 3072 and below).
 #ifndef HIF4_DECODED_W_MIN_ROWS
-#define HIF4_DECODED_W_MIN_ROWS 4096
+#define HIF4_DECODED_W_MIN_ROWS 3328
 #endif
 constexpr int64_t DECODED_W_MIN_ROWS = HIF4_DECODED_W_MIN_ROWS;
 

@@ -330,7 +330,7 @@ def test_grouped_gemm_moe_config_sampled(h, oracle):
 
 @pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
 def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
-    """From 4096 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
+    """From 3328 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
     HiF4 operands decode W once instead of inside the main loop: the same exact products, added in fp32 in
     another grouping, so the two results agree far inside the tolerance, and both are within it of the oracle."""
     M, N, K = 8192 + 77, 300, 320
@@ -351,7 +351,7 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
     small = h.hif4_gemm_workspace_bytes(a_kind, M, K)
     big = h.hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
     assert big >= small + N * K * 2 + (M * K * 2 if kind == "keep" else 0)  # BF16 activations: a reordered copy of A as well
-    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 4095, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 4095, K)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 3327, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 3327, K)
     ws_small = torch.empty(max(small, 16), dtype=torch.uint8, device="cuda")
     ws_big = torch.empty(max(big, 16), dtype=torch.uint8, device="cuda")
     c_small = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, workspace=ws_small)
@@ -470,7 +470,7 @@ def test_gemm_to_hif4_small_shapes(h, oracle, kind, M, N, K):
 
 
 def test_gemm_to_hif4_many_rows_and_k0(h, oracle):
-    """Through the decoded-operand kernel (4096+ rows, large workspace), and the empty sum."""
+    """Through the decoded-operand kernel (3328+ rows, large workspace), and the empty sum."""
     M, N, K = 8192 + 40, 192, 256
     ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 99)
     wcd, wmd = dev_packed(wc, wm)
