@@ -45,9 +45,8 @@ __device__ __forceinline__ uint32_t lds_offset(const void *p)
 // 16-byte load of codes) to 4 cells; a wave's stores are 64 consecutive cells of one group.
 // The 4-byte-per-lane reads of a wave touch 64 different lines, but the 8 loads that share a
 // line come from the same block, so they are served by the L1.
-// The planes are written with streaming (non-temporal) stores: the writer never reads them back, and the GEMM
-// that follows finds them in the memory-side cache all the same (measured: 4096 x 11008 x 4096 with both
-// pre-passes 372-408 -> 357-370 us; the large shape 1 % faster; few-row calls unchanged).
+// (Streaming stores for the planes were measured: no difference for the whole call, interleaved A/B on five shapes;
+// streaming stores for C in the main loop's epilogue cost 3 to 20 %.)
 __global__ __launch_bounds__(256) void decode_planes_kernel(const uint32_t *__restrict__ codes,
                                                             const uint32_t *__restrict__ meta, int64_t rows,
                                                             int64_t upr, uint4 *__restrict__ planes)
@@ -64,7 +63,7 @@ __global__ __launch_bounds__(256) void decode_planes_kernel(const uint32_t *__re
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int j = 4 * hh + t;
-        store16<true>(&planes[(unit * 8 + j) * rows + row], expand_chunk(cw[t], m, sbase, j));
+        planes[(unit * 8 + j) * rows + row] = expand_chunk(cw[t], m, sbase, j);
     }
 }
 
@@ -76,7 +75,7 @@ __global__ __launch_bounds__(512) void bf16_to_planes_kernel(const uint16_t *__r
     const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x % 64;
     const int64_t g = (int64_t)blockIdx.y * 8 + threadIdx.x / 64;
     if (row >= rows) return;
-    store16<true>(&planes[g * rows + row], permute_bf16_cell(*reinterpret_cast<const uint4 *>(x + row * ldx + g * 8)));
+    planes[g * rows + row] = permute_bf16_cell(*reinterpret_cast<const uint4 *>(x + row * ldx + g * 8));
 }
 
 int launch_bf16_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx, void *planes, hipStream_t stream)

@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256) void encode_to_planes_kernel(const void *__res
     const uint32_t sbase = unit_scale_bits(m);
     if (live) {
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) store16<true>(&planes[(u * 8 + c * LPU + l) * rows + row], expand_chunk(out[c], m, sbase, c * LPU + l)); // streaming: see decode_planes_kernel
+        for (int c = 0; c < NCH; ++c) planes[(u * 8 + c * LPU + l) * rows + row] = expand_chunk(out[c], m, sbase, c * LPU + l);
     }
 }
 
