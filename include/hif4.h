@@ -179,7 +179,7 @@ size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K)
  * per element) and runs its main loop on the decoded values of both operands.  The products are the same
  * and exact; the fp32 additions are grouped differently, so results agree to fp32 summation
  * accuracy, not always bit for bit.  Equals hif4_gemm_workspace_bytes() when M is too small for
- * this to pay (below 3328 rows), except for a_kind 2 on the shapes of the few-row kernel (up to
+ * this to pay (below 1536 rows, or below 3328 rows against more than 128 Mi weights), except for a_kind 2 on the shapes of the few-row kernel (up to
  * 192 rows, or up to 2048 rows with ceil(N/32) * ceil(M/128) <= 2048; not up to 16 rows, nor up to
  * 32 rows with N * K <= 48 Mi, nor up to 64 rows with N * K <= 24 Mi, which another kernel serves
  * faster), where M * K * 2 bytes for a reordered copy of A select that kernel.  A workspace between the two sizes is used as

@@ -539,7 +539,9 @@ size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
 // instead of expanding W inside the main loop.  Measured on MI355X: that main loop (on
 // v_mfma_f32_16x16x32_bf16, nothing but matrix work) is 10 to 17 % faster than the one that expands W,
 // and the pre-pass that decodes W costs 2.56 bytes per weight once per call, which that margin covers
-// from about 3300 rows on (+6 to 10 % at 4096 rows, +6 to 8 % at 3584, mixed at 3072 and below).
+// from about 3300 rows on whatever the shape (+8 to 12 % from 3328 to 4096 rows on five weight shapes, runs of the
+// two paths interleaved), and from 1536 rows on when the decoded W stays within the 256 MB memory-side cache (at
+// most 128 Mi weights: +2 to 10 % there; a 28672 x 8192 matrix loses 3 to 5 % below 3328 rows).
 #ifndef HIF4_DECODED_W_MIN_ROWS
 #define HIF4_DECODED_W_MIN_ROWS 3328
 #endif
@@ -589,6 +591,14 @@ static int colwave_dense_rows(int64_t M, int64_t N)
     return best;
 }
 
+// Whether a dense call should decode W once, given the room: see DECODED_W_MIN_ROWS; never on the shapes of the
+// few-row kernel, which is faster than both.
+static bool decoded_w_pays(int64_t M, int64_t N, int64_t K)
+{
+    if (M >= DECODED_W_MIN_ROWS) return true;
+    return M >= 1536 && N * K <= ((int64_t)128 << 20) && colwave_dense_rows(M, N) == 0;
+}
+
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K)
 {
     const size_t base = gemm_workspace_bytes(a_kind, M, K);
@@ -596,7 +606,7 @@ size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t 
     // copy of A selects it
     if (a_kind == HIF4_A_BF16_KEEP && N > 0 && K > 0 && (M > 64 ? colwave_dense_rows(M, N) > 0 : M > 0 && !few_rows_prefer_k_split(M, N, K)))
         return (size_t)M * (size_t)K * 2;
-    if (M < DECODED_W_MIN_ROWS || N <= 0 || K <= 0) return base;
+    if (N <= 0 || K <= 0 || !decoded_w_pays(M, N, K)) return base;
     if (a_kind == HIF4_A_BF16_KEEP) return align16((size_t)M * (size_t)K * 2) + (size_t)N * (size_t)K * 2; // A as planes, W decoded
     return align16(base) + (size_t)N * (size_t)K * 2;
 }
@@ -651,7 +661,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     bool a_cell = true;
     if (a_kind == HIF4_A_BF16_KEEP) {
         const size_t a_bytes = align16((size_t)M * (size_t)K * 2);
-        if (!offs && M >= DECODED_W_MIN_ROWS && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
+        if (!offs && decoded_w_pays(M, N, K) && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
             workspace_bytes >= a_bytes + (size_t)N * (size_t)K * 2) {
             // weight-only with many rows and room in the workspace: the plane-fed kernel here too
             uint8_t *ws = static_cast<uint8_t *>(workspace);
@@ -672,7 +682,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
     } else {
         uint8_t *ws = static_cast<uint8_t *>(workspace);
         const size_t base = align16(gemm_workspace_bytes(a_kind, M, K));
-        const bool planes = !offs && M >= DECODED_W_MIN_ROWS && workspace_bytes >= base + (size_t)N * (size_t)K * 2;
+        const bool planes = !offs && decoded_w_pays(M, N, K) && workspace_bytes >= base + (size_t)N * (size_t)K * 2;
         // the decoded copy of A sits behind the room for its packed planes (HIF4_A_BF16_QUANTIZE)
         uint8_t *adec = a_kind == HIF4_A_BF16_QUANTIZE
                             ? ws + align16((size_t)M * (size_t)K / 2) + align16((size_t)M * (size_t)(K / 64) * 4)

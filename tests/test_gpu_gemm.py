@@ -330,7 +330,7 @@ def test_grouped_gemm_moe_config_sampled(h, oracle):
 
 @pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
 def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
-    """From 3328 rows on, a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
+    """From 1536 rows on (3328 against more than 128 Mi weights), a workspace of hif4_gemm_workspace_bytes_decoded_w() bytes makes a call on two
     HiF4 operands decode W once instead of inside the main loop: the same exact products, added in fp32 in
     another grouping, so the two results agree far inside the tolerance, and both are within it of the oracle."""
     M, N, K = 8192 + 77, 300, 320
@@ -351,7 +351,10 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
     small = h.hif4_gemm_workspace_bytes(a_kind, M, K)
     big = h.hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
     assert big >= small + N * K * 2 + (M * K * 2 if kind == "keep" else 0)  # BF16 activations: a reordered copy of A as well
-    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 3327, N, K) == h.hif4_gemm_workspace_bytes(a_kind, 3327, K)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 1535, 11008, 4096) == h.hif4_gemm_workspace_bytes(a_kind, 1535, 4096)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 1536, 11008, 4096) > h.hif4_gemm_workspace_bytes(a_kind, 1536, 4096)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 3327, 28672, 8192) == h.hif4_gemm_workspace_bytes(a_kind, 3327, 8192)
+    assert h.hif4_gemm_workspace_bytes_decoded_w(a_kind, 3328, 28672, 8192) > h.hif4_gemm_workspace_bytes(a_kind, 3328, 8192)
     ws_small = torch.empty(max(small, 16), dtype=torch.uint8, device="cuda")
     ws_big = torch.empty(max(big, 16), dtype=torch.uint8, device="cuda")
     c_small = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, workspace=ws_small)
