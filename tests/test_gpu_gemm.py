@@ -52,7 +52,10 @@ SHAPES = [(1, 1, 64), (32, 32, 64), (256, 256, 64), (257, 255, 128), (333, 520, 
           # from 17); below, HiF4 activations go through the K-split kernel of the weight-only decode shape
           (40, 8300, 4096), (40, 8192, 3584), (40, 13200, 1920), (40, 16500, 1920),
           # a 192-row tile, an odd number of units (no K split) and more than 1024 strips: 8 waves per workgroup
-          (150, 33000, 576)]
+          (150, 33000, 576),
+          # 1536 rows and more against a W whose decoded copy fits the memory-side cache, too many strips for the few-row
+          # kernel: both operands decoded once (the binding's default workspace has the room)
+          (1600, 5100, 256)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
