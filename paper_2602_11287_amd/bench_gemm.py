@@ -184,7 +184,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
     mfma_leg("grouped_gemm_w4a4_E64_rows8192_N2048_K7168", M, N, K,
              lambda: hif4.hif4_grouped_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, od, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-             "hif4::gemm_colwave_kernel<6,8,3,4> (+ hif4::encode_to_planes_kernel)")
+             "hif4::gemm_colwave_kernel<TMAX=6,NW=8,KS=1,NB=3,R=4> (+ hif4::encode_to_planes_kernel)")
     nbytes = E * N * K // 64 * 36 + M * K * 2 + M * N * 2
     legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["GBps_algorithmic"] = round(
         nbytes / legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["ms"] / 1e6, 1)
