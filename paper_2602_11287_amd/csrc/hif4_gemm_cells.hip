@@ -30,7 +30,7 @@ namespace hif4 {
 // wait state the hardware needs between a write of M0 and an LDS-writing load.
 __device__ __forceinline__ void load_to_lds_16(const uint4 *src, uint32_t lds_byte)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte), "v"(src) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte), "v"(src) : "memory");
 }
 
 // byte offset of a __shared__ object inside the workgroup's LDS

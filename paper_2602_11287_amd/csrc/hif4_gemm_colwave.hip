@@ -52,11 +52,11 @@ __device__ __forceinline__ uint64_t cw_uniform(uint64_t v) // a wave-uniform val
 }
 __device__ __forceinline__ void cw_load_to_lds_16(uint64_t base, uint32_t off, uint32_t lds_byte)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory");
 }
 __device__ __forceinline__ void cw_load_to_lds_4(uint64_t base, uint32_t off, uint32_t lds_byte)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory");
 }
 
 struct ColwaveArgs {
@@ -444,8 +444,11 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
     g.K = (int)K;
     g.E = E;
     constexpr int NWG = HIF4_COLWAVE_NW, NWD = HIF4_COLWAVE_NW_DENSE;
-    if (!offs) {
-        const int64_t strips = (N + 31) / 32 * ((M + rows_per_tile - 1) / rows_per_tile), nk = K / 64;
+    {
+        // m-tiles: of a dense call, or the upper bound sum_e ceil(rows_e / tile) <= M / tile + E of a grouped one
+        const int tile_rows = rows_per_tile <= 64 ? 64 : rows_per_tile <= 128 ? 128 : rows_per_tile <= 192 ? 192 : 256;
+        const int64_t m_tiles = offs ? M / tile_rows + E : (M + rows_per_tile - 1) / rows_per_tile;
+        const int64_t strips = (N + 31) / 32 * m_tiles, nk = K / 64;
         const bool emit = out_dtype >= 16;
         // K parts per workgroup (4, 2 or 1; tiles of more than 128 rows: LDS holds 2) and waves (4 or 8): the
         // most parts whose workgroups still run in one round (one workgroup per CU), with 4 waves rather than
@@ -459,14 +462,15 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
         }
         // no split: 4 waves per workgroup, unless their workgroups need a second round and are too big to share a
         // CU (tiles of more than 128 rows) - then 8 waves, half as many workgroups
-        if (ks == 1) nw = (strips <= 4 * 256 || rows_per_tile <= 128) ? NWD : NWG;
+        // (a grouped call that fills the chip without a split keeps 8 waves: measured equal or better on 64 experts)
+        if (ks == 1) nw = offs ? NWG : (strips <= 4 * 256 || rows_per_tile <= 128) ? NWD : NWG;
 #define HIF4_CW_CASE(T, W, S) if (nw == W && ks == S) return launch_colwave_t<T, W, S, true>(g, out_dtype, stream)
         if (rows_per_tile <= 64) {
-            HIF4_CW_CASE(2, 8, 4); HIF4_CW_CASE(2, 8, 2); HIF4_CW_CASE(2, 4, 4); HIF4_CW_CASE(2, 4, 2);
+            HIF4_CW_CASE(2, 8, 4); HIF4_CW_CASE(2, 8, 2); HIF4_CW_CASE(2, 4, 4); HIF4_CW_CASE(2, 4, 2); HIF4_CW_CASE(2, NWG, 1);
             return launch_colwave_t<2, NWD, 1, true>(g, out_dtype, stream);
         }
         if (rows_per_tile <= 128) {
-            HIF4_CW_CASE(4, 8, 4); HIF4_CW_CASE(4, 8, 2); HIF4_CW_CASE(4, 4, 4); HIF4_CW_CASE(4, 4, 2);
+            HIF4_CW_CASE(4, 8, 4); HIF4_CW_CASE(4, 8, 2); HIF4_CW_CASE(4, 4, 4); HIF4_CW_CASE(4, 4, 2); HIF4_CW_CASE(4, NWG, 1);
             return launch_colwave_t<4, NWD, 1, true>(g, out_dtype, stream);
         }
         if (rows_per_tile <= 192) {
@@ -477,10 +481,6 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
         return launch_colwave_t<8, NWD, 1, true>(g, out_dtype, stream);
 #undef HIF4_CW_CASE
     }
-    if (rows_per_tile <= 64) return launch_colwave_t<2, NWG, 1>(g, out_dtype, stream);
-    if (rows_per_tile <= 128) return launch_colwave_t<4, NWG, 1>(g, out_dtype, stream);
-    if (rows_per_tile <= 192) return launch_colwave_t<6, NWG, 1>(g, out_dtype, stream);
-    return launch_colwave_t<8, NWG, 1>(g, out_dtype, stream);
 }
 
 } // namespace hif4

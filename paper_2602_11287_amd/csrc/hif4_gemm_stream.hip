@@ -23,7 +23,7 @@ namespace hif4 {
 // an LDS-writing load (it would serialise every LDS read behind it)
 __device__ __forceinline__ void stream_load_to_lds_16(const void *src, uint32_t lds_byte)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte), "v"(src) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte), "v"(src) : "memory");
 }
 
 #ifndef HIF4_STREAM_CP4

@@ -181,6 +181,37 @@ def test_grouped_gemm(h, oracle, counts):
     assert torch.equal(c, cq)
 
 
+@pytest.mark.parametrize("counts,N,K", [([100, 0, 130], 96, 2048), ([300, 200], 200, 1024), ([40, 50, 60, 1], 8300, 2048)])
+def test_grouped_gemm_few_experts_k_split(h, oracle, counts, N, K):
+    """Few experts against a long K: the grouped call has too few workgroups for the chip and splits K over the wave
+    groups of a workgroup, as the dense few-row calls do (128-, 256- and 64-row tiles; 4 and 8 waves)."""
+    E, M = len(counts), int(sum(counts))
+    offs = np.zeros(E + 1, np.int32)
+    offs[1:] = np.cumsum(counts)
+    rng = np.random.default_rng(E * 1000 + M)
+    ab, (ac, am), _ = quantized_operands(oracle, M, 1, K, 5150 + M)
+    w = rng.standard_normal((E * N, K)) * 0.02
+    wc, wm = oracle.quantize(synth.bits(torch.from_numpy(w).to(torch.bfloat16)))
+    adec, wdec = oracle.dequantize(ac, am), oracle.dequantize(wc, wm)
+    want = np.zeros((M, N))
+    for e in range(E):
+        if counts[e]:
+            want[offs[e]:offs[e + 1]] = oracle.gemm_f64(adec[offs[e]:offs[e + 1]], wdec[e * N:(e + 1) * N])
+    wcd, wmd = dev_packed(wc.reshape(E, N, K // 2), wm.reshape(E, N, K // 64))
+    od = torch.from_numpy(offs).cuda()
+    c = h.hif4_grouped_gemm(h.HIF4_A_HIF4, *dev_packed(ac, am), wcd, wmd, od, out_dtype=h.HIF4_OUT_F32)
+    cq = h.hif4_grouped_gemm(h.HIF4_A_BF16_QUANTIZE, synth.from_bits(ab).cuda(), None, wcd, wmd, od, out_dtype=h.HIF4_OUT_F32)
+    ck = h.hif4_grouped_gemm(h.HIF4_A_BF16_KEEP, synth.from_bits(ab).cuda(), None, wcd, wmd, od, out_dtype=h.HIF4_OUT_F32)
+    torch.cuda.synchronize()
+    assert rel_fro(c.cpu().numpy().astype(np.float64), want) <= TOL
+    assert torch.equal(c, cq)
+    want_k = np.zeros((M, N))
+    for e in range(E):
+        if counts[e]:
+            want_k[offs[e]:offs[e + 1]] = oracle.gemm_f64(ab[offs[e]:offs[e + 1]], wdec[e * N:(e + 1) * N])
+    assert rel_fro(ck.cpu().numpy().astype(np.float64), want_k) <= TOL
+
+
 def test_grouped_gemm_random_routings(h, oracle):
     """A seeded sweep of the grouped call: 1 to 12 experts with 0 to 330 rows each (so the mean row count selects every
     tile height of the few-row kernel, and single experts overflow a tile), ragged N, 1 to 12 units of K, all kinds
