@@ -445,9 +445,10 @@ int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint
     g.E = E;
     constexpr int NWG = HIF4_COLWAVE_NW, NWD = HIF4_COLWAVE_NW_DENSE;
     {
-        // m-tiles: of a dense call, or the upper bound sum_e ceil(rows_e / tile) <= M / tile + E of a grouped one
+        // m-tiles: of a dense call, or what a grouped one is expected to have (between M / tile and M / tile + E; the
+        // grid itself is sized for the upper bound, this number only picks the shape of the workgroups)
         const int tile_rows = rows_per_tile <= 64 ? 64 : rows_per_tile <= 128 ? 128 : rows_per_tile <= 192 ? 192 : 256;
-        const int64_t m_tiles = offs ? M / tile_rows + E : (M + rows_per_tile - 1) / rows_per_tile;
+        const int64_t m_tiles = offs ? M / tile_rows + (E + 1) / 2 : (M + rows_per_tile - 1) / rows_per_tile;
         const int64_t strips = (N + 31) / 32 * m_tiles, nk = K / 64;
         const bool emit = out_dtype >= 16;
         // K parts per workgroup (4, 2 or 1; tiles of more than 128 rows: LDS holds 2) and waves (4 or 8): the
