@@ -19,6 +19,14 @@ ROUND_RHA = 1
 _lib = None
 
 
+class Steps(C.Structure):
+    """Mirror of the C record ``hif4o_steps``: every intermediate of Algorithm 1 for one unit."""
+    _fields_ = [("V16", C.c_uint16 * 16), ("V8", C.c_uint16 * 8), ("Vmax", C.c_uint16), ("SF", C.c_uint16),
+                ("E6M2", C.c_uint8), ("REC", C.c_uint16), ("P8", C.c_uint16 * 8), ("P16", C.c_uint16 * 16),
+                ("E1_8", C.c_uint32), ("E1_16", C.c_uint32), ("scaled", C.c_uint16 * 64), ("S1P2", C.c_uint8 * 64),
+                ("special", C.c_int)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -46,7 +54,9 @@ def lib():
         L.hif4o_decode_unit.restype = None
         L.hif4o_decode_unit.argtypes = [u8p, C.c_uint32, u16p, C.POINTER(C.c_int)]
         L.hif4o_quantize_from.restype = C.c_int
-        L.hif4o_quantize_from.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, u8p, u32p, C.c_int]
+        L.hif4o_quantize_from.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, u8p, u32p, C.c_int, u16p]
+        L.hif4o_encode_unit_steps.restype = None
+        L.hif4o_encode_unit_steps.argtypes = [u16p, C.c_int, C.POINTER(Steps)]
         L.hif4o_f16_to_f64.restype = C.c_double
         L.hif4o_f16_to_f64.argtypes = [C.c_uint16]
         L.hif4o_quantize.restype = C.c_int
@@ -117,6 +127,19 @@ def encode_unit(x64, mode=ROUND_RNE):
     return codes, int(meta.value)
 
 
+def encode_unit_steps(x64, mode=ROUND_RNE):
+    """Algorithm 1 on 64 BF16 patterns -> dict of every intermediate, under the paper's names."""
+    x = np.ascontiguousarray(x64, dtype=np.uint16)
+    assert x.shape == (64,)
+    t = Steps()
+    lib().hif4o_encode_unit_steps(_ptr(x, C.c_uint16), mode, C.byref(t))
+    out = {}
+    for name, _ in Steps._fields_:
+        v = getattr(t, name)
+        out[name] = int(v) if isinstance(v, int) else np.array(list(v), dtype=np.uint32)
+    return out
+
+
 def decode_unit(codes, meta):
     """Eq. 2 on one unit -> uint16[64] BF16 patterns (raises if any value were inexact)."""
     c = np.ascontiguousarray(codes, dtype=np.uint8)
@@ -156,19 +179,22 @@ def quantize(x, mode=ROUND_RNE):
     return codes, meta
 
 
-def quantize_from(x, mode=ROUND_RNE):
-    """rows x K float32 or float16 matrix (numpy) -> planes: every input is rounded to BF16 first."""
+def quantize_from(x, mode=ROUND_RNE, return_bf16=False):
+    """rows x K float32 or float16 matrix (numpy) -> planes: every input is rounded to BF16 first.
+    return_bf16: also return those rounded inputs (uint16 patterns)."""
     x = np.ascontiguousarray(x)
     assert x.ndim == 2 and x.dtype in (np.float32, np.float16)
     rows, K = x.shape
     codes = np.zeros((rows, K // 2), np.uint8)
     meta = np.zeros((rows, K // 64), np.uint32)
     in_dtype = 2 if x.dtype == np.float32 else 1
+    xb = np.zeros((rows, K), np.uint16) if return_bf16 else None
     rc = lib().hif4o_quantize_from(in_dtype, x.ctypes.data_as(C.c_void_p), rows, K, K,
-                                   _ptr(codes, C.c_uint8), _ptr(meta, C.c_uint32), mode)
+                                   _ptr(codes, C.c_uint8), _ptr(meta, C.c_uint32), mode,
+                                   _ptr(xb, C.c_uint16) if return_bf16 else None)
     if rc:
         raise ValueError(f"hif4o_quantize_from failed: {rc}")
-    return codes, meta
+    return (codes, meta, xb) if return_bf16 else (codes, meta)
 
 
 def f16_to_f64(h):

@@ -5,8 +5,9 @@
  * written from the paper (HiFloat4 Format for Language Model Inference):
  *   - decode      : the value equation of Section II-A (Eq. 2) with the E6M2 /
  *                   S1P2 code points of Table 1;
- *   - encode      : Algorithm 1 (Section II-B), taken step by step in the
- *                   paper's order and notation, every multiply producing a BF16;
+ *   - encode      : Algorithm 1 (Section II-B): its three stages in the paper's order and
+ *                   under the paper's names, every multiply producing a BF16, every
+ *                   intermediate kept in a record that the tests can read;
  *   - GEMM        : the plain definition C = dec(A) * dec(W)^T in fp64, which per
  *                   pair of units equals the dot product of Eq. 4 (Section III-B).
  * Nothing here is blocked, fused or reordered.  Only tests, the smoke check and
@@ -15,8 +16,12 @@
  *
  * Pins (see tests/test_oracle_*.py): Table 1 / Table 2 code points and extremes,
  * exhaustive decode in rational arithmetic, brute-force nearest-code search,
- * scaling / negation / permutation invariants, canonical round trips, a unit
- * worked by hand, and the MSE ratios of Section III-A.
+ * scaling / negation / permutation invariants, canonical round trips, units
+ * worked by hand under both roundings (final planes and, through the record of
+ * intermediates, every rounding step on an exact tie), and the MSE ratios of
+ * Section III-A.  Under round-half-away only the rounding to E6M2 can change a
+ * packed unit; the BF16 roundings of SF and of the scaled values (and of FP16 /
+ * FP32 inputs) are still pinned, on the intermediates themselves.
  * Parity unpinned (the paper is silent; these are documented readings): the bit
  * layout of the packed unit, RNE as the default of the two roundings the paper
  * allows, Inf inputs producing the NaN unit, the reciprocal table being rounded
@@ -151,61 +156,91 @@ uint8_t hif4o_to_s1p2(double scaled, int negative, int mode)
 
 #define INV7_BF16 0x3E12u /* (1/7) rounded to BF16 = 73/512 */
 
+/* Every intermediate of one conversion, under the paper's names (Algorithm 1), so that each
+ * rounding step can be pinned on its own by the tests.  BF16 values are bit patterns. */
+typedef struct {
+    uint16_t V16[16], V8[8], Vmax; /* stage 1: peak magnitudes 64 -> 16 -> 8 -> 1                     */
+    uint16_t SF;                   /* stage 2: Vmax * (1/7)_BF16, a BF16                               */
+    uint8_t E6M2;                  /*          BF16_to_E6M2(SF)                                        */
+    uint16_t REC;                  /*          E6M2_REC_to_BF16(E6M2)                                  */
+    uint16_t P8[8], P16[16];       /*          V8[j] * REC and V16[k] * REC, each a BF16               */
+    uint32_t E1_8, E1_16;          /*          the micro-exponent bits                                 */
+    uint16_t scaled[64];           /* stage 3: V64[i] * REC, a BF16 (before the exact 2^-E1 factors)   */
+    uint8_t S1P2[64];              /*          the 4-bit codes                                         */
+    int special;                   /* a NaN or an infinity among the inputs: the unit is the NaN unit  */
+} hif4o_steps;
+
+static double mag_of(uint16_t b) { return hif4o_bf16_to_f64(b & 0x7FFFu); }
+
+/* Stage 1: the tree of peak magnitudes.  Each level takes the larger of its children. */
+static void peak_tree(const uint16_t x[64], hif4o_steps *t)
+{
+    for (int k = 0; k < 16; ++k) {
+        t->V16[k] = 0;
+        for (int i = 4 * k; i < 4 * k + 4; ++i)
+            if (mag_of(x[i]) > mag_of(t->V16[k])) t->V16[k] = x[i] & 0x7FFFu;
+    }
+    for (int j = 0; j < 8; ++j) t->V8[j] = mag_of(t->V16[2 * j + 1]) > mag_of(t->V16[2 * j]) ? t->V16[2 * j + 1] : t->V16[2 * j];
+    t->Vmax = 0;
+    for (int j = 0; j < 8; ++j)
+        if (mag_of(t->V8[j]) > mag_of(t->Vmax)) t->Vmax = t->V8[j];
+}
+
+/* Stage 2: the unit scale from the overall peak, its reciprocal, and one micro-exponent bit per
+ * group of 8 (scaled peak at least 4) and per group of 4 (scaled peak, halved where its group of 8
+ * has its bit set, at least 2).  Every product is a BF16 before it is compared. */
+static void scaling_metadata(hif4o_steps *t, int mode)
+{
+    t->SF = hif4o_bf16_mul(t->Vmax, INV7_BF16, mode);
+    t->E6M2 = hif4o_bf16_to_e6m2(t->SF, mode);
+    t->REC = hif4o_e6m2_rec_to_bf16(t->E6M2);
+    t->E1_8 = t->E1_16 = 0;
+    for (int j = 0; j < 8; ++j) {
+        t->P8[j] = hif4o_bf16_mul(t->V8[j], t->REC, mode);
+        if (hif4o_bf16_to_f64(t->P8[j]) >= 4.0) t->E1_8 |= 1u << j;
+    }
+    for (int k = 0; k < 16; ++k) {
+        t->P16[k] = hif4o_bf16_mul(t->V16[k], t->REC, mode);
+        int above = (int)((t->E1_8 >> (k / 2)) & 1u);             /* the bit of the enclosing group of 8 */
+        if (ldexp(hif4o_bf16_to_f64(t->P16[k]), -above) >= 2.0) t->E1_16 |= 1u << k; /* times 2^-E1_8: exact */
+    }
+}
+
+/* Stage 3: every element times the reciprocal (a BF16), divided by the two powers of two that its
+ * groups carry (exact), rounded to S1P2 with the input's sign. */
+static void element_codes(const uint16_t x[64], hif4o_steps *t, int mode)
+{
+    for (int i = 0; i < 64; ++i) {
+        t->scaled[i] = hif4o_bf16_mul(x[i], t->REC, mode);
+        int halvings = (int)((t->E1_8 >> (i / 8)) & 1u) + (int)((t->E1_16 >> (i / 4)) & 1u);
+        double s = ldexp(hif4o_bf16_to_f64(t->scaled[i]), -halvings);
+        t->S1P2[i] = hif4o_to_s1p2(s, (x[i] & 0x8000u) != 0, mode);
+    }
+}
+
+/* Algorithm 1 for one vector of 64 BF16 values, all intermediates kept. */
+void hif4o_encode_unit_steps(const uint16_t x[64], int mode, hif4o_steps *t)
+{
+    memset(t, 0, sizeof *t);
+    for (int i = 0; i < 64; ++i)
+        if ((x[i] & 0x7FFFu) >= 0x7F80u) t->special = 1; /* Inf or NaN among the inputs */
+    if (t->special) { /* the unit as a whole becomes NaN (Eq. 2, first case) */
+        t->E6M2 = 0xFF;
+        return;
+    }
+    peak_tree(x, t);
+    scaling_metadata(t, mode);
+    element_codes(x, t, mode);
+}
+
 /* Algorithm 1 for one vector of 64 BF16 values.  codes: 32 bytes, meta: one u32. */
 void hif4o_encode_unit(const uint16_t x[64], uint8_t codes[32], uint32_t *meta, int mode)
 {
-    uint16_t mag[64]; /* |V64| as BF16 patterns */
-    int special = 0;
-    for (int i = 0; i < 64; ++i) {
-        mag[i] = x[i] & 0x7FFFu;
-        if (mag[i] >= 0x7F80u) special = 1; /* Inf or NaN among the inputs */
-    }
-    if (special) { /* the unit as a whole becomes NaN (Eq. 2, first case) */
-        memset(codes, 0, 32);
-        *meta = 0x000000FFu;
-        return;
-    }
-
-    /* Stage 1: three-level tree of peak magnitudes, 64 -> 16 -> 8 -> 1. */
-    uint16_t V16[16], V8[8], Vmax = 0;
-    for (int k = 0; k < 16; ++k) {
-        V16[k] = 0;
-        for (int t = 0; t < 4; ++t)
-            if (hif4o_bf16_to_f64(mag[4 * k + t]) > hif4o_bf16_to_f64(V16[k])) V16[k] = mag[4 * k + t];
-    }
-    for (int j = 0; j < 8; ++j) {
-        V8[j] = V16[2 * j];
-        if (hif4o_bf16_to_f64(V16[2 * j + 1]) > hif4o_bf16_to_f64(V8[j])) V8[j] = V16[2 * j + 1];
-    }
-    for (int j = 0; j < 8; ++j)
-        if (hif4o_bf16_to_f64(V8[j]) > hif4o_bf16_to_f64(Vmax)) Vmax = V8[j];
-
-    /* Stage 2: the three levels of scaling metadata. */
-    uint16_t SF = hif4o_bf16_mul(Vmax, INV7_BF16, mode);
-    uint8_t E6M2 = hif4o_bf16_to_e6m2(SF, mode);
-    uint16_t REC = hif4o_e6m2_rec_to_bf16(E6M2);
-
-    uint32_t E1_8 = 0, E1_16 = 0;
-    for (int j = 0; j < 8; ++j) {
-        double p = hif4o_bf16_to_f64(hif4o_bf16_mul(V8[j], REC, mode));
-        if (p >= 4.0) E1_8 |= 1u << j;
-    }
-    for (int k = 0; k < 16; ++k) {
-        double p = hif4o_bf16_to_f64(hif4o_bf16_mul(V16[k], REC, mode));
-        p = ldexp(p, -(int)((E1_8 >> (k >> 1)) & 1u)); /* times 2^-E1_8: exact */
-        if (p >= 2.0) E1_16 |= 1u << k;
-    }
-
-    /* Stage 3: scale the 64 inputs and round each to S1P2. */
+    hif4o_steps t;
+    hif4o_encode_unit_steps(x, mode, &t);
     memset(codes, 0, 32);
-    for (int i = 0; i < 64; ++i) {
-        double s = hif4o_bf16_to_f64(hif4o_bf16_mul(x[i], REC, mode));
-        int shift = (int)((E1_8 >> (i >> 3)) & 1u) + (int)((E1_16 >> (i >> 2)) & 1u);
-        s = ldexp(s, -shift); /* a power of two: no rounding where the result can matter */
-        uint8_t c = hif4o_to_s1p2(s, (x[i] & 0x8000u) != 0, mode);
-        codes[code_byte(i)] |= (uint8_t)(c << code_shift(i));
-    }
-    *meta = (E1_16 << 16) | (E1_8 << 8) | E6M2;
+    for (int i = 0; i < 64; ++i) codes[code_byte(i)] |= (uint8_t)(t.S1P2[i] << code_shift(i));
+    *meta = (t.E1_16 << 16) | (t.E1_8 << 8) | t.E6M2;
 }
 
 /* ------------------------------------------------------------ one unit: decode */
@@ -264,11 +299,17 @@ double hif4o_f16_to_f64(uint16_t h)
 /* FP32 / FP16 matrices (Section II-B, first paragraph: other high-precision formats take
  * the same procedure).  The paper prints no algorithm for them; the reading taken here is
  * that every input is first rounded to BF16 with the conversion's rounding mode, after
- * which Algorithm 1 runs as written.  in_dtype: 1 = FP16 patterns (uint16), 2 = FP32. */
+ * which Algorithm 1 runs as written.  in_dtype: 1 = FP16 patterns (uint16), 2 = FP32.
+ * as_bf16 (may be NULL): receives the rounded inputs, rows x K dense, so that the conversion step
+ * can be pinned on its own. */
 int hif4o_quantize_from(int in_dtype, const void *x, int64_t rows, int64_t K, int64_t ldx,
-                        uint8_t *codes, uint32_t *meta, int mode)
+                        uint8_t *codes, uint32_t *meta, int mode, uint16_t *as_bf16)
 {
-    if (in_dtype == 0) return hif4o_quantize((const uint16_t *)x, rows, K, ldx, codes, meta, mode);
+    if (in_dtype == 0) {
+        if (as_bf16 && K % 64 == 0 && rows >= 0 && K >= 0 && ldx >= K)
+            for (int64_t r = 0; r < rows; ++r) memcpy(as_bf16 + r * K, (const uint16_t *)x + r * ldx, (size_t)K * 2);
+        return hif4o_quantize((const uint16_t *)x, rows, K, ldx, codes, meta, mode);
+    }
     if (in_dtype != 1 && in_dtype != 2) return -4;
     if (K % 64 != 0 || rows < 0 || K < 0 || ldx < K) return -2;
     int64_t upr = K / 64;
@@ -281,6 +322,7 @@ int hif4o_quantize_from(int in_dtype, const void *x, int64_t rows, int64_t K, in
                 double v = in_dtype == 1 ? hif4o_f16_to_f64(((const uint16_t *)x)[at]) : (double)((const float *)x)[at];
                 v64[i] = hif4o_f64_to_bf16(v, mode);
             }
+            if (as_bf16) memcpy(as_bf16 + r * K + 64 * u, v64, sizeof v64);
             hif4o_encode_unit(v64, codes + (r * upr + u) * 32, meta + r * upr + u, mode);
         }
     return 0;
@@ -341,9 +383,9 @@ double hif4o_unit_dot(const uint8_t ca[32], uint32_t ma, const uint8_t cb[32], u
                 int sa = (a & 8) ? -(a & 7) : (a & 7), sb = (b & 8) ? -(b & 7) : (b & 7);
                 inner += sa * sb; /* in units of 1/16 */
             }
-            mid += inner << (((ma >> (16 + j)) & 1u) + ((mb >> (16 + j)) & 1u));
+            mid += inner * ((int64_t)1 << (((ma >> (16 + j)) & 1u) + ((mb >> (16 + j)) & 1u)));
         }
-        outer += mid << (((ma >> (8 + i)) & 1u) + ((mb >> (8 + i)) & 1u));
+        outer += mid * ((int64_t)1 << (((ma >> (8 + i)) & 1u) + ((mb >> (8 + i)) & 1u)));
     }
     return hif4o_e6m2_to_f64((uint8_t)(ma & 0xFF)) * hif4o_e6m2_to_f64((uint8_t)(mb & 0xFF)) * ((double)outer / 16.0);
 }

@@ -57,7 +57,8 @@ def load_units():
         if not t:
             continue
         if t[0] == "unit":
-            cur = units.setdefault(t[1], {"x": {}, "meta": {}, "code": {"rne": {}, "rha": {}}, "dec": {"rne": {}}})
+            cur = units.setdefault(t[1], {"x": {}, "meta": {}, "code": {"rne": {}, "rha": {}}, "dec": {"rne": {}},
+                                          "step": {"rne": [], "rha": []}})
         elif t[0] == "x":
             cur["x"][int(t[1])] = float(t[2])
         elif t[0] == "meta":
@@ -66,10 +67,12 @@ def load_units():
             cur["code"][t[1]][int(t[2])] = int(t[3], 16)
         elif t[0] == "dec":
             cur["dec"][t[1]][int(t[2])] = float(t[3])
+        elif t[0] == "step":
+            cur["step"][t[1]].append((t[2], int(t[3]), int(t[4], 16)))
     return units
 
 
-@pytest.mark.parametrize("name", ["seven", "ten"])
+@pytest.mark.parametrize("name", ["seven", "ten", "e6tie", "sf208"])
 def test_handworked_units(oracle, name):
     u = load_units()[name]
     x = np.zeros(64)
@@ -84,6 +87,12 @@ def test_handworked_units(oracle, name):
         for i, c in u["code"][mode_name].items():
             want[i] = c
         assert (nibbles(codes) == want).all()
+        # intermediates of the conversion (BF16 patterns of SF, the reciprocal, scaled values), where listed
+        steps = oracle.encode_unit_steps(xb, mode)
+        for field, index, value in u["step"][mode_name]:
+            got = steps[field] if np.isscalar(steps[field]) else steps[field][index]
+            assert int(got) == value, (mode_name, field, index, hex(int(got)), hex(value))
+        assert (steps["S1P2"] == want).all() and steps["E6M2"] == (meta & 0xFF)
     codes, meta = oracle.encode_unit(xb)
     y = oracle.decode_unit(codes, meta)
     f = oracle.bf16_bits_to_f64(y)
@@ -137,6 +146,149 @@ def test_encoder_matches_rederivation(oracle, kind):
         wc, wm = rederive_unit(xb)
         assert meta == wm, (hex(meta), hex(wm))
         assert (nibbles(codes) == wc).all()
+
+
+# ---- the same re-derivation in exact rationals, for either rounding (nothing from torch: its
+# bfloat16 arithmetic rounds half to even only).  Every rounding is a nearest search over the target
+# grid with the tie rule stated once, in nearest().
+
+def nearest(v, grid_floor, step, mode):
+    """v >= 0 (Fraction) -> the multiple of `step` nearest to it; ties to the even multiple (mode 0)
+    or away from zero (mode 1).  grid_floor is the largest multiple not above v."""
+    lo, hi = grid_floor, grid_floor + step
+    assert lo <= v < hi
+    if v - lo != hi - v:
+        return lo if v - lo < hi - v else hi
+    if mode == 1:
+        return hi
+    return lo if (lo / step) % 2 == 0 else hi
+
+
+def bf16_round_fraction(v, mode):
+    """Nearest BF16 (normal range) to the positive rational v, as a Fraction."""
+    e = 0
+    while Fraction(2) ** (e + 1) <= v:
+        e += 1
+    while Fraction(2) ** e > v:
+        e -= 1
+    step = Fraction(2) ** (e - 7)
+    return nearest(v, (v // step) * step, step, mode)
+
+
+def rederive_unit_exact(xb, mode):
+    x = [Fraction(float(v)) for v in oracle_widen(xb)]
+    a = [abs(v) for v in x]
+    vmax = max(a)
+    if vmax == 0:
+        return np.array([8 if (b >> 15) else 0 for b in xb], np.uint8), 0
+    sf = bf16_round_fraction(vmax * Fraction(73, 512), mode)
+    # E6M2: nearest value with a 3-bit significand; the range limits are not reached by these inputs
+    e = 0
+    while Fraction(2) ** (e + 1) <= sf:
+        e += 1
+    while Fraction(2) ** e > sf:
+        e -= 1
+    q = Fraction(2) ** (e - 2)
+    s6 = nearest(sf, (sf // q) * q, q, mode)
+    byte = E6M2_TABLE.index(s6)
+    rec = {0: Fraction(1), 1: Fraction(205, 256), 2: Fraction(171, 256), 3: Fraction(146, 256)}[byte & 3] / Fraction(2) ** ((byte >> 2) - 48)
+    p = [bf16_round_fraction(v * rec, mode) if v else Fraction(0) for v in a]
+    e8 = [int(max(p[8 * j:8 * j + 8]) >= 4) for j in range(8)]
+    e16 = [int(max(p[4 * k:4 * k + 4]) / 2 ** e8[k // 2] >= 2) for k in range(16)]
+    codes = np.zeros(64, np.uint8)
+    quarter = Fraction(1, 4)
+    for i in range(64):
+        s = p[i] / 2 ** (e8[i // 8] + e16[i // 4])
+        m = min(7, int(nearest(s, (s // quarter) * quarter, quarter, mode) / quarter))
+        codes[i] = (8 if (xb[i] >> 15) else 0) | m
+    meta = byte | (sum(b << j for j, b in enumerate(e8)) << 8) | (sum(b << k for k, b in enumerate(e16)) << 16)
+    return codes, meta
+
+
+def oracle_widen(xb):
+    """BF16 patterns -> exact floats, by the IEEE field definition (no oracle code involved)."""
+    return (np.asarray(xb, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def e6m2_tie_units(rng, n):
+    """Units whose peak makes SF an exact tie of the E6M2 grid (peak significands 182/128, 252/128,
+    253/128, found by exhaustive search in test_which_roundings_can_change_a_unit): the one place
+    where the two roundings part for good."""
+    out = random_units(rng, n, "short")
+    for t, row in enumerate(out):
+        sig = (182, 252, 253)[t % 3]
+        peak = np.uint16(((120 + t % 14) << 7) | (sig - 128))
+        row[:] = np.minimum(row & 0x7FFF, peak - 1) | (row & 0x8000)
+        row[int(rng.integers(0, 64))] = peak
+    return out
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("kind", ["gauss", "short", "scales", "e6tie"])
+def test_encoder_matches_exact_rederivation_in_both_roundings(oracle, kind, mode):
+    rng = np.random.default_rng(300 + 7 * mode + len(kind))
+    xs = e6m2_tie_units(rng, 30) if kind == "e6tie" else random_units(rng, 60 if kind == "scales" else 40, kind)
+    if kind == "scales":   # stay inside the range where neither BF16 nor E6M2 saturates
+        xs = xs[[(0x2C00 < (r & 0x7FFF).max() < 0x4600) and ((r & 0x7FFF)[(r & 0x7FFF) > 0].min() > 0x1800) for r in xs]]
+        assert len(xs) >= 10
+    differ = 0
+    for xb in xs:
+        codes, meta = oracle.encode_unit(xb, mode)
+        wc, wm = rederive_unit_exact(xb, mode)
+        assert meta == wm, (hex(meta), hex(wm))
+        assert (nibbles(codes) == wc).all()
+        differ += oracle.encode_unit(xb, 1 - mode)[1] != meta
+    if kind == "e6tie":
+        assert differ == len(xs), "on these units the two roundings give different E6M2 bytes"
+
+
+def test_which_roundings_can_change_a_unit():
+    """Exhaustive, in exact rationals, no oracle involved: of the rounding steps of Algorithm 1 only the
+    rounding to E6M2 and the rounding to S1P2 can tell half-to-even from half-away in the packed unit.
+    (i) SF = BF16(Vmax * 73/512): the two roundings differ for one peak significand only (160/128) and
+    both results give the same E6M2 under either E6M2 rounding.  (ii) x * REC: an exact BF16 tie with
+    different neighbours exists only for the reciprocal 146/256 and x = 1.25 * 2^e, and both neighbours
+    compare alike against 4 and 2 and round to the same S1P2 code at every exponent and shift.
+    (iii) E6M2 ties are reached from peak significands 182, 252 and 253 (of 128).  The oracle's
+    intermediates at (i) and (ii) are pinned through its record of steps in the hand-worked units."""
+    def e6m2_of(sf, mode):
+        e = 0
+        while Fraction(2) ** (e + 1) <= sf:
+            e += 1
+        while Fraction(2) ** e > sf:
+            e -= 1
+        q = Fraction(2) ** (e - 2)
+        return nearest(sf, (sf // q) * q, q, mode)
+    sf_differs, e6_ties = [], []
+    for V in range(128, 256):
+        exact = Fraction(V, 128) * Fraction(73, 512)
+        a, b = bf16_round_fraction(exact, 0), bf16_round_fraction(exact, 1)
+        if a != b:
+            sf_differs.append(V)
+            for m2 in (0, 1):
+                assert e6m2_of(a, m2) == e6m2_of(b, m2)
+        if e6m2_of(b, 0) != e6m2_of(b, 1):
+            e6_ties.append(V)
+    assert sf_differs == [160] and e6_ties == [182, 252, 253]
+    quarter = Fraction(1, 4)
+    product_ties = set()
+    for M, rec in enumerate((Fraction(1), Fraction(205, 256), Fraction(171, 256), Fraction(146, 256))):
+        for X in range(128, 256):
+            for ex in range(-9, 4):
+                exact = Fraction(X, 128) * Fraction(2) ** ex * rec
+                pa, pb = bf16_round_fraction(exact, 0), bf16_round_fraction(exact, 1)
+                if pa == pb:
+                    continue
+                product_ties.add((M, X))
+                for thr in (4, 2):
+                    assert (pa >= thr) == (pb >= thr)
+                for sh in range(3):
+                    for m2 in (0, 1):
+                        sa, sb = pa / 2 ** sh, pb / 2 ** sh
+                        ca = min(7, int(nearest(sa, (sa // quarter) * quarter, quarter, m2) / quarter))
+                        cb = min(7, int(nearest(sb, (sb // quarter) * quarter, quarter, m2) / quarter))
+                        assert ca == cb
+    assert product_ties == {(3, 160)}
 
 
 # ------------------------------------------------------------------ invariants
@@ -359,6 +511,31 @@ def test_quantize_from_half_away_ties_and_overflow(oracle):
     big[0, 5] = 3.4e38
     c, m = oracle.quantize_from(big)
     assert m[0, 0] == 0xFF and not c.any()
+
+
+def test_input_conversion_rounding_is_pinned_on_the_rounded_inputs(oracle):
+    """The BF16 patterns that FP32 / FP16 inputs become, read back from the conversion itself: exact
+    ties go to the even neighbour under half-to-even and away from zero under half-away; everything
+    else goes to the nearer neighbour under both.  (Under half-away the direction of such a tie cannot
+    change the packed unit: every decision threshold of Algorithm 1, seen from the input, is a BF16
+    with an even significand, and a tie's two neighbours lie on the same side of it.  So the pin is on
+    the rounded inputs.)"""
+    vals = [1.0 + 2.0 ** -8, -(1.0 + 2.0 ** -8), 1.0 + 3 * 2.0 ** -8, -(1.0 + 3 * 2.0 ** -8), 1.0 + 2.0 ** -8 + 2.0 ** -20,
+            1.0 + 2.0 ** -8 - 2.0 ** -20, 6.0 + 2.0 ** -6, 2.0 ** -20 * (1 + 5 * 2.0 ** -8), 255.5, 0.0]
+    want = {0: [0x3F80, 0xBF80, 0x3F82, 0xBF82, 0x3F81, 0x3F80, 0x40C0, 0x3580 + 2, 0x4380, 0x0000],
+            1: [0x3F81, 0xBF81, 0x3F82, 0xBF82, 0x3F81, 0x3F80, 0x40C1, 0x3580 + 3, 0x4380, 0x0000]}
+    x = np.zeros((1, 64), np.float32)
+    x[0, :len(vals)] = vals
+    assert (x[0, :len(vals)].astype(np.float64) == np.array(vals)).all(), "inputs are exact in FP32"
+    for mode in (0, 1):
+        _, _, xb = oracle.quantize_from(x, mode, return_bf16=True)
+        assert [int(v) for v in xb[0, :len(vals)]] == want[mode], (mode, [hex(int(v)) for v in xb[0, :len(vals)]])
+    # FP16: 1 + 2^-8 and 1 + 3 * 2^-8 are exact there (ten mantissa bits)
+    h = np.zeros((1, 64), np.float16)
+    h[0, :4] = [1.0 + 2.0 ** -8, -(1.0 + 2.0 ** -8), 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -10]
+    for mode, w in ((0, [0x3F80, 0xBF80, 0x3F82, 0x3F81]), (1, [0x3F81, 0xBF81, 0x3F82, 0x3F81])):
+        _, _, hb = oracle.quantize_from(h, mode, return_bf16=True)
+        assert [int(v) for v in hb[0, :4]] == w
 
 
 def test_f16_widening_matches_numpy(oracle):

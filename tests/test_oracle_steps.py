@@ -133,3 +133,47 @@ def test_s1p2_rounding_brute_force(oracle):
                 if len(ties) == 2:
                     assert m == ([k for k in ties if k % 2 == 0][0] if mode == oracle.ROUND_RNE else max(ties))
     assert oracle.to_s1p2(1e30, 1) == 0xF and oracle.to_s1p2(1.875, 0) == 7
+
+
+def nearest_bf16_by_search(v, mode):
+    """Positive rational -> nearest finite positive BF16 pattern by search over all of them; an exact tie
+    goes to the even pattern (mode 0) or to the larger one (mode 1)."""
+    lo, hi = 0, 0x7F7F
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if bf16_fraction(mid) <= v:
+            lo = mid
+        else:
+            hi = mid
+    dl, dh = v - bf16_fraction(lo), bf16_fraction(hi) - v
+    if dl != dh:
+        return lo if dl < dh else hi
+    return hi if mode == 1 else (lo if lo % 2 == 0 else hi)
+
+
+def test_bf16_mul_half_away_on_exact_ties(oracle):
+    """Products that are exact BF16 ties (found by search, not by formula): half-away takes the larger
+    magnitude, half-to-even the even pattern; checked against the search above, signs included."""
+    rng = np.random.default_rng(6)
+    ties = 0
+    pairs = [(0x4120, 0x3E12), (0x3FA0, 0x3F12), (0x40A0, 0x3F92), (0x40E0, 0x3E12)]  # 10/7, 1.25*146/256, 5*146/128, 7/7
+    pairs += [(int(a), int(b)) for a, b in zip(rng.integers(0x3000, 0x5000, 3000), rng.integers(0x3000, 0x5000, 3000))]
+    for a, b in pairs:
+        exact = bf16_fraction(a) * bf16_fraction(b)
+        for mode in (oracle.ROUND_RNE, oracle.ROUND_RHA):
+            want = nearest_bf16_by_search(exact, mode)
+            assert oracle.bf16_mul(a, b, mode) == want
+            assert oracle.bf16_mul(a | 0x8000, b, mode) == want | 0x8000
+        ties += nearest_bf16_by_search(exact, 0) != nearest_bf16_by_search(exact, 1)
+    assert ties >= 3, "the list holds products on which the two roundings differ"
+
+
+def test_bf16_to_e6m2_half_away_on_every_tie(oracle):
+    """Every BF16 whose significand lies half-way between two E6M2 significands, at several exponents:
+    1.125 and 1.625 part the two roundings, 1.375 and 1.875 do not (their even neighbour is the upper one)."""
+    for e in (-40, -1, 0, 7, 14):
+        for sig, rne_q, rha_q in ((1.125, 4, 5), (1.375, 6, 6), (1.625, 6, 7), (1.875, 8, 8)):
+            bits = oracle.f64_to_bf16(sig * 2.0 ** e)
+            for mode, q in ((oracle.ROUND_RNE, rne_q), (oracle.ROUND_RHA, rha_q)):
+                ee, qq = (e + 1, 4) if q == 8 else (e, q)
+                assert oracle.bf16_to_e6m2(bits, mode) == ((ee + 48) << 2) | (qq - 4)
