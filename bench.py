@@ -211,7 +211,7 @@ def main():
 
     if not args.no_gemm:
         try:
-            from paper_2602_11287_amd import bench_gemm
+            import bench_gemm
             out["legs"].update(bench_gemm.run(hif4, synth, dev, args.steps, args.warmup, MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBPS))
         except ImportError:
             pass

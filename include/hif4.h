@@ -121,9 +121,10 @@ int hif4_dequantize(const uint8_t *codes, const uint32_t *meta, int64_t rows, in
  *   c          out  BF16 or fp32 [M][ldc] per out_dtype, ldc >= N
  *   workspace       device scratch of at least hif4_gemm_workspace_bytes(a_kind, M, K)
  *                   bytes, 16-byte aligned.  Kinds 0 and 1 use it for the exact BF16 values
- *                   of the HiF4 activations (2 bytes per element; kind 0 also for the packed
- *                   planes before that); kind 2 needs none and it may be NULL.  Its contents
- *                   after the call are unspecified.
+ *                   of the HiF4 activations (2 bytes per element; when the call quantises A
+ *                   itself, always with HIF4_ROUND_RNE, the packed planes never reach memory);
+ *                   kind 2 needs none and it may be NULL.  Its contents after the call are
+ *                   unspecified.
  * M == 0 or N == 0 is a no-op; K == 0 writes zeros.
  * Which kernel runs depends on a_kind, M, N, K and the workspace size only, and every kernel adds
  * its products in a fixed order (no atomics): equal calls give equal bits; calls that differ in

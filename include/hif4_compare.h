@@ -76,16 +76,6 @@ int hif4ref_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_
  */
 int hif4ref_mfma_loop(int kind, int iters, float *out, void *stream);
 
-/* Instruction-issue probe for the benchmark (Section III-B prices a dot product in matrix and
- * scalar operations; on this chip the expansion of Eq. 2 runs on the vector ALUs beside the
- * matrix pipeline, and this measures how the two share a SIMD).  256 workgroups of
- * 256 * waves_per_simd threads; every wave runs 4 * iters slots of
- * [one v_mfma_f32_32x32x16_bf16 if with_mfma ; n_valu single-cycle-class vector instructions].
- *   n_valu          0, 4, 8, 12 or 16; waves_per_simd 1, 2 or 4 (else HIF4_ERR_UNSUPPORTED)
- *   out             device, 262144 floats, receives checksums nobody needs
- */
-int hif4ref_issue_loop(int n_valu, int with_mfma, int waves_per_simd, int iters, float *out, void *stream);
-
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,6 @@ int launch_mxfp4_pack(const void *x, int64_t rows, int64_t K, int64_t ldx, void 
 int launch_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_cells, const void *w_scales, int64_t M, int64_t N,
                       int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream);
 int launch_mfma_loop(int kind, int iters, float *out, hipStream_t stream);
-int launch_issue_loop(int n_valu, int with_mfma, int waves_per_simd, int iters, float *out, hipStream_t stream);
 size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 } // namespace hif4
@@ -236,16 +235,6 @@ int hif4ref_mfma_loop(int kind, int iters, float *out, void *stream)
     if (!out) return HIF4_ERR_NULL;
     if (!aligned(out, 4)) return HIF4_ERR_ALIGN;
     return hif4::launch_mfma_loop(kind, iters, out, static_cast<hipStream_t>(stream));
-}
-
-int hif4ref_issue_loop(int n_valu, int with_mfma, int waves_per_simd, int iters, float *out, void *stream)
-{
-    if (n_valu != 0 && n_valu != 4 && n_valu != 8 && n_valu != 12 && n_valu != 16) return HIF4_ERR_UNSUPPORTED;
-    if (waves_per_simd != 1 && waves_per_simd != 2 && waves_per_simd != 4) return HIF4_ERR_UNSUPPORTED;
-    if (iters < 0 || iters > (1 << 24)) return HIF4_ERR_SHAPE;
-    if (!out) return HIF4_ERR_NULL;
-    if (!aligned(out, 4)) return HIF4_ERR_ALIGN;
-    return hif4::launch_issue_loop(n_valu, with_mfma != 0, waves_per_simd, iters, out, static_cast<hipStream_t>(stream));
 }
 
 const char *hif4_status_string(int status)

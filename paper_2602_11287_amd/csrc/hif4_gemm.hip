@@ -93,7 +93,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_kernel(GemmArgs g)
     }
     if (GROUPED) {
         int e;
-        if (!find_expert_tile<BM>(g.offs, g.E, tile_m, lane, e, row0, rows_end)) return;
+        if (!find_expert_tile<BM>(g.offs, g.E, g.M, tile_m, lane, e, row0, rows_end)) return;
         w_codes += (int64_t)e * g.N * (g.K / 8);
         w_meta += (int64_t)e * g.N * (g.K / 64);
     } else {
@@ -521,16 +521,15 @@ static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stre
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 
-// Workspace layout.  HIF4_A_BF16_QUANTIZE: packed A (codes, meta), then its decoded BF16 copy;
-// HIF4_A_HIF4: the decoded BF16 copy only.  Every part starts on a 16-byte boundary.
+// Workspace layout.  Both HiF4 kinds of A: the exact BF16 values of the HiF4 activations (2 bytes per
+// element; when the call quantises A itself the packed planes never reach memory).  Every part starts
+// on a 16-byte boundary.
 static inline size_t align16(size_t n) { return (n + 15) & ~(size_t)15; }
 
 size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K)
 {
     if (M <= 0 || K <= 0) return 0;
-    const size_t decoded = (size_t)M * (size_t)K * 2;
-    if (a_kind == HIF4_A_HIF4) return decoded;
-    if (a_kind == HIF4_A_BF16_QUANTIZE) return align16((size_t)M * (size_t)K / 2) + align16((size_t)M * (size_t)(K / 64) * 4) + decoded;
+    if (a_kind == HIF4_A_HIF4 || a_kind == HIF4_A_BF16_QUANTIZE) return (size_t)M * (size_t)K * 2;
     return 0;
 }
 
@@ -683,10 +682,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         uint8_t *ws = static_cast<uint8_t *>(workspace);
         const size_t base = align16(gemm_workspace_bytes(a_kind, M, K));
         const bool planes = !offs && decoded_w_pays(M, N, K) && workspace_bytes >= base + (size_t)N * (size_t)K * 2;
-        // the decoded copy of A sits behind the room for its packed planes (HIF4_A_BF16_QUANTIZE)
-        uint8_t *adec = a_kind == HIF4_A_BF16_QUANTIZE
-                            ? ws + align16((size_t)M * (size_t)K / 2) + align16((size_t)M * (size_t)(K / 64) * 4)
-                            : ws;
+        uint8_t *adec = ws; // the decoded copy of A
         if (planes) {
             // room for a decoded copy of W and enough rows for it to pay: both operands as
             // cell planes, main loop without any expansion

@@ -51,9 +51,11 @@ __global__ __launch_bounds__(256) void decode_planes_kernel(const uint32_t *__re
                                                             const uint32_t *__restrict__ meta, int64_t rows,
                                                             int64_t upr, uint4 *__restrict__ planes)
 {
-    const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x % 64;
+    // one grid axis (row blocks fastest): K is not bounded by the 65535 blocks of a second axis
+    const int64_t row_blocks = (rows + 63) / 64;
+    const int64_t row = (int64_t)(blockIdx.x % row_blocks) * 64 + threadIdx.x % 64;
     const int hu = threadIdx.x / 64;
-    const int64_t unit = (int64_t)blockIdx.y * 2 + (hu >> 1);
+    const int64_t unit = (int64_t)(blockIdx.x / row_blocks) * 2 + (hu >> 1);
     if (row >= rows || unit >= upr) return;
     const int hh = hu & 1;
     const uint4 c = *reinterpret_cast<const uint4 *>(codes + (row * upr + unit) * 8 + 4 * hh);
@@ -72,8 +74,9 @@ __global__ __launch_bounds__(256) void decode_planes_kernel(const uint32_t *__re
 __global__ __launch_bounds__(512) void bf16_to_planes_kernel(const uint16_t *__restrict__ x, int64_t rows, int64_t ldx,
                                                              uint4 *__restrict__ planes)
 {
-    const int64_t row = (int64_t)blockIdx.x * 64 + threadIdx.x % 64;
-    const int64_t g = (int64_t)blockIdx.y * 8 + threadIdx.x / 64;
+    const int64_t row_blocks = (rows + 63) / 64; // one grid axis, row blocks fastest
+    const int64_t row = (int64_t)(blockIdx.x % row_blocks) * 64 + threadIdx.x % 64;
+    const int64_t g = (int64_t)(blockIdx.x / row_blocks) * 8 + threadIdx.x / 64;
     if (row >= rows) return;
     planes[g * rows + row] = permute_bf16_cell(*reinterpret_cast<const uint4 *>(x + row * ldx + g * 8));
 }
@@ -81,7 +84,9 @@ __global__ __launch_bounds__(512) void bf16_to_planes_kernel(const uint16_t *__r
 int launch_bf16_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx, void *planes, hipStream_t stream)
 {
     if (rows == 0 || K == 0) return HIF4_OK;
-    const dim3 grid((unsigned)((rows + 63) / 64), (unsigned)(K / 64)), block(512);
+    const int64_t blocks = (rows + 63) / 64 * (K / 64);
+    if (blocks > 0x7FFFFFFF) return HIF4_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks), block(512);
     hipLaunchKernelGGL(bf16_to_planes_kernel, grid, block, 0, stream, static_cast<const uint16_t *>(x), rows, ldx,
                        static_cast<uint4 *>(planes));
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
@@ -92,7 +97,9 @@ int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t row
 {
     const int64_t upr = K / 64;
     if (rows == 0 || upr == 0) return HIF4_OK;
-    const dim3 grid((unsigned)((rows + 63) / 64), (unsigned)((upr + 1) / 2)), block(256);
+    const int64_t blocks = (rows + 63) / 64 * ((upr + 1) / 2);
+    if (blocks > 0x7FFFFFFF) return HIF4_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks), block(256);
     hipLaunchKernelGGL(decode_planes_kernel, grid, block, 0, stream, reinterpret_cast<const uint32_t *>(codes), meta, rows,
                        upr, static_cast<uint4 *>(planes));
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;

@@ -124,7 +124,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     const uint32_t *w_codes = g.w_codes, *w_meta = g.w_meta;
     if (g.offs) {
         int e;
-        if (!find_expert_tile<BM>(g.offs, g.E, tile_m, lane, e, row0, rows_end)) return;
+        if (!find_expert_tile<BM>(g.offs, g.E, g.M, tile_m, lane, e, row0, rows_end)) return;
         w_codes += (int64_t)e * g.N * (g.K / 8);
         w_meta += (int64_t)e * g.N * (g.K / 64);
     } else {

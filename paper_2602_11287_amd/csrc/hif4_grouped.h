@@ -10,9 +10,11 @@ namespace hif4 {
 // inclusive scan of their tile counts across the lanes, a ballot for the first lane whose
 // running count passes tile_m.  Returns false when tile_m lies past the last tile (the grid of a
 // grouped launch is an upper bound, the host does not know the counts).
+// The offsets are the caller's: they are clamped to [0, total_rows] and an expert whose range runs
+// backwards counts as empty, so that no row outside A and C is ever touched whatever they hold.
 template <int BM>
-__device__ __forceinline__ bool find_expert_tile(const int32_t *__restrict__ offs, int E, int tile_m, int lane, int &e,
-                                                 int &row0, int &rows_end)
+__device__ __forceinline__ bool find_expert_tile(const int32_t *__restrict__ offs, int E, int total_rows, int tile_m, int lane,
+                                                 int &e, int &row0, int &rows_end)
 {
     for (int base = 0, acc = 0; base < E; base += 64) {
         const int ee = base + lane;
@@ -20,6 +22,8 @@ __device__ __forceinline__ bool find_expert_tile(const int32_t *__restrict__ off
         if (ee < E) {
             lo = offs[ee];
             hi = offs[ee + 1];
+            lo = lo < 0 ? 0 : (lo > total_rows ? total_rows : lo);
+            hi = hi < lo ? lo : (hi > total_rows ? total_rows : hi);
         }
         const int nt = (hi - lo + BM - 1) / BM;
         int incl = nt;

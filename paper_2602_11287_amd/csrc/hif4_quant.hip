@@ -143,7 +143,9 @@ __global__ __launch_bounds__(256) void encode_to_planes_kernel(const void *__res
 {
     constexpr int LPU = 4, NCH = 2;
     const int l = (int)(threadIdx.x % LPU);
-    const int64_t r = (int64_t)blockIdx.x * 64 + threadIdx.x / LPU, u = blockIdx.y;
+    // one grid axis (row blocks fastest): K is not bounded by the 65535 blocks of a second axis
+    const int64_t row_blocks = (rows + 63) / 64;
+    const int64_t r = (int64_t)(blockIdx.x % row_blocks) * 64 + threadIdx.x / LPU, u = blockIdx.x / row_blocks;
     const bool live = r < rows;
     const int64_t row = live ? r : rows - 1; // dead lanes redo the last row and store nothing
     const int64_t e0 = row * ldx + u * 64;
@@ -163,7 +165,9 @@ int launch_encode_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx,
 {
     const int64_t upr = K / 64;
     if (rows == 0 || upr == 0) return HIF4_OK;
-    const dim3 grid((unsigned)((rows + 63) / 64), (unsigned)upr), block(256);
+    const int64_t blocks = (rows + 63) / 64 * upr;
+    if (blocks > 0x7FFFFFFF) return HIF4_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks), block(256);
     uint4 *y = static_cast<uint4 *>(planes);
     if (mode == HIF4_ROUND_RNE) hipLaunchKernelGGL(encode_to_planes_kernel<HIF4_ROUND_RNE>, grid, block, 0, stream, x, rows, ldx, y);
     else hipLaunchKernelGGL(encode_to_planes_kernel<HIF4_ROUND_RHA>, grid, block, 0, stream, x, rows, ldx, y);

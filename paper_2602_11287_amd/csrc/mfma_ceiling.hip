@@ -54,55 +54,6 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(float *out, int iters, u
     out[blockIdx.x * 512 + threadIdx.x] = t;
 }
 
-// How matrix and vector instructions share a SIMD: every wave runs `iters` times four slots of
-// [one v_mfma_f32_32x32x16_bf16 (MF) ; NV v_perm_b32 on four independent chains], WPS waves per
-// SIMD.  Operands are small integers, so that the clock stays up and the figures are issue
-// rates, not power limits.  Timed by the benchmark: ns per slot and wave.
-template <int NV, bool MF>
-__global__ __launch_bounds__(1024) void issue_loop_kernel(float *out, int iters, uint32_t seed)
-{
-    f32x16_t acc[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
-    const uint4 av = make_uint4(0x3F803F80u, 0x40003F80u, 0x3F803F80u, 0x3F803F80u), bv = make_uint4(0x3F803F80u, 0x3F803F80u, 0x40003F80u, 0x3F803F80u);
-    uint32_t x[4] = { seed + threadIdx.x, seed * 3 + threadIdx.x, seed * 5 + threadIdx.x, seed * 7 + threadIdx.x };
-    const uint32_t y = threadIdx.x * 2654435761u;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (MF) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, bv), acc[i], 0, 0, 0);
-#pragma unroll
-            for (int v = 0; v < NV; ++v) asm volatile("v_perm_b32 %0, %0, %1, %2" : "+v"(x[v % 4]) : "v"(y), "v"(0x07060302u));
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    float t = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t += acc[i][r];
-    out[blockIdx.x * blockDim.x + threadIdx.x] = t + (float)(x[0] ^ x[1] ^ x[2] ^ x[3]);
-}
-
-int launch_issue_loop(int n_valu, int with_mfma, int waves_per_simd, int iters, float *out, hipStream_t stream)
-{
-    const dim3 grid(256), block(256 * waves_per_simd);
-#define HIF4_ISSUE_CASE(NV)                                                                                         \
-    if (n_valu == NV) {                                                                                             \
-        if (with_mfma) hipLaunchKernelGGL((issue_loop_kernel<NV, true>), grid, block, 0, stream, out, iters, 1u);   \
-        else hipLaunchKernelGGL((issue_loop_kernel<NV, false>), grid, block, 0, stream, out, iters, 1u);            \
-    }
-    HIF4_ISSUE_CASE(0)
-    HIF4_ISSUE_CASE(4)
-    HIF4_ISSUE_CASE(8)
-    HIF4_ISSUE_CASE(12)
-    HIF4_ISSUE_CASE(16)
-#undef HIF4_ISSUE_CASE
-    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
-}
-
 // KIND 2 of the MFMA-only loop: v_mfma_f32_16x16x32_bf16, sixteen accumulators of 16 x 16 per wave and
 // iteration (the same flops per iteration as the eight 32 x 32 x 16 of KIND 0).
 __global__ __launch_bounds__(512) void mfma_loop16_kernel(float *out, int iters, uint32_t seed)

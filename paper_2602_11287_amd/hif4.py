@@ -22,7 +22,7 @@ HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_gemm_to_hif4", "hif4_grouped_gemm",
            "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version",
            "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16",
-           "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm", "hif4ref_mfma_loop", "hif4ref_issue_loop"]
+           "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm", "hif4ref_mfma_loop"]
 
 
 class Hif4Error(RuntimeError):
@@ -72,8 +72,6 @@ def load():
         L.hif4ref_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, i32, vp]
         L.hif4ref_mfma_loop.restype = i32
         L.hif4ref_mfma_loop.argtypes = [i32, i32, vp, vp]
-        L.hif4ref_issue_loop.restype = i32
-        L.hif4ref_issue_loop.argtypes = [i32, i32, i32, i32, vp, vp]
         L.hif4_status_string.restype = C.c_char_p
         L.hif4_status_string.argtypes = [i32]
         L.hif4_version.restype = i32
@@ -293,11 +291,3 @@ def hif4ref_mfma_loop(kind, iters, out, stream=None):
     assert out.is_cuda and out.dtype == torch.float32 and out.numel() >= 131072
     _check(load().hif4ref_mfma_loop(int(kind), int(iters), _ptr(out), _stream(stream)), "hif4ref_mfma_loop")
     return 2048 * int(iters) * 8 * (131072 if kind == 1 else 32768)
-
-
-def hif4ref_issue_loop(n_valu, with_mfma, waves_per_simd, iters, out, stream=None):
-    """out: CUDA float32 [262144]; returns the number of slots each wave runs (4 * iters)."""
-    assert out.is_cuda and out.dtype == torch.float32 and out.numel() >= 262144
-    _check(load().hif4ref_issue_loop(int(n_valu), int(bool(with_mfma)), int(waves_per_simd), int(iters), _ptr(out), _stream(stream)),
-           "hif4ref_issue_loop")
-    return 4 * int(iters)

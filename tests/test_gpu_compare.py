@@ -128,14 +128,8 @@ def test_mxfp4_reference_gemm(h, oracle, M, N, K):
     assert rel <= 1e-5, rel
 
 
-def test_issue_probe_runs(h):
-    """The instruction-issue probe of the benchmark: every offered shape launches, finishes and writes its checksums."""
-    out = torch.full((262144,), float("nan"), dtype=torch.float32, device="cuda")
-    for wps in (1, 2, 4):
-        for n_valu, mf in ((0, 1), (8, 0), (12, 1), (16, 1)):
-            assert h.hif4ref_issue_loop(n_valu, mf, wps, 8, out) == 32
-            torch.cuda.synchronize()
-            assert torch.isfinite(out[:256 * 256 * wps]).all()
+def test_mfma_only_loops_run(h):
+    """The MFMA-only loops of the benchmark: every kind launches, finishes and reports its flop count."""
     scratch = torch.empty(131072, dtype=torch.float32, device="cuda")
     assert h.hif4ref_mfma_loop(0, 4, scratch) == 2048 * 4 * 8 * 32768
     assert h.hif4ref_mfma_loop(2, 4, scratch) == 2048 * 4 * 8 * 32768
