@@ -52,7 +52,8 @@ enum {
     HIF4_ERR_ALIGN = -3,       /* BF16 matrices: base and row stride 16-byte aligned; codes 16-byte; meta 4-byte */
     HIF4_ERR_UNSUPPORTED = -4, /* an enum value this build does not implement */
     HIF4_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than hif4_gemm_workspace_bytes() */
-    HIF4_ERR_DEVICE = -6       /* the HIP runtime reported an error at launch */
+    HIF4_ERR_DEVICE = -6,      /* the HIP runtime reported an error at launch */
+    HIF4_ERR_SCRATCH = -7      /* hif4_gemm_noalloc: the call needs more than HIF4_NOALLOC_SCRATCH_BYTES of scratch */
 };
 
 /* Rounding used by every rounding step of the conversion (Section II-B, last
@@ -187,6 +188,31 @@ size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K)
  * the smaller one.  Host function.
  */
 size_t hif4_gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
+
+/*
+ * hif4_gemm for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The call takes the
+ * scratch that hif4_gemm takes from its workspace argument (the exact BF16 values of HiF4
+ * activations, hif4_gemm_workspace_bytes(a_kind, M, K) bytes) from a static device array of
+ * HIF4_NOALLOC_SCRATCH_BYTES bytes inside the library instead; it allocates and frees nothing.  Every
+ * GPU the library runs on holds its own copy of that array from the first such call on it until the
+ * process ends.  Result: bit for bit that of hif4_gemm given a workspace of exactly
+ * hif4_gemm_workspace_bytes(a_kind, M, K) bytes (the same kernels run).  a_kind HIF4_A_BF16_KEEP needs no
+ * scratch and is hif4_gemm with a NULL workspace.
+ * A call that needs more scratch returns HIF4_ERR_SCRATCH and enqueues nothing; other arguments and
+ * errors as hif4_gemm.  All calls on one GPU share the one array, which keeps the last call's contents
+ * (every call overwrites the part it reads before reading it, nothing needs to start at zero): calls
+ * whose kernels may overlap on one GPU (different streams, or threads) race and must be ordered by the
+ * caller.
+ */
+#define HIF4_NOALLOC_SCRATCH_BYTES (64 << 20)
+int hif4_gemm_noalloc(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
+                      const uint8_t *w_codes, const uint32_t *w_meta,
+                      int64_t M, int64_t N, int64_t K,
+                      void *c, int64_t ldc, int out_dtype, void *stream);
+
+/* HIF4_NOALLOC_SCRATCH_BYTES of the built library.  Host function. */
+size_t hif4_gemm_noalloc_max_bytes(void);
 
 /* Static host string naming a status code. */
 const char *hif4_status_string(int status);

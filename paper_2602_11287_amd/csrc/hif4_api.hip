@@ -1,5 +1,7 @@
 // C ABI of libhif4: host-side argument validation, then kernel launches on the
 // caller's stream.  See include/hif4.h for the contract of every entry point.
+#include <mutex>
+
 #include "hif4_common.h"
 
 #include "../../include/hif4_compare.h"
@@ -27,7 +29,37 @@ size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 } // namespace hif4
 
+// Scratch of hif4_gemm_noalloc: device memory that belongs to the loaded library, one copy per GPU,
+// held until the process ends.  In host code the name below stands for the symbol, not for a device
+// address; the address on each device comes from hipGetSymbolAddress (noalloc_scratch()).
+static __device__ __align__(256) unsigned char scratch[HIF4_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_lock;
+void *scratch_ptr[MAX_DEVICES]; // device address of `scratch` on each GPU, once known
+
+// Address of this library's scratch array on the current device; nullptr (and *status set) on failure.
+void *noalloc_scratch(int *status)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        *status = HIF4_ERR_DEVICE;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            *status = HIF4_ERR_DEVICE;
+            return nullptr;
+        }
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
 
 inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -127,6 +159,29 @@ int hif4_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, co
     return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, nullptr, 1, M, N, K, c, nullptr, ldc, out_dtype, workspace,
                              workspace_bytes, static_cast<hipStream_t>(stream));
 }
+
+int hif4_gemm_noalloc(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
+                      const uint32_t *w_meta, int64_t M, int64_t N, int64_t K, void *c, int64_t ldc, int out_dtype, void *stream)
+{
+    // the scratch stands in for a workspace of exactly hif4_gemm_workspace_bytes() bytes: same checks, same kernels
+    const size_t need = (K % HIF4_UNIT == 0) ? hif4::gemm_workspace_bytes(a_kind, M, K) : 0;
+    if (need > (size_t)HIF4_NOALLOC_SCRATCH_BYTES) return HIF4_ERR_SCRATCH;
+    // any non-null, aligned pointer passes the argument checks; the real one is fetched only if there is work
+    alignas(16) static const unsigned char probe[16] = { 0 };
+    if (int rc = check_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, need ? probe : nullptr, need))
+        return rc;
+    if (M == 0 || N == 0) return HIF4_OK;
+    void *ws = nullptr;
+    if (need) {
+        int status = HIF4_OK;
+        ws = noalloc_scratch(&status);
+        if (!ws) return status;
+    }
+    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, nullptr, 1, M, N, K, c, nullptr, ldc, out_dtype, ws, need,
+                             static_cast<hipStream_t>(stream));
+}
+
+size_t hif4_gemm_noalloc_max_bytes(void) { return (size_t)HIF4_NOALLOC_SCRATCH_BYTES; }
 
 int hif4_gemm_to_hif4(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                       const uint32_t *w_meta, int64_t M, int64_t N, int64_t K, uint8_t *c_codes, uint32_t *c_meta,
@@ -247,6 +302,7 @@ const char *hif4_status_string(int status)
     case HIF4_ERR_UNSUPPORTED: return "unsupported enum value";
     case HIF4_ERR_WORKSPACE: return "workspace missing or too small";
     case HIF4_ERR_DEVICE: return "HIP launch error";
+    case HIF4_ERR_SCRATCH: return "call needs more scratch than the library's static buffer holds (hif4_gemm_noalloc_max_bytes)";
     default: return "unknown status";
     }
 }

@@ -14,12 +14,13 @@ LIB_PATH = os.path.join(HERE, "libhif4.so")
 
 HIF4_OK = 0
 HIF4_ERR_NULL, HIF4_ERR_SHAPE, HIF4_ERR_ALIGN = -1, -2, -3
-HIF4_ERR_UNSUPPORTED, HIF4_ERR_WORKSPACE, HIF4_ERR_DEVICE = -4, -5, -6
+HIF4_ERR_UNSUPPORTED, HIF4_ERR_WORKSPACE, HIF4_ERR_DEVICE, HIF4_ERR_SCRATCH = -4, -5, -6, -7
 HIF4_ROUND_RNE, HIF4_ROUND_RHA = 0, 1
 HIF4_A_BF16_QUANTIZE, HIF4_A_HIF4, HIF4_A_BF16_KEEP = 0, 1, 2
 HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 
 EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_gemm_to_hif4", "hif4_grouped_gemm",
+           "hif4_gemm_noalloc", "hif4_gemm_noalloc_max_bytes",
            "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version",
            "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16",
            "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm", "hif4ref_mfma_loop"]
@@ -54,6 +55,10 @@ def load():
         L.hif4_gemm_to_hif4.argtypes = [i32, vp, vp, i64, vp, vp, i64, i64, i64, vp, vp, i32, vp, sz, vp]
         L.hif4_grouped_gemm.restype = i32
         L.hif4_grouped_gemm.argtypes = [i32, vp, vp, i64, vp, vp, vp, i32, i64, i64, i64, vp, i64, i32, vp, sz, vp]
+        L.hif4_gemm_noalloc.restype = i32
+        L.hif4_gemm_noalloc.argtypes = [i32, vp, vp, i64, vp, vp, i64, i64, i64, vp, i64, i32, vp]
+        L.hif4_gemm_noalloc_max_bytes.restype = sz
+        L.hif4_gemm_noalloc_max_bytes.argtypes = []
         L.hif4_gemm_workspace_bytes.restype = sz
         L.hif4_gemm_workspace_bytes.argtypes = [i32, i64, i64]
         L.hif4_gemm_workspace_bytes_decoded_w.restype = sz
@@ -179,6 +184,25 @@ def hif4_gemm(a_kind, a, a_meta, w_codes, w_meta, out_dtype=HIF4_OUT_BF16, c=Non
     _check(load().hif4_gemm(a_kind, _ptr(a), _ptr(a_meta), lda, _ptr(w_codes), _ptr(w_meta), M, N, K, _ptr(c), ldc,
                             out_dtype, _ptr(workspace), wsz, _stream(stream)), "hif4_gemm")
     return c
+
+
+def hif4_gemm_noalloc(a_kind, a, a_meta, w_codes, w_meta, out_dtype=HIF4_OUT_BF16, c=None, stream=None):
+    """hif4_gemm on the library's own static scratch: no workspace argument, nothing allocated by the call
+    (c must be given by callers that may not allocate; it is created here only as a convenience)."""
+    M = a.shape[0]
+    K = a.shape[1] * 2 if a_kind == HIF4_A_HIF4 else a.shape[1]
+    N = w_codes.shape[0]
+    lda = _gemm_common(a_kind, a, a_meta, w_codes, M, K)
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16 if out_dtype == HIF4_OUT_BF16 else torch.float32, device=a.device)
+    ldc = c.stride(0) if M > 1 else max(c.stride(0), N)
+    _check(load().hif4_gemm_noalloc(a_kind, _ptr(a), _ptr(a_meta), lda, _ptr(w_codes), _ptr(w_meta), M, N, K, _ptr(c), ldc,
+                                    out_dtype, _stream(stream)), "hif4_gemm_noalloc")
+    return c
+
+
+def hif4_gemm_noalloc_max_bytes():
+    return int(load().hif4_gemm_noalloc_max_bytes())
 
 
 def hif4_gemm_to_hif4(a_kind, a, a_meta, w_codes, w_meta, round_mode=HIF4_ROUND_RNE, c_codes=None, c_meta=None,
