@@ -463,6 +463,14 @@ __global__ void zero_kernel(void *c, int64_t M, int64_t N, int64_t ldc, int elem
 int launch_encode(const void *x, int64_t rows, int64_t K, int64_t ldx, uint8_t *codes, uint32_t *meta, int mode,
                   hipStream_t stream);
 int launch_encode_to_cells(const void *x, int64_t rows, int64_t K, int64_t ldx, void *cells, int mode, hipStream_t stream);
+int launch_encode_to_rows(const void *x, int64_t rows, int64_t K, int64_t ldx, void *y, int mode, hipStream_t stream);
+int launch_decode(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, int64_t ldy, hipStream_t stream);
+bool fewrows_fits(int64_t M, int64_t N, int64_t K, int64_t lda);
+int launch_gemm_fewrows(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N, int64_t K,
+                        void *c, int64_t ldc, int out_dtype, hipStream_t stream);
+#ifndef HIF4_FEWROWS
+#define HIF4_FEWROWS 1
+#endif
 int launch_encode_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx, void *planes, int mode, hipStream_t stream);
 int launch_decode_cells(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *y, hipStream_t stream);
 int launch_decode_planes(const uint8_t *codes, const uint32_t *meta, int64_t rows, int64_t K, void *planes, hipStream_t stream);
@@ -563,6 +571,18 @@ static bool few_rows_prefer_k_split(int64_t M, int64_t N, int64_t K)
     return M <= 16 || (M <= 32 && weights <= ((int64_t)48 << 20)) || (M <= 64 && weights <= ((int64_t)24 << 20));
 }
 
+// 5 to 16 rows against at least 14336 columns, 17 to 32 rows against at least 28672: the kernel of
+// hif4_gemm_fewrows.hip.  Measured from HIP graphs over distinct weight matrices (us, that kernel : gemm_skinny_kernel):
+// 16 x 14336 x 4096 16.5 : 19.8, 16 x 28672 x 4096 27.5 : 31.8, 16 x 16384 x 8192 30.2 : 36.9, 8 x 28672 x 8192 48.9 : 53.2,
+// 16 x 28672 x 8192 49.8 : 62.6, 32 x 28672 x 8192 57.0 : 74.6, 32 x 28672 x 4096 31.6 : 38.3; the other way round with fewer
+// columns (its 32-column strips do not fill the chip: 16 x 11008 x 4096 17 : 16, 16 x 8192 x 28672 82 : 68, 16 x 4096 x 4096
+// 16 : 7.5), with 32 rows on 16384 columns (53 : 47) and with one or two rows (a tie: 2 x 28672 x 8192 49.0 : 48.2).
+static bool fewrows_pays(int64_t M, int64_t N, int64_t K)
+{
+    (void)K;
+    return (M >= 5 && M <= 16 && N >= 14336) || (M > 16 && M <= 32 && N >= 28672);
+}
+
 // Rows of A per workgroup of that kernel for a dense call, 0: not its case.  Up to 192 rows: one tile.
 // Beyond, every m-tile expands W again, which pays only while the whole call is small: at most
 // HIF4_COLWAVE_DENSE_STRIPS (32-column strip, 128-row tile) pairs, i.e. one round of two waves per SIMD
@@ -639,6 +659,18 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             hipLaunchKernelGGL(zero_kernel, grid, block, 0, stream, c, M, N, ldc, out_dtype == HIF4_OUT_F32 ? 4 : 2);
         }
         return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+    }
+    if (HIF4_FEWROWS && !offs && !emit && fewrows_pays(M, N, K) && fewrows_fits(M, N, K, a_kind == HIF4_A_BF16_KEEP ? lda : K)) {
+        // a few rows against a wide weight matrix: the kernel that streams W once and applies the unit scales to the
+        // units' partial sums (hif4_gemm_fewrows.hip); HiF4 activations enter as their exact BF16 values, dense rows
+        // in the workspace
+        if (a_kind == HIF4_A_BF16_KEEP) return launch_gemm_fewrows(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+        if (a_kind == HIF4_A_BF16_QUANTIZE) {
+            if (int rc = launch_encode_to_rows(a, M, K, lda, workspace, HIF4_ROUND_RNE, stream)) return rc;
+        } else {
+            if (int rc = launch_decode(static_cast<const uint8_t *>(a), a_meta, M, K, workspace, K, stream)) return rc;
+        }
+        return launch_gemm_fewrows(workspace, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
     }
     if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64 && !emit &&
         (few_rows_prefer_k_split(M, N, K) || !colwave_fits(M, N, K) || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 15) != 0 ||

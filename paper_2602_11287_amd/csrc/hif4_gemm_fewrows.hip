@@ -1,0 +1,444 @@
+// HiF4 GEMM for at most 32 rows of A (token generation: the "decode" shape): C[M][N] = A[M][K] * W[N][K]^T
+// with W packed HiF4 and A BF16 rows (plain activations, or the exact BF16 values of HiF4 activations).
+// The work is streaming W from HBM once, 0.5625 bytes per weight, and turning it into matrix operands;
+// every 64-wide K step of an output is the unit dot product of Eq. 4 of the HiF4 paper (Section III-B),
+// in the factored form that equation prints: the sum over the unit's 64 products of S1P2 integers and
+// micro-exponent powers of two first, one multiplication by the unit scale E6M2 after it.
+//
+// How a weight becomes an operand (Eq. 2, Section II-A, without its E6M2 factor): the 3-bit magnitude of
+// four codes goes through one v_perm_b32 with the FP8 (E4M3) patterns of 0..7 as its byte table, the
+// sign bits are OR-ed in, and v_cvt_scalef32_pk_bf16_fp8 turns two such bytes into two BF16 values times
+// 2^(E1_8 + E1_16), the power of two riding in the exponent of its scale operand (zero stays zero, which
+// a table of BF16 patterns with the exponent added afterwards would not give).  That is about 2.3 vector
+// instructions per weight instead of 4.6 for the expansion that carries the E6M2 factor in every weight.
+// The factor (4 + M) 2^(E - 50) of the unit, which no 8-bit format can carry next to the code (six
+// significant bits), is applied to the unit's partial sums instead: every unit starts from a zero
+// accumulator, and 8 fused multiply-adds per lane and 16 rows add its scaled sums to the running result.  With few rows that is cheap; from about 128 rows
+// on it would cost what it saves, which is why the kernels for more rows keep the full expansion.
+//
+// Shape: a wave owns 32 output columns (two column groups of 16 for v_mfma_f32_16x16x32_bf16, whose K of
+// 32 is half a unit: lane (n, q) = (lane % 16, lane / 16) supplies group 4 hs + q of the unit's 8 groups of 8
+// from both operands in half step hs) over one of KS parts of K; a workgroup is NWC such column strips
+// times KS parts.
+// Everything comes in through LDS by direct global -> LDS loads, D steps of two units deep, so that the
+// bytes in flight per CU (what hides HBM latency) are bounded by LDS, not by registers:
+//   W codes  per wave and step: 32 rows x 64 bytes, four adjacent lanes per row, so every request
+//            covers whole 64-byte runs of a row (two steps use up a 128-byte line); the 16-byte chunks
+//            of a row are stored XOR-swizzled so that the operand reads are spread over the banks;
+//   W meta   per wave and 8 steps: 32 rows x 16 words (64-byte runs again: a request per row and step for
+//            8 bytes would double the number of requests, and requests in flight are what a CU runs out of);
+//   A        per K part and step: 16 cells of 8 values x RM rows, [cell][row], shared by the part's
+//            NWC waves (plain 16-byte pieces of the rows of A: the K order inside a cell is natural here).
+// One barrier per step (two units).  The partial sums of the K parts meet in LDS at the end, in a
+// fixed order.  All global loads of the loop are LDS-writing loads in inline assembly, PER per wave and step
+// plus two of metadata every eighth step, issued at least eight steps before their use; loads land in
+// the order they were issued, so s_waitcnt vmcnt((D - 2) PER) before step i leaves only loads younger than
+// those of step i in flight (the compiler never sees them, and the loop contains no other vector memory
+// instruction).  K must be a multiple of 256 (metadata rows then start on 16-byte boundaries).
+#include "hif4_common.h"
+
+namespace hif4 {
+
+__device__ __forceinline__ void fr_load_to_lds_16(uint64_t base, uint32_t off, uint32_t lds_byte)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory");
+}
+__device__ __forceinline__ void fr_load_to_lds_4(uint64_t base, uint32_t off, uint32_t lds_byte)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_byte), "v"(off), "s"(base) : "memory");
+}
+__device__ __forceinline__ uint64_t fr_uniform(uint64_t v) // a wave-uniform value, in scalar registers
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v), hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+struct FewRowsArgs {
+    const void *a; // BF16 [M][lda], natural element order
+    int64_t lda;
+    const uint8_t *w_codes; // [N][K/2]
+    const uint32_t *w_meta; // [N][K/64]
+    void *c;
+    int64_t ldc;
+    int M, N, K;
+    int out_f32;
+};
+
+template <int RM, int NWC, int KS>
+struct FewRowsShape {
+    static constexpr int NW = NWC * KS;
+    static constexpr size_t slot_bytes = (size_t)KS * 16 * RM * 16 + (size_t)NW * 2048; // A of every K part, codes of every wave
+    static constexpr size_t meta_bytes = (size_t)NW * 2 * 2048;                          // two blocks of 16 units x 32 rows per wave
+    // workgroups of 4 waves leave room for a second one on the CU where three steps fit half the LDS
+    static constexpr size_t budget = ((NW == 4 && 3 * slot_bytes + meta_bytes <= 80 * 1024) ? 80 * 1024 : 160 * 1024) - meta_bytes;
+    static constexpr int D = budget / slot_bytes >= 6 ? 6 : (int)(budget / slot_bytes);
+    static constexpr bool fits = D >= 3;
+    static constexpr size_t lds_bytes = D * slot_bytes + meta_bytes;
+};
+
+// E4M3 patterns of the integers 0..7 (bias 7: 1 = 0x38, 2 = 0x40, 3 = 0x44, ...), the byte table of v_perm_b32
+constexpr uint32_t FP8_OF_0123 = 0x44403800u, FP8_OF_4567 = 0x4E4C4A48u;
+
+template <int RM, int NWC, int KS>
+__global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs g)
+{
+    using Shape = FewRowsShape<RM, NWC, KS>;
+    constexpr int NW = Shape::NW, D = Shape::D;
+    constexpr int RB = RM / 16;                   // 16-row blocks
+    constexpr int A_INSTR = RM / 4;               // 64-cell loads of A per K part and step (16 cells x RM rows)
+    constexpr int IA = (KS * A_INSTR + NW - 1) / NW; // of them per wave
+    constexpr int PER = IA + 2;                   // LDS-writing loads per wave and step: A, two of codes
+    constexpr int A_PART = 16 * RM;               // cells of A per K part and slot
+    constexpr int CODES0 = KS * A_PART;           // first cell of the codes of a slot
+    constexpr int SLOT = CODES0 + NW * 128;       // cells per slot
+    constexpr int META0 = D * SLOT;               // first cell of the metadata ring: [wave][2 blocks][32 rows][4 cells]
+    static_assert(Shape::fits && SLOT * 16 == Shape::slot_bytes, "LDS plan");
+    static_assert((D - 2) * PER <= 63, "the wait count is a 6-bit field");
+    static_assert(RM == 16 || RM == 32, "rows of a tile");
+    extern __shared__ uint4 lds[];
+
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    const int cw = wave % NWC, kw = wave / NWC; // column strip and K part of this wave
+    const int col0 = ((int)blockIdx.x * NWC + cw) * 32;
+    const int upr = g.K / 64, np = (upr + 1) / 2; // units per row, pairs of units (steps) in K
+    const int ppp = (np + KS - 1) / KS;           // steps per K part; part kw takes pairs [kw ppp, (kw + 1) ppp)
+    const int p0 = kw * ppp;
+    const bool odd_tail = (upr & 1) != 0;         // the last pair has one unit only
+
+    // ---- load plan.  Every address is a 64-bit scalar base that moves with the step plus a 32-bit byte
+    // offset per lane (the host keeps the operands below 4 GiB).  Loads past the end of K repeat the
+    // last pair, and the missing second unit of an odd last pair repeats its first: never used, in bounds.
+    // W codes, load t of 2: lane -> weight row 16 t + lane / 4, position lane % 4 of the row's four
+    // 16-byte chunks, which holds chunk (position ^ swizzle(row)); chunk c = half c % 2 of unit c / 2.
+    uint32_t wc_off[2], wc_off_tail[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int row = 16 * t + lane / 4, c = (lane % 4) ^ ((row >> 2) & 3);
+        int col = col0 + row;
+        col = col < g.N ? col : g.N - 1;
+        wc_off[t] = (uint32_t)col * (uint32_t)(g.K / 2) + 16u * c;
+        wc_off_tail[t] = (uint32_t)col * (uint32_t)(g.K / 2) + 16u * (c & 1);
+    }
+    // W metadata, a block of 16 units at a time (blocks aligned to multiples of 16 units of the row), load t of 2:
+    // lane -> weight row 16 t + lane / 4, units 4 (lane % 4) .. + 3 of the block; chunks past the end of the
+    // row repeat its last four units
+    uint32_t wm_row_off[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        int col = col0 + 16 * t + lane / 4;
+        col = col < g.N ? col : g.N - 1;
+        wm_row_off[t] = (uint32_t)col * (uint32_t)upr * 4u;
+    }
+    // A: load id = wave IA + i covers, for K part id / A_INSTR, the 64 cells (j, row) with
+    // j = (id % A_INSTR) (64 / RM) + lane / RM, row = lane % RM; rows past M repeat the last row
+    uint32_t a_row_off[IA], a_pair0[IA], a_tail_adj[IA], a_dst[IA];
+#pragma unroll
+    for (int i = 0; i < IA; ++i) {
+        int id = wave * IA + i;
+        id = id < KS * A_INSTR ? id : KS * A_INSTR - 1;
+        const int part = id / A_INSTR, ai = id % A_INSTR;
+        const int j = ai * (64 / RM) + lane / RM;
+        int row = lane % RM;
+        row = row < g.M ? row : g.M - 1;
+        a_row_off[i] = (uint32_t)row * (uint32_t)g.lda * 2u + 16u * j;
+        a_pair0[i] = (uint32_t)(part * ppp);
+        a_tail_adj[i] = j >= 8 ? 128u : 0u;
+        a_dst[i] = (uint32_t)__builtin_amdgcn_readfirstlane((part * A_PART + ai * 64) * 16);
+    }
+    auto lds_byte_of = [](const void *p) { return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p; };
+    const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds));
+    const uint64_t wc_ptr = fr_uniform((uint64_t)(uintptr_t)g.w_codes), wm_ptr = fr_uniform((uint64_t)(uintptr_t)g.w_meta);
+    const uint64_t a_ptr = fr_uniform((uint64_t)(uintptr_t)g.a);
+
+    // the loads of step `it` (of every K part, this wave's share of A; of this wave's part, its W) into slot `slot`
+    auto issue = [&](int it, int slot) {
+        const uint32_t sbase = lds0 + (uint32_t)(slot * SLOT * 16);
+#pragma unroll
+        for (int i = 0; i < IA; ++i) {
+            uint32_t p = a_pair0[i] + (uint32_t)it;
+            p = p < (uint32_t)np ? p : (uint32_t)(np - 1);
+            uint32_t off = a_row_off[i] + p * 256u;
+            if (odd_tail) off -= (2 * p + 1 >= (uint32_t)upr) ? a_tail_adj[i] : 0u;
+            fr_load_to_lds_16(a_ptr, off, sbase + a_dst[i]);
+        }
+        int pw = p0 + it;
+        pw = pw < np ? pw : np - 1;
+        const bool tail = 2 * pw + 1 >= upr; // wave-uniform
+        const uint32_t cdst = sbase + (uint32_t)((CODES0 + wave * 128) * 16);
+        fr_load_to_lds_16(wc_ptr + (uint64_t)pw * 64, tail ? wc_off_tail[0] : wc_off[0], cdst);
+        fr_load_to_lds_16(wc_ptr + (uint64_t)pw * 64, tail ? wc_off_tail[1] : wc_off[1], cdst + 1024);
+    };
+    // the metadata of block `blk` (units 16 blk .. 16 blk + 15 of this wave's rows) into its ring slot blk % 2
+    auto issue_meta = [&](int blk) {
+        int u4 = 16 * blk + 4 * (lane % 4);
+        u4 = u4 < upr - 4 ? u4 : upr - 4;
+        const uint32_t dst = lds0 + (uint32_t)((META0 + (wave * 2 + (blk & 1)) * 128) * 16);
+        fr_load_to_lds_16(wm_ptr, wm_row_off[0] + 4u * (uint32_t)u4, dst);
+        fr_load_to_lds_16(wm_ptr, wm_row_off[1] + 4u * (uint32_t)u4, dst + 1024);
+    };
+
+    // results: acc[cg][rb] is the 16 x 16 tile of column group cg (columns 16 cg .. + 15 of the strip) and row
+    // block rb; lane (n, q) = (lane % 16, lane / 16) holds its column n, rows 4 q .. 4 q + 3
+    f32x4_t acc[2][RB];
+#pragma unroll
+    for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+        for (int i = 0; i < RB; ++i) acc[cg][i] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
+
+    // ---- one dword of codes (group of 8 number j = 4 hs + q of its unit) -> one operand of 8 BF16: S1P2
+    // magnitude times sign times 2^(E1_8 + E1_16), natural element order.  m8q, m16q: the unit's metadata word
+    // shifted so that bit 4 hs of m8q is E1_8[j] and bits 8 hs, 8 hs + 1 of m16q are E1_16[2 j], E1_16[2 j + 1]
+    // (one bit-field extract and one shift-add per power of two).
+    auto expand_dword = [&](uint32_t c, uint32_t m8q, uint32_t m16q, int hs) {
+        const uint32_t one8 = (__builtin_amdgcn_ubfe(m8q, 4 * hs, 1) << 23) + 0x3F800000u;      // 2^E1_8 as an fp32 pattern
+        const float sa = u2f((__builtin_amdgcn_ubfe(m16q, 8 * hs, 1) << 23) + one8);             // ... times 2^E1_16, elements 0..3
+        const float sb = u2f((__builtin_amdgcn_ubfe(m16q, 8 * hs + 1, 1) << 23) + one8);         // elements 4..7
+        const uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u;                         // magnitudes, one per byte
+        const uint32_t f8lo = __builtin_amdgcn_perm(FP8_OF_4567, FP8_OF_0123, lo) | ((c << 4) & 0x80808080u);
+        const uint32_t f8hi = __builtin_amdgcn_perm(FP8_OF_4567, FP8_OF_0123, hi) | (c & 0x80808080u);
+        uint4 b;
+        b.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(f8lo, sa, false));
+        b.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(f8lo, sa, true));
+        b.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(f8hi, sb, false));
+        b.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(f8hi, sb, true));
+        return b;
+    };
+    // fp32 pattern of the unit scale (4 + M) 2^(E - 48 - 4) (codes count quarters, E6M2 = (1 + M / 4) 2^(E - 48)); NaN unit: NaN
+    auto unit_scale = [](uint32_t m) {
+        const uint32_t s = ((((m >> 2) & 0x3Fu) + (127u - 50u)) << 23) | ((m & 3u) << 21);
+        return u2f((m & 0xFFu) == 0xFFu ? 0x7FC00000u : s);
+    };
+
+    // Matrix instruction: v_mfma_f32_16x16x32_bf16, half a unit of K each.  Lane (n, q) = (lane % 16, lane / 16)
+    // supplies, for half step hs of a unit, group of 8 number 4 hs + q of both operands: of row n of a 16-row
+    // block of A, and of weight rows n and 16 + n of the strip (two column groups).  Codes live in LDS as
+    // cell(row, chunk) = 4 row + (chunk ^ swizzle(row)) (see the load plan): the 64 dword reads of a wave
+    // fall on 64 different banks.
+    const int n16 = lane % 16, q = lane / 16;
+    const int wswz = (n16 >> 2) & 3; // swizzle of rows n and 16 + n alike
+    const f32x4_t zero4 = { 0.f, 0.f, 0.f, 0.f };
+
+    // matrix work of the pair in slot `slot`.  Every LDS read of the step is requested up front, so that the
+    // read latency is covered by arithmetic the wave has anyway.
+    auto compute = [&](int slot, int pair) {
+        if (pair >= np) return; // wave-uniform: a K part past the end of K
+        const uint4 *sl = lds + slot * SLOT;
+        const int u0 = 2 * pair; // the pair's first unit; both units lie in metadata block u0 / 16
+        const bool two = u0 + 1 < upr; // wave-uniform
+        const uint32_t *mring = reinterpret_cast<const uint32_t *>(lds + META0 + (wave * 2 + ((u0 >> 4) & 1)) * 128) + (u0 & 15);
+        uint2 mm[2];       // metadata of the pair's units, per column group
+        uint32_t cd[2][2][2]; // codes dword [column group][unit][half step]
+        const uint32_t *cbase = reinterpret_cast<const uint32_t *>(sl + CODES0 + wave * 128) + q;
+#pragma unroll
+        for (int cg = 0; cg < 2; ++cg) {
+            mm[cg] = *reinterpret_cast<const uint2 *>(mring + (16 * cg + n16) * 16);
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu)
+#pragma unroll
+                for (int hs = 0; hs < 2; ++hs) cd[cg][uu][hs] = cbase[(64 * cg + 4 * n16 + ((2 * uu + hs) ^ wswz)) * 4];
+        }
+        uint4 av[2][2][RB]; // A operands [unit][half step][row block]
+#pragma unroll
+        for (int uu = 0; uu < 2; ++uu)
+#pragma unroll
+            for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+                for (int i = 0; i < RB; ++i) av[uu][hs][i] = sl[kw * A_PART + (uu * 8 + 4 * hs + q) * RM + i * 16 + n16];
+        __builtin_amdgcn_sched_barrier(0);
+        f32x4_t part[2][2][RB]; // the units' own sums [unit][column group][row block]
+#pragma unroll
+        for (int uu = 0; uu < 2; ++uu) {
+            if (uu == 1 && !two) break;
+            uint32_t m8q[2], m16q[2];
+#pragma unroll
+            for (int cg = 0; cg < 2; ++cg) {
+                const uint32_t m = uu == 0 ? mm[cg].x : mm[cg].y;
+                m8q[cg] = m >> (8 + q);
+                m16q[cg] = m >> (16 + 2 * q);
+            }
+#pragma unroll
+            for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+                for (int cg = 0; cg < 2; ++cg) {
+                    const uint4 b = expand_dword(cd[cg][uu][hs], m8q[cg], m16q[cg], hs);
+#pragma unroll
+                    for (int i = 0; i < RB; ++i)
+                        part[uu][cg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[uu][hs][i]), __builtin_bit_cast(bf16x8_t, b),
+                                                                                   hs == 0 ? zero4 : part[uu][cg][i], 0, 0, 0);
+                }
+        }
+        // the units' sums times their E6M2 factors (the first unit's have long left the matrix pipeline)
+#pragma unroll
+        for (int uu = 0; uu < 2; ++uu) {
+            if (uu == 1 && !two) break;
+#pragma unroll
+            for (int cg = 0; cg < 2; ++cg) {
+                const float sc = unit_scale(uu == 0 ? mm[cg].x : mm[cg].y);
+#pragma unroll
+                for (int i = 0; i < RB; ++i)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[cg][i][r] = __builtin_fmaf(part[uu][cg][i][r], sc, acc[cg][i][r]);
+            }
+        }
+    };
+
+    // ---- pipeline: step `it` is issued D - 1 steps ahead of its matrix work; the two metadata blocks the part
+    // starts in come first, block b + 1 follows when the part enters block b
+    int blk = (2 * p0) >> 4;
+    issue_meta(blk);
+    issue_meta(blk + 1);
+#pragma unroll
+    for (int it = 0; it < D - 1; ++it) issue(it, it);
+    int slot = 0;
+    for (int it = 0; it < ppp; ++it) {
+        // the loads of step `it` have landed once only younger ones (those of D - 2 steps, at least) are in flight
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"((D - 2) * PER) : "memory");
+        __syncthreads(); // every wave's share of A(it) is there, and every wave is through with the slot refilled next
+        const int nblk = (2 * (p0 + it)) >> 4;
+        if (nblk != blk) { // wave-uniform: block nblk - 1 is used up, its ring slot takes block nblk + 1
+            blk = nblk;
+            issue_meta(blk + 1);
+        }
+        issue(it + D - 1, slot == 0 ? D - 1 : slot - 1);
+        compute(slot, p0 + it);
+        slot = slot + 1 == D ? 0 : slot + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // no load may outlive the workgroup's LDS
+
+    // ---- the partial sums of K parts 1 .. KS - 1 go through LDS to part 0, lane for lane, in a fixed order
+    if constexpr (KS > 1) {
+        static_assert((size_t)(KS - 1) * NWC * 2 * RB * 1024 <= Shape::lds_bytes, "partial sums fit the buffers");
+        f32x4_t *red = reinterpret_cast<f32x4_t *>(lds); // [kw - 1][cw][column group][row block][lane]
+        __syncthreads();
+        if (kw > 0) {
+            f32x4_t *dst = red + (size_t)((kw - 1) * NWC + cw) * 2 * RB * 64 + lane;
+#pragma unroll
+            for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+                for (int i = 0; i < RB; ++i) dst[(cg * RB + i) * 64] = acc[cg][i];
+        }
+        __syncthreads();
+        if (kw > 0) return;
+#pragma unroll
+        for (int p = 0; p < KS - 1; ++p) {
+            const f32x4_t *src = red + (size_t)(p * NWC + cw) * 2 * RB * 64 + lane;
+#pragma unroll
+            for (int cg = 0; cg < 2; ++cg)
+#pragma unroll
+                for (int i = 0; i < RB; ++i) acc[cg][i] += src[(cg * RB + i) * 64];
+        }
+    }
+
+    // ---- epilogue: lane (n, q) holds column n of each 16 x 16 tile, rows 4 q + r
+#pragma unroll
+    for (int cg = 0; cg < 2; ++cg) {
+        const int col = col0 + 16 * cg + n16;
+        if (col >= g.N) continue;
+#pragma unroll
+        for (int i = 0; i < RB; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = i * 16 + 4 * q + r;
+                if (row < g.M) {
+                    const float v = acc[cg][i][r];
+                    if (g.out_f32) static_cast<float *>(g.c)[(int64_t)row * g.ldc + col] = v;
+                    else static_cast<uint16_t *>(g.c)[(int64_t)row * g.ldc + col] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
+                }
+            }
+    }
+}
+
+// ------------------------------------------------------------------ launch
+
+namespace {
+
+struct FewRowsChoice {
+    int nwc, ks;
+};
+
+// Which (column strips, K parts) a workgroup takes.  Time is modelled as rounds of workgroups over the
+// chip's 256 CUs times the K range of one wave; among equals, more column strips per workgroup (they
+// share A).  Only shapes whose LDS plan fits are offered (the table mirrors FewRowsShape).
+template <int RM>
+FewRowsChoice fewrows_choose(int64_t N, int64_t K)
+{
+    const int64_t strips = (N + 31) / 32, np = (K / 64 + 1) / 2;
+    const FewRowsChoice cand[] = { { 4, 2 }, { 2, 4 }, { 1, 8 }, { 8, 1 }, { 2, 2 }, { 1, 4 }, { 4, 1 } };
+    FewRowsChoice best = { 8, 1 };
+    double best_t = 1e300;
+    for (const FewRowsChoice &c : cand) {
+        const int nw = c.nwc * c.ks;
+        const size_t slot = (size_t)c.ks * 16 * RM * 16 + (size_t)nw * 2048, meta = (size_t)nw * 4096;
+        const bool half_lds = nw == 4 && 3 * slot + meta <= 80 * 1024;
+        const size_t budget = (half_lds ? 80 * 1024 : 160 * 1024) - meta;
+        if (budget / slot < 3) continue;
+        const int64_t per_cu = half_lds ? 2 : 1;
+        const int64_t wgs = (strips + c.nwc - 1) / c.nwc;
+        const int64_t rounds = (wgs + 256 * per_cu - 1) / (256 * per_cu);
+        const int64_t steps = (np + c.ks - 1) / c.ks;
+        const double t = (double)rounds * (double)(steps + 3); // + 3: filling the pipeline, the final reduction
+        if (t < best_t) best = c, best_t = t;
+    }
+    return best;
+}
+
+template <int RM, int NWC, int KS>
+int launch_fewrows_t(const FewRowsArgs &g, hipStream_t stream)
+{
+    using Shape = FewRowsShape<RM, NWC, KS>;
+    if constexpr (!Shape::fits) {
+        return HIF4_ERR_UNSUPPORTED;
+    } else {
+        auto k = gemm_fewrows_kernel<RM, NWC, KS>;
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)Shape::lds_bytes) != hipSuccess)
+            return HIF4_ERR_DEVICE;
+        const dim3 grid((unsigned)((g.N + 32 * NWC - 1) / (32 * NWC))), block(64 * NWC * KS);
+        hipLaunchKernelGGL(k, grid, block, Shape::lds_bytes, stream, g);
+        return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+    }
+}
+
+template <int RM>
+int launch_fewrows_rm(const FewRowsArgs &g, hipStream_t stream)
+{
+    const FewRowsChoice c = fewrows_choose<RM>(g.N, g.K);
+#define HIF4_FR_CASE(W, S) if (c.nwc == W && c.ks == S) return launch_fewrows_t<RM, W, S>(g, stream)
+    HIF4_FR_CASE(4, 2);
+    HIF4_FR_CASE(2, 4);
+    HIF4_FR_CASE(1, 8);
+    HIF4_FR_CASE(2, 2);
+    HIF4_FR_CASE(1, 4);
+    HIF4_FR_CASE(4, 1);
+#undef HIF4_FR_CASE
+    return launch_fewrows_t<RM, 8, 1>(g, stream);
+}
+
+} // namespace
+
+// The kernel addresses each operand as a scalar base plus a 32-bit byte offset per lane.
+bool fewrows_fits(int64_t M, int64_t N, int64_t K, int64_t lda)
+{
+    return M >= 1 && M <= 32 && K >= 256 && K % 256 == 0 && N * (K / 2) < ((int64_t)1 << 32) && M * lda * 2 < ((int64_t)1 << 32);
+}
+
+// a: BF16 rows in natural element order (row stride lda elements, 16-byte aligned rows).
+int launch_gemm_fewrows(const void *a, int64_t lda, const uint8_t *w_codes, const uint32_t *w_meta, int64_t M, int64_t N, int64_t K,
+                        void *c, int64_t ldc, int out_dtype, hipStream_t stream)
+{
+    FewRowsArgs g;
+    g.a = a;
+    g.lda = lda;
+    g.w_codes = w_codes;
+    g.w_meta = w_meta;
+    g.c = c;
+    g.ldc = ldc;
+    g.M = (int)M;
+    g.N = (int)N;
+    g.K = (int)K;
+    g.out_f32 = out_dtype == HIF4_OUT_F32;
+    if (M <= 16) return launch_fewrows_rm<16>(g, stream);
+    return launch_fewrows_rm<32>(g, stream);
+}
+
+} // namespace hif4

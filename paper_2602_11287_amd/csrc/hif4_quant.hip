@@ -104,8 +104,9 @@ __global__ __launch_bounds__(256) void encode_kernel(const void *__restrict__ x,
 // Quantise-dequantise in one pass for the GEMM that converts its activations itself: the same
 // loads and the same Algorithm 1 as encode_kernel, but what is stored is the exact BF16 value of
 // every element of the resulting unit (Eq. 2), 8 per 16-byte cell in the cell order of the tile
-// GEMM, dense rows.  The packed unit never goes to memory.
-template <int MODE, bool CONTIG>
+// GEMM, dense rows.  The packed unit never goes to memory.  NATURAL: every group of 8 in element order
+// instead (plain decoded rows, what hif4_dequantize would write).
+template <int MODE, bool CONTIG, bool NATURAL = false>
 __global__ __launch_bounds__(256) void encode_to_cells_kernel(const void *__restrict__ x, int64_t units, int64_t upr,
                                                               int64_t ldx, uint4 *__restrict__ cells)
 {
@@ -129,7 +130,8 @@ __global__ __launch_bounds__(256) void encode_to_cells_kernel(const void *__rest
     const uint32_t sbase = unit_scale_bits(m);
     if (live) {
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) cells[unit * 8 + c * LPU + l] = expand_chunk(out[c], m, sbase, c * LPU + l);
+        for (int c = 0; c < NCH; ++c)
+            cells[unit * 8 + c * LPU + l] = NATURAL ? decode_chunk(out[c], m, c * LPU + l) : expand_chunk(out[c], m, sbase, c * LPU + l);
     }
 }
 
@@ -171,6 +173,18 @@ int launch_encode_to_planes(const void *x, int64_t rows, int64_t K, int64_t ldx,
     uint4 *y = static_cast<uint4 *>(planes);
     if (mode == HIF4_ROUND_RNE) hipLaunchKernelGGL(encode_to_planes_kernel<HIF4_ROUND_RNE>, grid, block, 0, stream, x, rows, ldx, y);
     else hipLaunchKernelGGL(encode_to_planes_kernel<HIF4_ROUND_RHA>, grid, block, 0, stream, x, rows, ldx, y);
+    return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+}
+
+// Quantise and decode in one pass into dense rows of BF16 in natural element order (row stride K).
+int launch_encode_to_rows(const void *x, int64_t rows, int64_t K, int64_t ldx, void *y, int mode, hipStream_t stream)
+{
+    const int64_t upr = K / 64, units = rows * upr;
+    if (units == 0) return HIF4_OK;
+    const dim3 grid((unsigned)((units + 63) / 64)), block(256);
+    uint4 *out = static_cast<uint4 *>(y);
+    if (mode == HIF4_ROUND_RNE) hipLaunchKernelGGL((encode_to_cells_kernel<HIF4_ROUND_RNE, false, true>), grid, block, 0, stream, x, units, upr, ldx, out);
+    else hipLaunchKernelGGL((encode_to_cells_kernel<HIF4_ROUND_RHA, false, true>), grid, block, 0, stream, x, units, upr, ldx, out);
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 

@@ -786,3 +786,75 @@ def test_gemm_weight_only_few_rows_optional_workspace(h, oracle):
     torch.cuda.synchronize()
     assert rel_fro(c_ws.cpu().numpy().astype(np.float64), want) <= TOL
     assert rel_fro(c_no.cpu().numpy().astype(np.float64), want) <= TOL
+
+
+# ---- the kernel for a few rows against a wide weight matrix (5..16 rows from 14336 columns, 17..32 rows from 28672):
+# unit scales applied to the units' partial sums, weights expanded through the FP8 byte table.  Ragged column edges,
+# one, odd and uneven numbers of pairs of units per K part, all three kinds of A.
+
+FEWROW_SHAPES = [(5, 14336, 256), (16, 14353, 768), (9, 14340, 1280), (16, 14336, 4096), (13, 16400, 2304),
+                 (17, 28672, 256), (32, 28700, 512), (20, 28673, 768), (32, 28672, 1792)]
+
+
+@pytest.mark.parametrize("M,N,K", FEWROW_SHAPES)
+def test_gemm_few_rows_wide_weights(h, oracle, M, N, K):
+    print(f"few-row gemm parity M={M} N={N} K={K}", flush=True)
+    ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 900 + M + N + K)
+    wdec = oracle.dequantize(wc, wm)
+    wcd, wmd = dev_packed(wc, wm)
+    key = lambda b: np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    for a_kind in (h.HIF4_A_BF16_KEEP, h.HIF4_A_HIF4, h.HIF4_A_BF16_QUANTIZE):
+        a_bits = ab if a_kind == h.HIF4_A_BF16_KEEP else oracle.dequantize(ac, am)
+        want = oracle.gemm_f64(a_bits, wdec)
+        if a_kind == h.HIF4_A_HIF4:
+            a_dev, a_meta = dev_packed(ac, am)
+        else:
+            a_dev, a_meta = synth.from_bits(ab).cuda(), None
+        c32 = h.hif4_gemm(a_kind, a_dev, a_meta, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+        c16 = h.hif4_gemm(a_kind, a_dev, a_meta, wcd, wmd, out_dtype=h.HIF4_OUT_BF16)
+        c32b = h.hif4_gemm(a_kind, a_dev, a_meta, wcd, wmd, out_dtype=h.HIF4_OUT_F32)
+        torch.cuda.synchronize()
+        got = c32.cpu().numpy().astype(np.float64)
+        assert rel_fro(got, want) <= TOL, (a_kind, rel_fro(got, want))
+        assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max() + 1e-30
+        assert torch.equal(c32, c32b), "same launch twice gives the same bits"
+        # BF16 output: within one BF16 ulp of the rounded oracle value, except where the sum cancels to (nearly) nothing:
+        # there the fp32 accumulation error, bounded by 1e-5 of the largest result as checked above, exceeds the ulp
+        gb = synth.bits(c16.cpu()).astype(np.int32)
+        wb = synth.bits(torch.from_numpy(want).to(torch.bfloat16)).astype(np.int32)
+        g16 = c16.float().cpu().numpy().astype(np.float64)
+        close = (np.abs(key(gb) - key(wb)) <= 1) | (np.abs(g16 - want) <= 1e-5 * np.abs(want).max())
+        assert close.all(), (a_kind, int((~close).sum()))
+        assert (np.abs(key(gb) - key(wb)) <= 1).mean() > 0.9999
+
+
+def test_gemm_few_rows_every_metadata_pattern_and_nan(h, oracle):
+    """Packed weights drawn directly: every micro-exponent pattern, scales many binades apart, zero codes of both signs,
+    a NaN unit; strided A and C."""
+    rng = np.random.default_rng(55)
+    M, N, K = 11, 14400, 512
+    wc = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    wc[rng.random((N, K // 2)) < 0.1] &= 0x88            # zero magnitudes, signs kept
+    wm = (rng.integers(0, 2 ** 24, (N, K // 64)).astype(np.uint32) << 8) | rng.integers(100, 220, (N, K // 64)).astype(np.uint32)
+    wm[7, 2] |= 0xFF
+    wm[14399, 7] |= 0xFF
+    a = rng.standard_normal((M, K)) * np.exp(rng.uniform(-4, 4, (M, 1)))
+    ab = synth.bits(torch.from_numpy(a).to(torch.bfloat16))
+    want = oracle.gemm_f64(ab, oracle.dequantize(wc, wm))
+    abuf = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    abuf[:, :K] = synth.from_bits(ab).cuda()
+    cbuf = torch.full((M, N + 3), -1.0, dtype=torch.float32, device="cuda")
+    h.hif4_gemm(h.HIF4_A_BF16_KEEP, abuf[:, :K], None, *dev_packed(wc, wm), out_dtype=h.HIF4_OUT_F32, c=cbuf[:, :N])
+    torch.cuda.synchronize()
+    got = cbuf[:, :N].cpu().numpy().astype(np.float64)
+    assert (cbuf[:, N:] == -1.0).all()
+    nan_want = np.isnan(want)
+    assert nan_want[:, 7].all() and nan_want[:, 14399].all() and nan_want.sum() == 2 * M
+    assert (np.isnan(got) == nan_want).all()
+    ok = ~nan_want
+    for r in range(M):   # each row against its own norm: rows and columns differ by many binades
+        assert np.linalg.norm(got[r][ok[r]] - want[r][ok[r]]) <= TOL * np.linalg.norm(want[r][ok[r]])
+    # column by column too (the unit scales are per column): a sample of columns
+    for col in rng.integers(0, N, 400):
+        if ok[:, col].all():
+            assert np.linalg.norm(got[:, col] - want[:, col]) <= TOL * np.linalg.norm(want[:, col]) + 1e-30
