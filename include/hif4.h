@@ -171,6 +171,21 @@ int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t
                       void *c, int64_t ldc, int out_dtype,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * hif4_grouped_gemm whose result leaves as HiF4 (mixture-of-experts layers feed the next linear layer, whose input
+ * the paper converts before its matrix product, Section IV): every row of C that an expert owns, rounded to BF16 as
+ * HIF4_OUT_BF16 would round it, is converted by Algorithm 1 (Section II-B) with units of 64 consecutive columns.
+ * The planes equal hif4_quantize(result of hif4_grouped_gemm with HIF4_OUT_BF16 and the same workspace size) bit
+ * for bit.  Rows that no expert owns are not written.
+ *   c_codes  out  uint8 [total_rows][N/2], c_meta out uint32 [total_rows][N/64];  N a multiple of 64
+ * Other arguments, workspace and errors as hif4_grouped_gemm.
+ */
+int hif4_grouped_gemm_to_hif4(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda,
+                              const uint8_t *w_codes, const uint32_t *w_meta,
+                              const int32_t *offs, int E, int64_t total_rows, int64_t N, int64_t K,
+                              uint8_t *c_codes, uint32_t *c_meta, int round_mode,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
 /* Scratch bytes hif4_gemm / hif4_grouped_gemm need for M (or total_rows) rows of A. Host function. */
 size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K);
 

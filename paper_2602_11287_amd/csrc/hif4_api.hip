@@ -213,6 +213,21 @@ int hif4_grouped_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t
                              workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
+int hif4_grouped_gemm_to_hif4(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
+                              const uint32_t *w_meta, const int32_t *offs, int E, int64_t total_rows, int64_t N, int64_t K,
+                              uint8_t *c_codes, uint32_t *c_meta, int round_mode, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (round_mode != HIF4_ROUND_RNE && round_mode != HIF4_ROUND_RHA) return HIF4_ERR_UNSUPPORTED;
+    if (E < 0 || N % HIF4_UNIT != 0) return HIF4_ERR_SHAPE; // units of the result run along N
+    if (int rc = check_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, total_rows, N, K, c_codes, N, HIF4_OUT_BF16, workspace, workspace_bytes))
+        return rc;
+    if (total_rows == 0 || N == 0 || E == 0) return HIF4_OK;
+    if (!c_meta || !offs) return HIF4_ERR_NULL;
+    if (!aligned(c_codes, 16) || !aligned(c_meta, 4) || !aligned(offs, 4)) return HIF4_ERR_ALIGN;
+    return hif4::launch_gemm(a_kind, a, a_meta, lda, w_codes, w_meta, offs, E, total_rows, N, K, c_codes, c_meta, N, 16 + round_mode,
+                             workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
 // ---- comparison tools (include/hif4_compare.h)
 
 static int check_compare_matrix(const void *x, int64_t rows, int64_t K, int64_t ldx, int64_t group)

@@ -503,12 +503,12 @@ static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stre
                                    : (int64_t)((m_tiles + 3) / 4) * ((g.tiles_n + 7) / 8) * 32;
     const dim3 grid((unsigned)((padded + 7) / 8 * 8)), block(64 * WM * WN);
     hipError_t e;
-    if constexpr (!GROUPED) {
+    {
         if (out_dtype == OUT_HIF4_RNE || out_dtype == OUT_HIF4_RHA) { // result written as HiF4
             constexpr size_t emit_bytes = emit_lds_bytes<BM, BN>() > loop_bytes ? emit_lds_bytes<BM, BN>() : loop_bytes;
             static_assert(emit_bytes <= 160 * 1024, "fits the LDS of one CU");
-            auto k = out_dtype == OUT_HIF4_RNE ? gemm_kernel<BM, BN, WM, WN, A_CELL, false, false, HIF4_ROUND_RNE>
-                                               : gemm_kernel<BM, BN, WM, WN, A_CELL, false, false, HIF4_ROUND_RHA>;
+            auto k = out_dtype == OUT_HIF4_RNE ? gemm_kernel<BM, BN, WM, WN, A_CELL, false, GROUPED, HIF4_ROUND_RNE>
+                                               : gemm_kernel<BM, BN, WM, WN, A_CELL, false, GROUPED, HIF4_ROUND_RHA>;
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)emit_bytes);
             if (e != hipSuccess) return HIF4_ERR_DEVICE;
             hipLaunchKernelGGL(k, grid, block, emit_bytes, stream, g);
@@ -644,7 +644,7 @@ static int colwave_rows(int64_t M, int E)
 }
 
 // out_dtype: HIF4_OUT_BF16, HIF4_OUT_F32, or 16 + rounding mode for a HiF4 result (c = codes plane, c_meta = its
-// metadata plane, ldc unused; dense calls only).
+// metadata plane, ldc unused).
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
                 uint32_t *c_meta, int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream)
@@ -700,7 +700,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (int rc = launch_decode_planes(w_codes, w_meta, N, K, ws + a_bytes, stream)) return rc;
             return launch_gemm_planes(ws, ws + a_bytes, M, N, K, c, c_meta, ldc, out_dtype, stream);
         }
-        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && (!emit || !offs) && colwave_fits(M, N, K) && workspace &&
+        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K) && workspace &&
             (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 && workspace_bytes >= (size_t)M * (size_t)K * 2) {
             // weight-only, grouped or a small dense call (colwave_dense_rows), and room for a reordered copy of A: the kernel of
             // the HiF4 x HiF4 calls of those shapes
@@ -739,7 +739,7 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
             if (M <= 32) return launch_skinny<2, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
             return launch_skinny<4, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         }
-        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K) && (!emit || !offs)) {
+        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K)) {
             // grouped, or a dense call of few rows (one m-tile, or a few on a small N): every weight meets few rows only,
             // so the kernel that expands W straight into MFMA operands takes the call
             // (hif4_gemm_colwave.hip); A as cell planes

@@ -65,7 +65,7 @@ struct ColwaveArgs {
     const uint32_t *w_meta;  // [E][N][K/64]
     const int32_t *offs;     // device int32[E+1], or nullptr: one matrix W for all M rows
     void *c;
-    uint32_t *c_meta; // HiF4 result (dense calls): c is its codes plane [M][N/2], this its metadata plane [M][N/64]
+    uint32_t *c_meta; // HiF4 result: c is its codes plane [M][N/2], this its metadata plane [M][N/64]
     int64_t ldc;
     int M, N, K, E;
     int tiles_m, tiles_n;
@@ -387,7 +387,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
 #ifndef HIF4_COLWAVE_NW_DENSE
 #define HIF4_COLWAVE_NW_DENSE 4
 #endif
-// EMIT_OK: also instantiate the kernels that write the result as HiF4 (dense shapes only)
+// EMIT_OK: also instantiate the kernels that write the result as HiF4
 template <int TMAX, int NW, int KS, bool EMIT_OK = false>
 static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
 {
@@ -409,7 +409,7 @@ static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
     bool ok;
     if (out_dtype == HIF4_OUT_F32) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_F32>);
     else if (out_dtype == HIF4_OUT_BF16) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_BF16>);
-    else if constexpr (EMIT_OK && BN % 64 == 0) { // 16 + rounding mode: the result as HiF4 (dense calls, the launcher below picks shapes that allow it)
+    else if constexpr (EMIT_OK && BN % 64 == 0) { // 16 + rounding mode: the result as HiF4 (the launcher below picks shapes that allow it)
         ok = out_dtype == 16 + HIF4_ROUND_RNE ? launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RNE>)
                                               : launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RHA>);
     } else return HIF4_ERR_UNSUPPORTED;
@@ -425,7 +425,7 @@ bool colwave_fits(int64_t M, int64_t N, int64_t K)
 
 // a_planes: decoded A as cell planes (launch_decode_planes).  offs != nullptr: grouped, E experts;
 // rows_per_tile: 64, 128, 192 or 256 rows of A per workgroup.
-// out_dtype: HIF4_OUT_BF16, HIF4_OUT_F32, or (dense calls, N a multiple of 64) 16 + rounding mode for a HiF4 result:
+// out_dtype: HIF4_OUT_BF16, HIF4_OUT_F32, or (N a multiple of 64) 16 + rounding mode for a HiF4 result:
 // c = codes plane, c_meta = its metadata plane, ldc unused.
 int launch_gemm_colwave(const void *a_planes, const uint8_t *w_codes, const uint32_t *w_meta, const int32_t *offs, int E,
                         int64_t M, int64_t N, int64_t K, void *c, uint32_t *c_meta, int64_t ldc, int out_dtype, int rows_per_tile,

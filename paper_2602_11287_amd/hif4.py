@@ -20,7 +20,7 @@ HIF4_A_BF16_QUANTIZE, HIF4_A_HIF4, HIF4_A_BF16_KEEP = 0, 1, 2
 HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 
 EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_gemm_to_hif4", "hif4_grouped_gemm",
-           "hif4_gemm_noalloc", "hif4_gemm_noalloc_max_bytes",
+           "hif4_gemm_noalloc", "hif4_gemm_noalloc_max_bytes", "hif4_grouped_gemm_to_hif4",
            "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version",
            "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16",
            "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm", "hif4ref_mfma_loop"]
@@ -55,6 +55,8 @@ def load():
         L.hif4_gemm_to_hif4.argtypes = [i32, vp, vp, i64, vp, vp, i64, i64, i64, vp, vp, i32, vp, sz, vp]
         L.hif4_grouped_gemm.restype = i32
         L.hif4_grouped_gemm.argtypes = [i32, vp, vp, i64, vp, vp, vp, i32, i64, i64, i64, vp, i64, i32, vp, sz, vp]
+        L.hif4_grouped_gemm_to_hif4.restype = i32
+        L.hif4_grouped_gemm_to_hif4.argtypes = [i32, vp, vp, i64, vp, vp, vp, i32, i64, i64, i64, vp, vp, i32, vp, sz, vp]
         L.hif4_gemm_noalloc.restype = i32
         L.hif4_gemm_noalloc.argtypes = [i32, vp, vp, i64, vp, vp, i64, i64, i64, vp, i64, i32, vp]
         L.hif4_gemm_noalloc_max_bytes.restype = sz
@@ -247,6 +249,30 @@ def hif4_grouped_gemm(a_kind, a, a_meta, w_codes, w_meta, offs, out_dtype=HIF4_O
                                     N, K, _ptr(c), ldc, out_dtype, _ptr(workspace), wsz, _stream(stream)),
            "hif4_grouped_gemm")
     return c
+
+
+def hif4_grouped_gemm_to_hif4(a_kind, a, a_meta, w_codes, w_meta, offs, round_mode=HIF4_ROUND_RNE, c_codes=None, c_meta=None,
+                              workspace=None, stream=None):
+    """As hif4_grouped_gemm, the result leaving as HiF4 planes (codes uint8 [M, N/2], meta int32 [M, N/64]), units along N."""
+    M = a.shape[0]
+    K = a.shape[1] * 2 if a_kind == HIF4_A_HIF4 else a.shape[1]
+    E, N = w_codes.shape[0], w_codes.shape[1]
+    assert offs.dtype == torch.int32 and offs.is_cuda and offs.numel() == E + 1
+    lda = _gemm_common(a_kind, a, a_meta, w_codes, M, K)
+    if c_codes is None:
+        c_codes = torch.empty((M, N // 2), dtype=torch.uint8, device=a.device)
+    if c_meta is None:
+        c_meta = torch.empty((M, N // 64), dtype=torch.int32, device=a.device)
+    need = hif4_gemm_workspace_bytes(a_kind, M, K)
+    if a_kind == HIF4_A_BF16_KEEP:
+        need = M * K * 2  # optional: room for a reordered copy of A selects the faster kernel
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+    wsz = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().hif4_grouped_gemm_to_hif4(a_kind, _ptr(a), _ptr(a_meta), lda, _ptr(w_codes), _ptr(w_meta), _ptr(offs), E, M,
+                                            N, K, _ptr(c_codes), _ptr(c_meta), round_mode, _ptr(workspace), wsz, _stream(stream)),
+           "hif4_grouped_gemm_to_hif4")
+    return c_codes, c_meta
 
 
 # ---- comparison tools of include/hif4_compare.h (quantisation-error study, Section III-A) -------------

@@ -111,6 +111,14 @@ def test_gemm_argument_errors(lib):
     assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, 4, 8, 16, 256, p, 16, 1, p, 4096, None) == h.HIF4_ERR_NULL
     assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, -1, 8, 16, 256, p, 16, 1, p, 4096, None) == h.HIF4_ERR_SHAPE
     assert gg(h.HIF4_A_HIF4, p, p, 256, p, p, None, 0, 8, 16, 256, p, 16, 1, p, 4096, None) == h.HIF4_OK
+    # grouped with a HiF4 result: units of the result run along N; both planes and the offsets are required
+    gh = lib.hif4_grouped_gemm_to_hif4
+    assert gh(h.HIF4_A_HIF4, p, p, 256, p, p, p, 4, 8, 96, 256, p, p, 0, p, 4096, None) == h.HIF4_ERR_SHAPE
+    assert gh(h.HIF4_A_HIF4, p, p, 256, p, p, p, 4, 8, 128, 256, p, p, 7, p, 4096, None) == h.HIF4_ERR_UNSUPPORTED
+    assert gh(h.HIF4_A_HIF4, p, p, 256, p, p, p, 4, 8, 128, 256, p, None, 0, p, 4096, None) == h.HIF4_ERR_NULL
+    assert gh(h.HIF4_A_HIF4, p, p, 256, p, p, None, 4, 8, 128, 256, p, p, 0, p, 4096, None) == h.HIF4_ERR_NULL
+    assert gh(h.HIF4_A_HIF4, p, p, 256, p, p, p, 4, 8, 128, 256, p, p, 1, p, 4095, None) == h.HIF4_ERR_WORKSPACE
+    assert gh(h.HIF4_A_HIF4, p, p, 256, p, p, p, 4, 0, 128, 256, p, p, 1, p, 4096, None) == h.HIF4_OK
 
 
 def test_product_path_has_no_cpu_fallback():
