@@ -54,6 +54,10 @@ def _quantize_rows(hif4, w, chunk_rows=16384):
 
 def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=True):
     legs = {}
+
+    def plan(a_kind, M, N, K, experts=0, ws=None, emit=False):
+        """Name of the main loop the library dispatches this call to (its own host query, not a guess)."""
+        return hif4.hif4_gemm_plan_name(hif4.hif4_gemm_plan(a_kind, M, N, K, experts=experts, result_as_hif4=emit, workspace_bytes=ws))
     gen = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 99)
     steps = max(2, min(steps, 10))
 
@@ -113,7 +117,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
                          "algorithmic_bytes": nbytes, "traffic": _TRAFFIC.get(name), "traffic_source": "profiles/ (not measured in this run)"}}
         return w, wcs[0], wms[0]
 
-    w, wc, wm = decode_leg("gemm_weight_only_M16_N4096_K4096", 16, 4096, 4096, 64, 0.02, "hif4::gemm_skinny_kernel<1,...> (expected)", True)
+    w, wc, wm = decode_leg("gemm_weight_only_M16_N4096_K4096", 16, 4096, 4096, 64, 0.02, plan(hif4.HIF4_A_BF16_KEEP, 16, 4096, 4096, ws=0), True)
     M, N, K = 16, 4096, 4096
     # the same weights against more rows (W4A4, activations quantised inside the call): the few-row kernel with K
     # split over wave groups, then several m-tiles of it, then the tile kernel; the vendor BF16 GEMM on the same
@@ -135,7 +139,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     del w, wc, wm
     # the decode shape of a 70B-class MLP: 16 rows against 28672 x 8192 weights (132 MB packed), 4 distinct matrices in turn
     if large:
-        tmp = decode_leg("gemm_weight_only_M16_N28672_K8192", 16, 28672, 8192, 4, 0.015, "hif4::gemm_skinny_kernel<1,...> (expected)", False)
+        tmp = decode_leg("gemm_weight_only_M16_N28672_K8192", 16, 28672, 8192, 4, 0.015, plan(hif4.HIF4_A_BF16_KEEP, 16, 28672, 8192, ws=0), False)
         del tmp
         torch.cuda.empty_cache()
 
@@ -165,7 +169,9 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     # the workspace with room for a decoded copy of W: both operands decoded once, plain BF16 main loop
     ws = torch.empty(hif4.hif4_gemm_workspace_bytes_decoded_w(hif4.HIF4_A_BF16_QUANTIZE, M, N, K), dtype=torch.uint8, device=dev)
     ws_small = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
-    planes, tiles = "hif4::gemm_planes16_kernel<256,256,2,4>", "hif4::gemm_kernel<256,256,2,4>"
+    QK = hif4.HIF4_A_BF16_QUANTIZE
+    planes = plan(QK, M, N, K, ws=ws.numel()) + " (+ pre-passes: encode_to_planes, decode_planes)"
+    tiles = plan(QK, M, N, K, ws=ws_small.numel()) + " (+ pre-pass: encode_to_cells)"
     mfma_leg("gemm_w4a4_quantize_inside_M4096_N11008_K4096", M, N, K,
              lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
              planes)
@@ -197,7 +203,7 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
     ws = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
     mfma_leg("grouped_gemm_w4a4_E64_rows8192_N2048_K7168", M, N, K,
              lambda: hif4.hif4_grouped_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, od, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
-             "hif4::gemm_colwave_kernel<TMAX=6,NW=8,KS=1,NB=3,R=4> (+ hif4::encode_to_planes_kernel)")
+             plan(hif4.HIF4_A_BF16_QUANTIZE, M, N, K, experts=E, ws=ws.numel()) + " (+ pre-pass: encode_to_planes)")
     nbytes = E * N * K // 64 * 36 + M * K * 2 + M * N * 2
     legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["GBps_algorithmic"] = round(
         nbytes / legs["grouped_gemm_w4a4_E64_rows8192_N2048_K7168"]["ms"] / 1e6, 1)

@@ -190,17 +190,22 @@ int hif4_grouped_gemm_to_hif4(int a_kind, const void *a, const uint32_t *a_meta,
 size_t hif4_gemm_workspace_bytes(int a_kind, int64_t M_or_total_rows, int64_t K);
 
 /*
- * Optional larger workspace for hif4_gemm (not the grouped call).  When M is large every unit
- * of W is decoded by many tiles of C; given this many bytes, hif4_gemm decodes W once per call
- * into the workspace (2 more bytes per weight; for a_kind 2 also a reordered copy of A, 2 bytes
- * per element) and runs its main loop on the decoded values of both operands.  The products are the same
- * and exact; the fp32 additions are grouped differently, so results agree to fp32 summation
- * accuracy, not always bit for bit.  Equals hif4_gemm_workspace_bytes() when M is too small for
- * this to pay (below 1536 rows, or below 3328 rows against more than 128 Mi weights), except for a_kind 2 on the shapes of the few-row kernel (up to
- * 192 rows, or up to 2048 rows with ceil(N/32) * ceil(M/128) <= 2048; not up to 16 rows, nor up to
- * 32 rows with N * K <= 48 Mi, nor up to 64 rows with N * K <= 24 Mi, which another kernel serves
- * faster), where M * K * 2 bytes for a reordered copy of A select that kernel.  A workspace between the two sizes is used as
- * the smaller one.  Host function.
+ * Optional larger workspace for hif4_gemm / hif4_gemm_to_hif4 (not the grouped calls): the size below which the
+ * library cannot take its fastest path for the shape.  Host function.  hif4_gemm_plan() tells which path a given
+ * size selects; a workspace between two sizes of the table is used as the smaller one.
+ *
+ *   shape                                                what the extra room holds             returned size
+ *   ---------------------------------------------------  ------------------------------------  -----------------------------
+ *   M >= 3328; or M >= 1536 with N*K <= 128 Mi and       a decoded copy of W (exact BF16       kinds 0, 1: mandatory size (16-byte
+ *   ceil(N/32)*ceil(M/128) > 2048 (or M > 2048)          values, 2 bytes per weight); kind 2    rounded) + N*K*2;  kind 2: M*K*2
+ *                                                        also a reordered copy of A             (16-byte rounded) + N*K*2
+ *   kind 2 only, 17 <= M <= 64 with N*K above 48 Mi      a reordered copy of A (it selects     M*K*2
+ *   (M <= 32) or 24 Mi; 65 <= M <= 192; 193 <= M <=      the kernel of the HiF4 x HiF4 calls
+ *   2048 with ceil(N/32)*ceil(M/128) <= 2048             of those shapes)
+ *   anything else                                        nothing                               hif4_gemm_workspace_bytes()
+ *
+ * With the decoded copy of W the products are the same and exact and the fp32 additions are grouped differently,
+ * so results agree to fp32 summation accuracy, not always bit for bit.
  */
 size_t hif4_gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 
@@ -228,6 +233,29 @@ int hif4_gemm_noalloc(int a_kind, const void *a, const uint32_t *a_meta, int64_t
 
 /* HIF4_NOALLOC_SCRATCH_BYTES of the built library.  Host function. */
 size_t hif4_gemm_noalloc_max_bytes(void);
+
+/*
+ * Which main loop a GEMM call runs: a pure host function of the call's kind, shape, output form and workspace size,
+ * the same one the library itself dispatches by (for tests, benchmarks and bug reports; nothing is launched).
+ *   experts          0 for hif4_gemm / hif4_gemm_to_hif4 / hif4_gemm_noalloc, E for the grouped calls
+ *   result_as_hif4   non-zero for the ..._to_hif4 calls
+ *   workspace_bytes  as passed to the call (taken to be non-NULL and 16-byte aligned when non-zero); lda is taken as K
+ * Returns a HIF4_PLAN_* value, or a negative status for arguments the calls would reject.
+ */
+enum {
+    HIF4_PLAN_ZERO_FILL = 0, /* K == 0: the result is zero                                                        */
+    HIF4_PLAN_FEWROWS = 1,   /* up to 32 rows against a wide W: W streamed once, E6M2 applied to unit sums      */
+    HIF4_PLAN_SKINNY = 2,    /* up to 64 rows: K split over the waves of 16-column workgroups                     */
+    HIF4_PLAN_STREAM = 3,    /* 33..64 BF16 rows against many columns: columns split only                         */
+    HIF4_PLAN_COLWAVE = 4,   /* few rows per weight (grouped, small dense): W expanded into MFMA operands         */
+    HIF4_PLAN_PLANES = 5,    /* many rows, large workspace: both operands decoded once, plain BF16 main loop      */
+    HIF4_PLAN_TILES = 6      /* 256 x 256 tiles, W expanded inside the main loop                                  */
+};
+int hif4_gemm_plan(int a_kind, int experts, int64_t M_or_total_rows, int64_t N, int64_t K, int result_as_hif4,
+                   size_t workspace_bytes);
+
+/* Static host string naming a HIF4_PLAN_* value (the kernel's name in the sources). */
+const char *hif4_gemm_plan_name(int plan);
 
 /* Static host string naming a status code. */
 const char *hif4_status_string(int status);

@@ -25,6 +25,7 @@ int launch_mxfp4_pack(const void *x, int64_t rows, int64_t K, int64_t ldx, void 
 int launch_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_cells, const void *w_scales, int64_t M, int64_t N,
                       int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream);
 int launch_mfma_loop(int kind, int iters, float *out, hipStream_t stream);
+int gemm_plan(int a_kind, bool grouped, int E, int64_t M, int64_t N, int64_t K, int64_t lda, bool emit, bool ws_ok, size_t ws_bytes);
 size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 } // namespace hif4
@@ -305,6 +306,29 @@ int hif4ref_mfma_loop(int kind, int iters, float *out, void *stream)
     if (!out) return HIF4_ERR_NULL;
     if (!aligned(out, 4)) return HIF4_ERR_ALIGN;
     return hif4::launch_mfma_loop(kind, iters, out, static_cast<hipStream_t>(stream));
+}
+
+int hif4_gemm_plan(int a_kind, int experts, int64_t M, int64_t N, int64_t K, int result_as_hif4, size_t workspace_bytes)
+{
+    if (a_kind != HIF4_A_BF16_QUANTIZE && a_kind != HIF4_A_HIF4 && a_kind != HIF4_A_BF16_KEEP) return HIF4_ERR_UNSUPPORTED;
+    if (experts < 0 || M < 0 || N < 0 || K < 0 || K % HIF4_UNIT != 0 || M >= MAX_DIM || N >= MAX_DIM || K >= MAX_DIM) return HIF4_ERR_SHAPE;
+    if (result_as_hif4 && N % HIF4_UNIT != 0) return HIF4_ERR_SHAPE;
+    if (workspace_bytes < hif4_gemm_workspace_bytes(a_kind, M, K)) return HIF4_ERR_WORKSPACE;
+    return hif4::gemm_plan(a_kind, experts > 0, experts, M, N, K, K, result_as_hif4 != 0, workspace_bytes > 0, workspace_bytes);
+}
+
+const char *hif4_gemm_plan_name(int plan)
+{
+    switch (plan) {
+    case HIF4_PLAN_ZERO_FILL: return "hif4::zero_kernel";
+    case HIF4_PLAN_FEWROWS: return "hif4::gemm_fewrows_kernel";
+    case HIF4_PLAN_SKINNY: return "hif4::gemm_skinny_kernel";
+    case HIF4_PLAN_STREAM: return "hif4::gemm_stream_kernel";
+    case HIF4_PLAN_COLWAVE: return "hif4::gemm_colwave_kernel";
+    case HIF4_PLAN_PLANES: return "hif4::gemm_planes16_kernel";
+    case HIF4_PLAN_TILES: return "hif4::gemm_kernel";
+    default: return "unknown plan";
+    }
 }
 
 const char *hif4_status_string(int status)

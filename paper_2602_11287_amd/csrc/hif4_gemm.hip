@@ -643,14 +643,49 @@ static int colwave_rows(int64_t M, int E)
     return want <= 64 ? 64 : want <= 128 ? 128 : want <= 192 ? 192 : 256;
 }
 
+// Which main loop takes a call: a pure function of the call's shape, kind, output form and workspace, so that the
+// choice can be tested (and reported) without a GPU.  grouped: the call has per-expert row ranges (E experts);
+// ws_ok: the workspace pointer is there and 16-byte aligned.
+int gemm_plan(int a_kind, bool grouped, int E, int64_t M, int64_t N, int64_t K, int64_t lda, bool emit, bool ws_ok, size_t ws_bytes)
+{
+    if (K == 0) return HIF4_PLAN_ZERO_FILL;
+    const bool keep = a_kind == HIF4_A_BF16_KEEP;
+    const size_t a_bf16 = (size_t)M * (size_t)K * 2; // A as BF16: the decoded copy of HiF4 activations, or a reordered copy of plain ones
+    // a few rows against a wide weight matrix: W streamed once, unit scales applied to the units' partial sums
+    if (HIF4_FEWROWS && !grouped && !emit && fewrows_pays(M, N, K) && fewrows_fits(M, N, K, keep ? lda : K)) return HIF4_PLAN_FEWROWS;
+    const int cw_rows = grouped ? colwave_rows(M, E) : colwave_dense_rows(M, N);
+    const bool colwave_ok = cw_rows > 0 && colwave_fits(M, N, K) && (!keep || (ws_ok && ws_bytes >= a_bf16));
+    if (keep && !grouped && M <= 64 && !emit && (few_rows_prefer_k_split(M, N, K) || !colwave_ok)) {
+        // decode-shaped: 33 to 64 rows against many columns go to the kernel that splits columns only (measured 96
+        // against 122 us for 64 x 28672 x 8192, 38 against 43 us at 14336 x 4096, 36 against 30 us at 11008 x 4096),
+        // the rest to the one that splits K over the waves of 16-column workgroups
+        return M > 32 && K % 128 == 0 && N >= STREAM_MIN_COLUMNS ? HIF4_PLAN_STREAM : HIF4_PLAN_SKINNY;
+    }
+    // many rows and room for a decoded copy of W: both operands decoded once, main loop without any expansion
+    if (!grouped && decoded_w_pays(M, N, K) && (!keep || ws_ok) && ws_bytes >= align16(a_bf16) + (size_t)N * (size_t)K * 2) return HIF4_PLAN_PLANES;
+    // HiF4 activations, few rows against not too many weights: the K-split kernel fed with their exact BF16 values
+    if (!keep && !grouped && !emit && M <= 64 && few_rows_prefer_k_split(M, N, K)) return HIF4_PLAN_SKINNY;
+    // grouped, or a dense call of few rows (one m-tile, or a few on a small N): every weight meets few rows only, so
+    // the kernel that expands W straight into MFMA operands takes the call
+    if (colwave_ok) return HIF4_PLAN_COLWAVE;
+    return HIF4_PLAN_TILES; // W expanded inside the main loop of the 256 x 256 tile kernel
+}
+
 // out_dtype: HIF4_OUT_BF16, HIF4_OUT_F32, or 16 + rounding mode for a HiF4 result (c = codes plane, c_meta = its
-// metadata plane, ldc unused).
+// metadata plane, ldc unused).  HiF4 activations enter every main loop as their exact BF16 values (at most 6
+// significant bits each), written once per call into the workspace in the form the chosen loop reads; when the call
+// quantises them itself, Algorithm 1 and Eq. 2 run in one pass and the packed activations never reach memory.
 int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, const uint8_t *w_codes,
                 const uint32_t *w_meta, const int32_t *offs, int E, int64_t M, int64_t N, int64_t K, void *c,
                 uint32_t *c_meta, int64_t ldc, int out_dtype, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
     const bool emit = out_dtype == OUT_HIF4_RNE || out_dtype == OUT_HIF4_RHA;
-    if (K == 0) { // empty sum: C = 0 (a fill kernel, so that the call can be captured in a graph)
+    const bool keep = a_kind == HIF4_A_BF16_KEEP, quantize = a_kind == HIF4_A_BF16_QUANTIZE;
+    const bool ws_ok = workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0;
+    const uint8_t *a_packed = static_cast<const uint8_t *>(a);
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    switch (gemm_plan(a_kind, offs != nullptr, E, M, N, K, lda, emit, ws_ok, workspace_bytes)) {
+    case HIF4_PLAN_ZERO_FILL: { // empty sum: C = 0 (a fill kernel, so that the call can be captured in a graph)
         const dim3 grid((unsigned)((N + 255) / 256), (unsigned)(M < 65535 ? M : 65535)), block(256);
         if (emit) { // the all-zero unit: codes 0, metadata 0 (E6M2 at its least code, no micro-exponents)
             hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((N / 4 + 255) / 256), grid.y), block, 0, stream, c, M, N / 4, N / 4, 2);
@@ -660,106 +695,53 @@ int launch_gemm(int a_kind, const void *a, const uint32_t *a_meta, int64_t lda, 
         }
         return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
     }
-    if (HIF4_FEWROWS && !offs && !emit && fewrows_pays(M, N, K) && fewrows_fits(M, N, K, a_kind == HIF4_A_BF16_KEEP ? lda : K)) {
-        // a few rows against a wide weight matrix: the kernel that streams W once and applies the unit scales to the
-        // units' partial sums (hif4_gemm_fewrows.hip); HiF4 activations enter as their exact BF16 values, dense rows
-        // in the workspace
-        if (a_kind == HIF4_A_BF16_KEEP) return launch_gemm_fewrows(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
-        if (a_kind == HIF4_A_BF16_QUANTIZE) {
-            if (int rc = launch_encode_to_rows(a, M, K, lda, workspace, HIF4_ROUND_RNE, stream)) return rc;
-        } else {
-            if (int rc = launch_decode(static_cast<const uint8_t *>(a), a_meta, M, K, workspace, K, stream)) return rc;
+    case HIF4_PLAN_FEWROWS: { // A as dense rows in natural element order
+        if (keep) return launch_gemm_fewrows(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+        if (int rc = quantize ? launch_encode_to_rows(a, M, K, lda, ws, HIF4_ROUND_RNE, stream) : launch_decode(a_packed, a_meta, M, K, ws, K, stream)) return rc;
+        return launch_gemm_fewrows(ws, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+    }
+    case HIF4_PLAN_STREAM: return launch_gemm_stream(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+    case HIF4_PLAN_SKINNY: {
+        if (keep) {
+            if (M <= 16) return launch_skinny<1>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+            if (M <= 32) return launch_skinny<2>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+            return launch_skinny<4>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
         }
-        return launch_gemm_fewrows(workspace, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+        // A as dense rows, every group of 8 in cell order
+        if (int rc = quantize ? launch_encode_to_cells(a, M, K, lda, ws, HIF4_ROUND_RNE, stream) : launch_decode_cells(a_packed, a_meta, M, K, ws, stream)) return rc;
+        if (M <= 16) return launch_skinny<1, true>(ws, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+        if (M <= 32) return launch_skinny<2, true>(ws, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+        return launch_skinny<4, true>(ws, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
     }
-    if (a_kind == HIF4_A_BF16_KEEP && !offs && M <= 64 && !emit &&
-        (few_rows_prefer_k_split(M, N, K) || !colwave_fits(M, N, K) || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 15) != 0 ||
-         workspace_bytes < (size_t)M * (size_t)K * 2)) { // decode-shaped: stream the weights once
-        // 33 to 64 rows against many columns: columns split over workgroups only, whole K per wave, the
-        // activations shared through LDS (hif4_gemm_stream.hip; measured 96 us against 122 us for
-        // 64 x 28672 x 8192, 38 against 43 us at 14336 x 4096, 36 against 30 us at 11008 x 4096).  With
-        // fewer rows or columns the split of K over the waves of a workgroup below is as fast or faster
-        // (both kernels are bound by the expansion arithmetic, not by HBM).
-        if (M > 32 && K % 128 == 0 && N >= STREAM_MIN_COLUMNS) return launch_gemm_stream(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
-        if (M <= 16) return launch_skinny<1>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
-        if (M <= 32) return launch_skinny<2>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
-        return launch_skinny<4>(a, lda, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
+    case HIF4_PLAN_PLANES: { // both operands as cell planes: A first, W behind it
+        uint8_t *wplanes = ws + align16((size_t)M * (size_t)K * 2);
+        if (int rc = keep       ? launch_bf16_to_planes(a, M, K, lda, ws, stream)
+                     : quantize ? launch_encode_to_planes(a, M, K, lda, ws, HIF4_ROUND_RNE, stream)
+                                : launch_decode_planes(a_packed, a_meta, M, K, ws, stream))
+            return rc;
+        if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
+        return launch_gemm_planes(ws, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
     }
-    // HiF4 activations enter the tile kernel as their exact BF16 values (at most 6 significant
-    // bits each), decoded once per call into the workspace in cell order; only the weights are
-    // expanded inside the main loop.  This halves the VALU work next to the MFMA pipeline.
+    case HIF4_PLAN_COLWAVE: { // A as cell planes
+        if (int rc = keep       ? launch_bf16_to_planes(a, M, K, lda, ws, stream)
+                     : quantize ? launch_encode_to_planes(a, M, K, lda, ws, HIF4_ROUND_RNE, stream)
+                                : launch_decode_planes(a_packed, a_meta, M, K, ws, stream))
+            return rc;
+        return launch_gemm_colwave(ws, w_codes, w_meta, offs, E, M, N, K, c, c_meta, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
+    }
+    default: break;
+    }
+    // HIF4_PLAN_TILES: plain BF16 rows of A as they are, HiF4 activations as dense rows in cell order
     GemmArgs g;
-    bool a_cell = true;
-    if (a_kind == HIF4_A_BF16_KEEP) {
-        const size_t a_bytes = align16((size_t)M * (size_t)K * 2);
-        if (!offs && decoded_w_pays(M, N, K) && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
-            workspace_bytes >= a_bytes + (size_t)N * (size_t)K * 2) {
-            // weight-only with many rows and room in the workspace: the plane-fed kernel here too
-            uint8_t *ws = static_cast<uint8_t *>(workspace);
-            if (int rc = launch_bf16_to_planes(a, M, K, lda, ws, stream)) return rc;
-            if (int rc = launch_decode_planes(w_codes, w_meta, N, K, ws + a_bytes, stream)) return rc;
-            return launch_gemm_planes(ws, ws + a_bytes, M, N, K, c, c_meta, ldc, out_dtype, stream);
-        }
-        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K) && workspace &&
-            (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 && workspace_bytes >= (size_t)M * (size_t)K * 2) {
-            // weight-only, grouped or a small dense call (colwave_dense_rows), and room for a reordered copy of A: the kernel of
-            // the HiF4 x HiF4 calls of those shapes
-            if (int rc = launch_bf16_to_planes(a, M, K, lda, workspace, stream)) return rc;
-            return launch_gemm_colwave(workspace, w_codes, w_meta, offs, E, M, N, K, c, c_meta, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
-        }
+    if (keep) {
         g.a = static_cast<const uint16_t *>(a);
         g.lda = lda;
-        a_cell = false;
     } else {
-        uint8_t *ws = static_cast<uint8_t *>(workspace);
-        const size_t base = align16(gemm_workspace_bytes(a_kind, M, K));
-        const bool planes = !offs && decoded_w_pays(M, N, K) && workspace_bytes >= base + (size_t)N * (size_t)K * 2;
-        uint8_t *adec = ws; // the decoded copy of A
-        if (planes) {
-            // room for a decoded copy of W and enough rows for it to pay: both operands as
-            // cell planes, main loop without any expansion
-            uint8_t *wplanes = ws + base;
-            if (a_kind == HIF4_A_BF16_QUANTIZE) {
-                if (int rc = launch_encode_to_planes(a, M, K, lda, adec, HIF4_ROUND_RNE, stream)) return rc;
-            } else {
-                if (int rc = launch_decode_planes(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
-            }
-            if (int rc = launch_decode_planes(w_codes, w_meta, N, K, wplanes, stream)) return rc;
-            return launch_gemm_planes(adec, wplanes, M, N, K, c, c_meta, ldc, out_dtype, stream);
-        }
-        if (!offs && !emit && M <= 64 && few_rows_prefer_k_split(M, N, K)) {
-            // few rows against not too many weights: the kernel of the weight-only decode shape, fed with the exact
-            // BF16 values of the HiF4 activations (cell order, dense rows)
-            if (a_kind == HIF4_A_BF16_QUANTIZE) {
-                if (int rc = launch_encode_to_cells(a, M, K, lda, adec, HIF4_ROUND_RNE, stream)) return rc;
-            } else {
-                if (int rc = launch_decode_cells(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
-            }
-            if (M <= 16) return launch_skinny<1, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
-            if (M <= 32) return launch_skinny<2, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
-            return launch_skinny<4, true>(adec, K, w_codes, w_meta, M, N, K, c, ldc, out_dtype, stream);
-        }
-        if ((offs ? colwave_rows(M, E) : colwave_dense_rows(M, N)) > 0 && colwave_fits(M, N, K)) {
-            // grouped, or a dense call of few rows (one m-tile, or a few on a small N): every weight meets few rows only,
-            // so the kernel that expands W straight into MFMA operands takes the call
-            // (hif4_gemm_colwave.hip); A as cell planes
-            if (a_kind == HIF4_A_BF16_QUANTIZE) {
-                // quantise and decode in one pass: the packed activations are never needed in memory
-                if (int rc = launch_encode_to_planes(a, M, K, lda, adec, HIF4_ROUND_RNE, stream)) return rc;
-            } else {
-                if (int rc = launch_decode_planes(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
-            }
-            return launch_gemm_colwave(adec, w_codes, w_meta, offs, E, M, N, K, c, c_meta, ldc, out_dtype, offs ? colwave_rows(M, E) : colwave_dense_rows(M, N), stream);
-        }
-        if (a_kind == HIF4_A_BF16_QUANTIZE) {
-            // quantise and decode in one pass: the packed activations are never needed in memory
-            if (int rc = launch_encode_to_cells(a, M, K, lda, adec, HIF4_ROUND_RNE, stream)) return rc;
-        } else {
-            if (int rc = launch_decode_cells(static_cast<const uint8_t *>(a), a_meta, M, K, adec, stream)) return rc;
-        }
-        g.a = reinterpret_cast<const uint16_t *>(adec);
+        if (int rc = quantize ? launch_encode_to_cells(a, M, K, lda, ws, HIF4_ROUND_RNE, stream) : launch_decode_cells(a_packed, a_meta, M, K, ws, stream)) return rc;
+        g.a = reinterpret_cast<const uint16_t *>(ws);
         g.lda = K;
     }
+    const bool a_cell = !keep;
     g.w_codes = reinterpret_cast<const uint32_t *>(w_codes);
     g.w_meta = w_meta;
     g.offs = offs;

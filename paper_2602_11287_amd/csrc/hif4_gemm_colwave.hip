@@ -220,6 +220,15 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
         issue_a(k + NB, k + NB);
         issue_w(k + R, k + R);
     }
+    // Why the wait counts below are exact.  (1) Loads land in the order they were issued, and from here to the end of
+    // the main loop this wave issues no vector memory instruction but the LDS-writing loads of issue_a / issue_w, PER_STEP
+    // per step in a fixed order: the reads of the row offsets in find_expert_tile were consumed above (the compiler waited
+    // for them before the lane shuffles), the results are stored after the loop's final vmcnt(0), and the build fails if
+    // this kernel uses scratch memory (paper_2602_11287_amd/build.py), so no spill code can sit between them.
+    // (2) In the prologue the order is W(0) .. W(R - NB - 1), then [A(j), W(j + R - NB)] for j = 0 .. NB - 1: the loads
+    // younger than A(0) are its own W (2) and NB - 1 later groups.  (3) In the loop, step k issues [A(k + NB), W(k + R)]
+    // after its wait, so at the wait of step k the loads younger than A(k + 1) are W(k + 1 + R - NB) (2) and the groups
+    // of steps k + 2 - NB .. k - 1, i.e. NB - 2 of them; W(k + 1) is older than A(k + 1) because R > NB.
     // A(0) and W(0) have landed once only the loads younger than A(0) are in flight
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(2 + (NB - 1) * PER_STEP) : "memory");
     __syncthreads();

@@ -18,9 +18,10 @@ HIF4_ERR_UNSUPPORTED, HIF4_ERR_WORKSPACE, HIF4_ERR_DEVICE, HIF4_ERR_SCRATCH = -4
 HIF4_ROUND_RNE, HIF4_ROUND_RHA = 0, 1
 HIF4_A_BF16_QUANTIZE, HIF4_A_HIF4, HIF4_A_BF16_KEEP = 0, 1, 2
 HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
+HIF4_PLAN_ZERO_FILL = 0
 
 EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_gemm_to_hif4", "hif4_grouped_gemm",
-           "hif4_gemm_noalloc", "hif4_gemm_noalloc_max_bytes", "hif4_grouped_gemm_to_hif4",
+           "hif4_gemm_noalloc", "hif4_gemm_noalloc_max_bytes", "hif4_grouped_gemm_to_hif4", "hif4_gemm_plan", "hif4_gemm_plan_name",
            "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version",
            "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16",
            "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm", "hif4ref_mfma_loop"]
@@ -57,6 +58,10 @@ def load():
         L.hif4_grouped_gemm.argtypes = [i32, vp, vp, i64, vp, vp, vp, i32, i64, i64, i64, vp, i64, i32, vp, sz, vp]
         L.hif4_grouped_gemm_to_hif4.restype = i32
         L.hif4_grouped_gemm_to_hif4.argtypes = [i32, vp, vp, i64, vp, vp, vp, i32, i64, i64, i64, vp, vp, i32, vp, sz, vp]
+        L.hif4_gemm_plan.restype = i32
+        L.hif4_gemm_plan.argtypes = [i32, i32, i64, i64, i64, i32, sz]
+        L.hif4_gemm_plan_name.restype = C.c_char_p
+        L.hif4_gemm_plan_name.argtypes = [i32]
         L.hif4_gemm_noalloc.restype = i32
         L.hif4_gemm_noalloc.argtypes = [i32, vp, vp, i64, vp, vp, i64, i64, i64, vp, i64, i32, vp]
         L.hif4_gemm_noalloc_max_bytes.restype = sz
@@ -112,6 +117,19 @@ def hif4_status_string(status):
 
 def hif4_gemm_workspace_bytes(a_kind, rows, K):
     return int(load().hif4_gemm_workspace_bytes(int(a_kind), int(rows), int(K)))
+
+
+def hif4_gemm_plan(a_kind, M, N, K, experts=0, result_as_hif4=False, workspace_bytes=None):
+    """HIF4_PLAN_* value of the main loop a call with these arguments runs (workspace_bytes None: the mandatory size)."""
+    if workspace_bytes is None:
+        workspace_bytes = hif4_gemm_workspace_bytes(a_kind, M, K)
+    plan = load().hif4_gemm_plan(int(a_kind), int(experts), int(M), int(N), int(K), int(bool(result_as_hif4)), int(workspace_bytes))
+    _check(min(plan, 0), "hif4_gemm_plan")
+    return plan
+
+
+def hif4_gemm_plan_name(plan):
+    return load().hif4_gemm_plan_name(int(plan)).decode()
 
 
 def hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K):

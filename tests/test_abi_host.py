@@ -174,3 +174,14 @@ def test_gemm_to_hif4_argument_errors(lib):
     assert call(c_codes=p + 8) == h.HIF4_ERR_ALIGN
     assert call(a_kind=h.HIF4_A_HIF4, a_meta=p, ws=None) == h.HIF4_ERR_WORKSPACE
     assert call(M=0, a=None, c_codes=None, c_meta=None) == h.HIF4_OK
+
+
+def test_build_refuses_scratch_in_kernels_that_count_their_own_loads():
+    """The kernels with hand-counted s_waitcnt vmcnt literals must not spill (a spill adds vector memory instructions
+    the count does not know): the build reads the compiler's resource report and fails on any scratch use in them."""
+    from paper_2602_11287_amd import build
+    with pytest.raises(RuntimeError):
+        build._check_no_scratch("f.hip:1:1: remark: Function Name: _ZN4hif419gemm_colwave_kernelILi6ELi8EEEv [-Rpass-analysis=kernel-resource-usage]\n"
+                                "f.hip:1:1: remark:     ScratchSize [bytes/lane]: 16 [-Rpass-analysis=kernel-resource-usage]")
+    build._check_no_scratch("f.hip:1:1: remark: Function Name: _ZN4hif419gemm_colwave_kernelILi6ELi8EEEv [-Rpass-analysis=kernel-resource-usage]\n"
+                            "f.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]")
