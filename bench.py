@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-gemm", action="store_true", help="time the encode/decode legs only")
+    ap.add_argument("--gemm-legs", default="", help="comma-separated subset of the GEMM legs (ceiling, decode, decode_large, prefill, "
+                                                    "grouped, large), e.g. for a profiler run; default: all")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain device copy of the 512 MiB batch (known size) for counter scaling")
     args = ap.parse_args()
@@ -212,7 +214,8 @@ def main():
     if not args.no_gemm:
         try:
             import bench_gemm
-            out["legs"].update(bench_gemm.run(hif4, synth, dev, args.steps, args.warmup, MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBPS))
+            out["legs"].update(bench_gemm.run(hif4, synth, dev, args.steps, args.warmup, MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBPS,
+                                              only=set(args.gemm_legs.split(",")) if args.gemm_legs else None))
         except ImportError:
             pass
 
