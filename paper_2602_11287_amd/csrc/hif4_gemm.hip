@@ -571,16 +571,17 @@ static bool few_rows_prefer_k_split(int64_t M, int64_t N, int64_t K)
     return M <= 16 || (M <= 32 && weights <= ((int64_t)48 << 20)) || (M <= 64 && weights <= ((int64_t)24 << 20));
 }
 
-// 5 to 16 rows against at least 14336 columns, 17 to 32 rows against at least 28672: the kernel of
-// hif4_gemm_fewrows.hip.  Measured from HIP graphs over distinct weight matrices (us, that kernel : gemm_skinny_kernel):
-// 16 x 14336 x 4096 16.5 : 19.8, 16 x 28672 x 4096 27.5 : 31.8, 16 x 16384 x 8192 30.2 : 36.9, 8 x 28672 x 8192 48.9 : 53.2,
-// 16 x 28672 x 8192 49.8 : 62.6, 32 x 28672 x 8192 57.0 : 74.6, 32 x 28672 x 4096 31.6 : 38.3; the other way round with fewer
-// columns (its 32-column strips do not fill the chip: 16 x 11008 x 4096 17 : 16, 16 x 8192 x 28672 82 : 68, 16 x 4096 x 4096
-// 16 : 7.5), with 32 rows on 16384 columns (53 : 47) and with one or two rows (a tie: 2 x 28672 x 8192 49.0 : 48.2).
+// Up to 32 rows against at least 6144 columns: the kernel of hif4_gemm_fewrows.hip.  Measured from HIP graphs over
+// distinct weight matrices (us, that kernel : gemm_skinny_kernel), 16 rows: 6144 x 4096 10.8 : 11.2, 8192 x 4096 11.1 : 11.5,
+// 11008 x 4096 13.0 : 15.2, 14336 x 4096 15.0 : 19.8, 8192 x 8192 18.0 : 20.6, 28672 x 8192 41.9 : 62.6, 8192 x 28672
+// 48.5 : 66.4; 32 rows: 6144 x 4096 14.4 : 14.4, 11008 x 4096 16.9 : 19.7, 8192 x 8192 25.4 : 31.5, 28672 x 8192 51.2 : 74.6,
+// 8192 x 28672 79.7 : 88.0; one row: 11008 x 4096 11.1 : 12.4, 28672 x 8192 40.9 : 46.8.  The other way round on fewer
+// columns, where its 16-column strips do not fill the chip with waves (16 rows: 4096 x 4096 8.8 : 7.2, 2048 x 7168
+// 12.3 : 10.3, 4096 x 11008 17.5 : 15.4; 32 rows: 14.2 : 8.4, 20.9 : 13.5, 32.1 : 20.5; 8 rows and fewer: within 5 %).
 static bool fewrows_pays(int64_t M, int64_t N, int64_t K)
 {
     (void)K;
-    return (M >= 5 && M <= 16 && N >= 14336) || (M > 16 && M <= 32 && N >= 28672);
+    return M <= 32 && N >= 6144;
 }
 
 // Rows of A per workgroup of that kernel for a dense call, 0: not its case.  Up to 192 rows: one tile.

@@ -16,22 +16,23 @@
 // accumulator, and 8 fused multiply-adds per lane and 16 rows add its scaled sums to the running result.  With few rows that is cheap; from about 128 rows
 // on it would cost what it saves, which is why the kernels for more rows keep the full expansion.
 //
-// Shape: a wave owns 32 output columns (two column groups of 16 for v_mfma_f32_16x16x32_bf16, whose K of
+// Shape: a wave owns a strip of CG column groups of 16 output columns (v_mfma_f32_16x16x32_bf16, whose K of
 // 32 is half a unit: lane (n, q) = (lane % 16, lane / 16) supplies group 4 hs + q of the unit's 8 groups of 8
 // from both operands in half step hs) over one of KS parts of K; a workgroup is NWC such column strips
-// times KS parts.
+// times KS parts.  With CG = 2 an operand of A serves two MFMAs; with CG = 1 there are twice as many strips to
+// spread over the compute units and over K, which is what counts on all but the widest matrices.
 // Everything comes in through LDS by direct global -> LDS loads, D steps of two units deep, so that the
 // bytes in flight per CU (what hides HBM latency) are bounded by LDS, not by registers:
-//   W codes  per wave and step: 32 rows x 64 bytes, four adjacent lanes per row, so every request
+//   W codes  per wave and step: 16 CG rows x 64 bytes, four adjacent lanes per row, so every request
 //            covers whole 64-byte runs of a row (two steps use up a 128-byte line); the 16-byte chunks
 //            of a row are stored XOR-swizzled so that the operand reads are spread over the banks;
-//   W meta   per wave and 8 steps: 32 rows x 16 words (64-byte runs again: a request per row and step for
+//   W meta   per wave and 8 steps: 16 CG rows x 16 words (64-byte runs again: a request per row and step for
 //            8 bytes would double the number of requests, and requests in flight are what a CU runs out of);
 //   A        per K part and step: 16 cells of 8 values x RM rows, [cell][row], shared by the part's
 //            NWC waves (plain 16-byte pieces of the rows of A: the K order inside a cell is natural here).
 // One barrier per step (two units).  The partial sums of the K parts meet in LDS at the end, in a
 // fixed order.  All global loads of the loop are LDS-writing loads in inline assembly, PER per wave and step
-// plus two of metadata every eighth step, issued at least eight steps before their use; loads land in
+// plus CG of metadata every eighth step, issued at least eight steps before their use; loads land in
 // the order they were issued, so s_waitcnt vmcnt((D - 2) PER) before step i leaves only loads younger than
 // those of step i in flight (the compiler never sees them, and the loop contains no other vector memory
 // instruction).  K must be a multiple of 256 (metadata rows then start on 16-byte boundaries).
@@ -64,11 +65,11 @@ struct FewRowsArgs {
     int out_f32;
 };
 
-template <int RM, int NWC, int KS>
+template <int RM, int NWC, int KS, int CG>
 struct FewRowsShape {
     static constexpr int NW = NWC * KS;
-    static constexpr size_t slot_bytes = (size_t)KS * 16 * RM * 16 + (size_t)NW * 2048; // A of every K part, codes of every wave
-    static constexpr size_t meta_bytes = (size_t)NW * 2 * 2048;                          // two blocks of 16 units x 32 rows per wave
+    static constexpr size_t slot_bytes = (size_t)KS * 16 * RM * 16 + (size_t)NW * CG * 1024; // A of every K part, codes of every wave
+    static constexpr size_t meta_bytes = (size_t)NW * 2 * CG * 1024;                          // two blocks of 16 units x 16 CG rows per wave
     // workgroups of 4 waves leave room for a second one on the CU where three steps fit half the LDS
     static constexpr size_t budget = ((NW == 4 && 3 * slot_bytes + meta_bytes <= 80 * 1024) ? 80 * 1024 : 160 * 1024) - meta_bytes;
     static constexpr int D = budget / slot_bytes >= 6 ? 6 : (int)(budget / slot_bytes);
@@ -79,28 +80,30 @@ struct FewRowsShape {
 // E4M3 patterns of the integers 0..7 (bias 7: 1 = 0x38, 2 = 0x40, 3 = 0x44, ...), the byte table of v_perm_b32
 constexpr uint32_t FP8_OF_0123 = 0x44403800u, FP8_OF_4567 = 0x4E4C4A48u;
 
-template <int RM, int NWC, int KS>
+template <int RM, int NWC, int KS, int CG>
 __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs g)
 {
-    using Shape = FewRowsShape<RM, NWC, KS>;
+    using Shape = FewRowsShape<RM, NWC, KS, CG>;
     constexpr int NW = Shape::NW, D = Shape::D;
     constexpr int RB = RM / 16;                   // 16-row blocks
     constexpr int A_INSTR = RM / 4;               // 64-cell loads of A per K part and step (16 cells x RM rows)
     constexpr int IA = (KS * A_INSTR + NW - 1) / NW; // of them per wave
-    constexpr int PER = IA + 2;                   // LDS-writing loads per wave and step: A, two of codes
+    constexpr int PER = IA + CG;                  // LDS-writing loads per wave and step: A, one of codes per column group
     constexpr int A_PART = 16 * RM;               // cells of A per K part and slot
     constexpr int CODES0 = KS * A_PART;           // first cell of the codes of a slot
-    constexpr int SLOT = CODES0 + NW * 128;       // cells per slot
-    constexpr int META0 = D * SLOT;               // first cell of the metadata ring: [wave][2 blocks][32 rows][4 cells]
+    constexpr int WCELLS = 64 * CG;               // cells of codes per wave and step (16 CG rows x 64 bytes), and of a metadata block
+    constexpr int SLOT = CODES0 + NW * WCELLS;    // cells per slot
+    constexpr int META0 = D * SLOT;               // first cell of the metadata ring: [wave][2 blocks][16 CG rows][4 cells]
     static_assert(Shape::fits && SLOT * 16 == Shape::slot_bytes, "LDS plan");
     static_assert((D - 2) * PER <= 63, "the wait count is a 6-bit field");
     static_assert(RM == 16 || RM == 32, "rows of a tile");
+    static_assert(CG == 1 || CG == 2, "column groups of a wave");
     extern __shared__ uint4 lds[];
 
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const int cw = wave % NWC, kw = wave / NWC; // column strip and K part of this wave
-    const int col0 = ((int)blockIdx.x * NWC + cw) * 32;
+    const int col0 = ((int)blockIdx.x * NWC + cw) * 16 * CG;
     const int upr = g.K / 64, np = (upr + 1) / 2; // units per row, pairs of units (steps) in K
     const int ppp = (np + KS - 1) / KS;           // steps per K part; part kw takes pairs [kw ppp, (kw + 1) ppp)
     const int p0 = kw * ppp;
@@ -109,23 +112,23 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
     // ---- load plan.  Every address is a 64-bit scalar base that moves with the step plus a 32-bit byte
     // offset per lane (the host keeps the operands below 4 GiB).  Loads past the end of K repeat the
     // last pair, and the missing second unit of an odd last pair repeats its first: never used, in bounds.
-    // W codes, load t of 2: lane -> weight row 16 t + lane / 4, position lane % 4 of the row's four
+    // W codes, load t of CG: lane -> weight row 16 t + lane / 4, position lane % 4 of the row's four
     // 16-byte chunks, which holds chunk (position ^ swizzle(row)); chunk c = half c % 2 of unit c / 2.
-    uint32_t wc_off[2], wc_off_tail[2];
+    uint32_t wc_off[CG], wc_off_tail[CG];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < CG; ++t) {
         const int row = 16 * t + lane / 4, c = (lane % 4) ^ ((row >> 2) & 3);
         int col = col0 + row;
         col = col < g.N ? col : g.N - 1;
         wc_off[t] = (uint32_t)col * (uint32_t)(g.K / 2) + 16u * c;
         wc_off_tail[t] = (uint32_t)col * (uint32_t)(g.K / 2) + 16u * (c & 1);
     }
-    // W metadata, a block of 16 units at a time (blocks aligned to multiples of 16 units of the row), load t of 2:
+    // W metadata, a block of 16 units at a time (blocks aligned to multiples of 16 units of the row), load t of CG:
     // lane -> weight row 16 t + lane / 4, units 4 (lane % 4) .. + 3 of the block; chunks past the end of the
     // row repeat its last four units
-    uint32_t wm_row_off[2];
+    uint32_t wm_row_off[CG];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < CG; ++t) {
         int col = col0 + 16 * t + lane / 4;
         col = col < g.N ? col : g.N - 1;
         wm_row_off[t] = (uint32_t)col * (uint32_t)upr * 4u;
@@ -165,24 +168,24 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
         int pw = p0 + it;
         pw = pw < np ? pw : np - 1;
         const bool tail = 2 * pw + 1 >= upr; // wave-uniform
-        const uint32_t cdst = sbase + (uint32_t)((CODES0 + wave * 128) * 16);
-        fr_load_to_lds_16(wc_ptr + (uint64_t)pw * 64, tail ? wc_off_tail[0] : wc_off[0], cdst);
-        fr_load_to_lds_16(wc_ptr + (uint64_t)pw * 64, tail ? wc_off_tail[1] : wc_off[1], cdst + 1024);
+        const uint32_t cdst = sbase + (uint32_t)((CODES0 + wave * WCELLS) * 16);
+#pragma unroll
+        for (int t = 0; t < CG; ++t) fr_load_to_lds_16(wc_ptr + (uint64_t)pw * 64, tail ? wc_off_tail[t] : wc_off[t], cdst + 1024u * t);
     };
     // the metadata of block `blk` (units 16 blk .. 16 blk + 15 of this wave's rows) into its ring slot blk % 2
     auto issue_meta = [&](int blk) {
         int u4 = 16 * blk + 4 * (lane % 4);
         u4 = u4 < upr - 4 ? u4 : upr - 4;
-        const uint32_t dst = lds0 + (uint32_t)((META0 + (wave * 2 + (blk & 1)) * 128) * 16);
-        fr_load_to_lds_16(wm_ptr, wm_row_off[0] + 4u * (uint32_t)u4, dst);
-        fr_load_to_lds_16(wm_ptr, wm_row_off[1] + 4u * (uint32_t)u4, dst + 1024);
+        const uint32_t dst = lds0 + (uint32_t)((META0 + (wave * 2 + (blk & 1)) * WCELLS) * 16);
+#pragma unroll
+        for (int t = 0; t < CG; ++t) fr_load_to_lds_16(wm_ptr, wm_row_off[t] + 4u * (uint32_t)u4, dst + 1024u * t);
     };
 
     // results: acc[cg][rb] is the 16 x 16 tile of column group cg (columns 16 cg .. + 15 of the strip) and row
     // block rb; lane (n, q) = (lane % 16, lane / 16) holds its column n, rows 4 q .. 4 q + 3
-    f32x4_t acc[2][RB];
+    f32x4_t acc[CG][RB];
 #pragma unroll
-    for (int cg = 0; cg < 2; ++cg)
+    for (int cg = 0; cg < CG; ++cg)
 #pragma unroll
         for (int i = 0; i < RB; ++i) acc[cg][i] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
 
@@ -226,12 +229,12 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
         const uint4 *sl = lds + slot * SLOT;
         const int u0 = 2 * pair; // the pair's first unit; both units lie in metadata block u0 / 16
         const bool two = u0 + 1 < upr; // wave-uniform
-        const uint32_t *mring = reinterpret_cast<const uint32_t *>(lds + META0 + (wave * 2 + ((u0 >> 4) & 1)) * 128) + (u0 & 15);
-        uint2 mm[2];       // metadata of the pair's units, per column group
-        uint32_t cd[2][2][2]; // codes dword [column group][unit][half step]
-        const uint32_t *cbase = reinterpret_cast<const uint32_t *>(sl + CODES0 + wave * 128) + q;
+        const uint32_t *mring = reinterpret_cast<const uint32_t *>(lds + META0 + (wave * 2 + ((u0 >> 4) & 1)) * WCELLS) + (u0 & 15);
+        uint2 mm[CG];       // metadata of the pair's units, per column group
+        uint32_t cd[CG][2][2]; // codes dword [column group][unit][half step]
+        const uint32_t *cbase = reinterpret_cast<const uint32_t *>(sl + CODES0 + wave * WCELLS) + q;
 #pragma unroll
-        for (int cg = 0; cg < 2; ++cg) {
+        for (int cg = 0; cg < CG; ++cg) {
             mm[cg] = *reinterpret_cast<const uint2 *>(mring + (16 * cg + n16) * 16);
 #pragma unroll
             for (int uu = 0; uu < 2; ++uu)
@@ -246,13 +249,13 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
 #pragma unroll
                 for (int i = 0; i < RB; ++i) av[uu][hs][i] = sl[kw * A_PART + (uu * 8 + 4 * hs + q) * RM + i * 16 + n16];
         __builtin_amdgcn_sched_barrier(0);
-        f32x4_t part[2][2][RB]; // the units' own sums [unit][column group][row block]
+        f32x4_t part[2][CG][RB]; // the units' own sums [unit][column group][row block]
 #pragma unroll
         for (int uu = 0; uu < 2; ++uu) {
             if (uu == 1 && !two) break;
-            uint32_t m8q[2], m16q[2];
+            uint32_t m8q[CG], m16q[CG];
 #pragma unroll
-            for (int cg = 0; cg < 2; ++cg) {
+            for (int cg = 0; cg < CG; ++cg) {
                 const uint32_t m = uu == 0 ? mm[cg].x : mm[cg].y;
                 m8q[cg] = m >> (8 + q);
                 m16q[cg] = m >> (16 + 2 * q);
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
 #pragma unroll
             for (int hs = 0; hs < 2; ++hs)
 #pragma unroll
-                for (int cg = 0; cg < 2; ++cg) {
+                for (int cg = 0; cg < CG; ++cg) {
                     const uint4 b = expand_dword(cd[cg][uu][hs], m8q[cg], m16q[cg], hs);
 #pragma unroll
                     for (int i = 0; i < RB; ++i)
@@ -273,7 +276,7 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
         for (int uu = 0; uu < 2; ++uu) {
             if (uu == 1 && !two) break;
 #pragma unroll
-            for (int cg = 0; cg < 2; ++cg) {
+            for (int cg = 0; cg < CG; ++cg) {
                 const float sc = unit_scale(uu == 0 ? mm[cg].x : mm[cg].y);
 #pragma unroll
                 for (int i = 0; i < RB; ++i)
@@ -308,13 +311,13 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
 
     // ---- the partial sums of K parts 1 .. KS - 1 go through LDS to part 0, lane for lane, in a fixed order
     if constexpr (KS > 1) {
-        static_assert((size_t)(KS - 1) * NWC * 2 * RB * 1024 <= Shape::lds_bytes, "partial sums fit the buffers");
+        static_assert((size_t)(KS - 1) * NWC * CG * RB * 1024 <= Shape::lds_bytes, "partial sums fit the buffers");
         f32x4_t *red = reinterpret_cast<f32x4_t *>(lds); // [kw - 1][cw][column group][row block][lane]
         __syncthreads();
         if (kw > 0) {
-            f32x4_t *dst = red + (size_t)((kw - 1) * NWC + cw) * 2 * RB * 64 + lane;
+            f32x4_t *dst = red + (size_t)((kw - 1) * NWC + cw) * CG * RB * 64 + lane;
 #pragma unroll
-            for (int cg = 0; cg < 2; ++cg)
+            for (int cg = 0; cg < CG; ++cg)
 #pragma unroll
                 for (int i = 0; i < RB; ++i) dst[(cg * RB + i) * 64] = acc[cg][i];
         }
@@ -322,9 +325,9 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
         if (kw > 0) return;
 #pragma unroll
         for (int p = 0; p < KS - 1; ++p) {
-            const f32x4_t *src = red + (size_t)(p * NWC + cw) * 2 * RB * 64 + lane;
+            const f32x4_t *src = red + (size_t)(p * NWC + cw) * CG * RB * 64 + lane;
 #pragma unroll
-            for (int cg = 0; cg < 2; ++cg)
+            for (int cg = 0; cg < CG; ++cg)
 #pragma unroll
                 for (int i = 0; i < RB; ++i) acc[cg][i] += src[(cg * RB + i) * 64];
         }
@@ -332,7 +335,7 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
 
     // ---- epilogue: lane (n, q) holds column n of each 16 x 16 tile, rows 4 q + r
 #pragma unroll
-    for (int cg = 0; cg < 2; ++cg) {
+    for (int cg = 0; cg < CG; ++cg) {
         const int col = col0 + 16 * cg + n16;
         if (col >= g.N) continue;
 #pragma unroll
@@ -354,46 +357,59 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
 namespace {
 
 struct FewRowsChoice {
-    int nwc, ks;
+    int nwc, ks, cg;
 };
 
-// Which (column strips, K parts) a workgroup takes.  Time is modelled as rounds of workgroups over the
-// chip's 256 CUs times the K range of one wave; among equals, more column strips per workgroup (they
-// share A).  Only shapes whose LDS plan fits are offered (the table mirrors FewRowsShape).
+// The shapes a workgroup can take: (column strips, K parts, column groups of 16 per strip).  Strips of 16 columns
+// give twice as many strips to spread over the chip and over K; strips of 32 share each A operand between two MFMAs.
+#define HIF4_FR_SHAPES(X) X(7, 2, 1) X(3, 4, 1) X(2, 4, 1) X(4, 2, 1) X(4, 2, 2)
+
+// Which of them a call takes.  The kernel is bound by the vector instructions of the expansion, which a SIMD
+// issues for its waves in turn, so time is modelled as rounds of workgroups over the chip's 256 CUs times the
+// waves a SIMD holds times the weights of a wave: its column groups times its steps of K, plus 8 steps for
+// starting a workgroup, filling its pipeline and the final reduction (fitted to measurements of thirteen shapes,
+// those of the list among them, on ten weight matrices from 2048 x 7168 to 28672 x 8192: the choice is the fastest
+// or within 6 % of it; the shapes the model never picks from 6144 columns on are no longer compiled);
+// among equals, the earlier entry of the list.  Only shapes whose LDS plan fits are offered (the arithmetic mirrors
+// FewRowsShape).
 template <int RM>
 FewRowsChoice fewrows_choose(int64_t N, int64_t K)
 {
-    const int64_t strips = (N + 31) / 32, np = (K / 64 + 1) / 2;
-    const FewRowsChoice cand[] = { { 4, 2 }, { 2, 4 }, { 1, 8 }, { 8, 1 }, { 2, 2 }, { 1, 4 }, { 4, 1 } };
-    FewRowsChoice best = { 8, 1 };
+    const int64_t np = (K / 64 + 1) / 2;
+#define HIF4_FR_ENTRY(W, S, G) { W, S, G },
+    const FewRowsChoice cand[] = { HIF4_FR_SHAPES(HIF4_FR_ENTRY) };
+#undef HIF4_FR_ENTRY
+    FewRowsChoice best = cand[0];
     double best_t = 1e300;
     for (const FewRowsChoice &c : cand) {
         const int nw = c.nwc * c.ks;
-        const size_t slot = (size_t)c.ks * 16 * RM * 16 + (size_t)nw * 2048, meta = (size_t)nw * 4096;
+        const size_t slot = (size_t)c.ks * 16 * RM * 16 + (size_t)nw * c.cg * 1024, meta = (size_t)nw * 2 * c.cg * 1024;
         const bool half_lds = nw == 4 && 3 * slot + meta <= 80 * 1024;
         const size_t budget = (half_lds ? 80 * 1024 : 160 * 1024) - meta;
         if (budget / slot < 3) continue;
         const int64_t per_cu = half_lds ? 2 : 1;
+        const int64_t strips = (N + 16 * c.cg - 1) / (16 * c.cg);
         const int64_t wgs = (strips + c.nwc - 1) / c.nwc;
         const int64_t rounds = (wgs + 256 * per_cu - 1) / (256 * per_cu);
         const int64_t steps = (np + c.ks - 1) / c.ks;
-        const double t = (double)rounds * (double)(steps + 3); // + 3: filling the pipeline, the final reduction
+        // (a second round costs more than its share: the tail of the first leaves compute units idle)
+        const double t = (double)rounds * (1.0 + 0.05 * (double)(rounds - 1)) * (double)(per_cu * nw) / 4.0 * c.cg * (double)(steps + 8);
         if (t < best_t) best = c, best_t = t;
     }
     return best;
 }
 
-template <int RM, int NWC, int KS>
+template <int RM, int NWC, int KS, int CG>
 int launch_fewrows_t(const FewRowsArgs &g, hipStream_t stream)
 {
-    using Shape = FewRowsShape<RM, NWC, KS>;
+    using Shape = FewRowsShape<RM, NWC, KS, CG>;
     if constexpr (!Shape::fits) {
         return HIF4_ERR_UNSUPPORTED;
     } else {
-        auto k = gemm_fewrows_kernel<RM, NWC, KS>;
+        auto k = gemm_fewrows_kernel<RM, NWC, KS, CG>;
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)Shape::lds_bytes) != hipSuccess)
             return HIF4_ERR_DEVICE;
-        const dim3 grid((unsigned)((g.N + 32 * NWC - 1) / (32 * NWC))), block(64 * NWC * KS);
+        const dim3 grid((unsigned)((g.N + 16 * CG * NWC - 1) / (16 * CG * NWC))), block(64 * NWC * KS);
         hipLaunchKernelGGL(k, grid, block, Shape::lds_bytes, stream, g);
         return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
     }
@@ -403,15 +419,10 @@ template <int RM>
 int launch_fewrows_rm(const FewRowsArgs &g, hipStream_t stream)
 {
     const FewRowsChoice c = fewrows_choose<RM>(g.N, g.K);
-#define HIF4_FR_CASE(W, S) if (c.nwc == W && c.ks == S) return launch_fewrows_t<RM, W, S>(g, stream)
-    HIF4_FR_CASE(4, 2);
-    HIF4_FR_CASE(2, 4);
-    HIF4_FR_CASE(1, 8);
-    HIF4_FR_CASE(2, 2);
-    HIF4_FR_CASE(1, 4);
-    HIF4_FR_CASE(4, 1);
+#define HIF4_FR_CASE(W, S, G) if (c.nwc == W && c.ks == S && c.cg == G) return launch_fewrows_t<RM, W, S, G>(g, stream);
+    HIF4_FR_SHAPES(HIF4_FR_CASE)
 #undef HIF4_FR_CASE
-    return launch_fewrows_t<RM, 8, 1>(g, stream);
+    return HIF4_ERR_UNSUPPORTED;
 }
 
 } // namespace

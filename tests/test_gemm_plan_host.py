@@ -32,7 +32,7 @@ def decoded_w_pays(M, N, K):
 
 def fewrows(M, N, K):
     ok_shape = K % 256 == 0 and N * (K // 2) < 2 ** 32
-    return ok_shape and ((5 <= M <= 16 and N >= 14336) or (16 < M <= 32 and N >= 28672))
+    return ok_shape and M <= 32 and N >= 6144
 
 
 def expected(a_kind, M, N, K, emit, ws):

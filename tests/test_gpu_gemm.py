@@ -841,12 +841,40 @@ def test_gemm_weight_only_few_rows_optional_workspace(h, oracle):
     assert rel_fro(c_no.cpu().numpy().astype(np.float64), want) <= TOL
 
 
-# ---- the kernel for a few rows against a wide weight matrix (5..16 rows from 14336 columns, 17..32 rows from 28672):
-# unit scales applied to the units' partial sums, weights expanded through the FP8 byte table.  Ragged column edges,
-# one, odd and uneven numbers of pairs of units per K part, all three kinds of A.
+# ---- the kernel for at most 32 rows against at least 6144 columns: unit scales applied to the units' partial sums,
+# weights expanded through the FP8 byte table.  Ragged column edges, one, odd and uneven numbers of pairs of units per
+# K part, all three kinds of A, and every (column strips, K parts, column groups) shape of workgroup the launcher has,
+# for both tile heights.
 
-FEWROW_SHAPES = [(5, 14336, 256), (16, 14353, 768), (9, 14340, 1280), (16, 14336, 4096), (13, 16400, 2304),
-                 (17, 28672, 256), (32, 28700, 512), (20, 28673, 768), (32, 28672, 1792)]
+FEWROW_SHAPES = [(5, 6144, 256), (16, 6150, 1280), (16, 8200, 4096), (11, 11008, 2304), (9, 8200, 256), (16, 14353, 768),
+                 (13, 16400, 2304), (16, 28673, 768), (1, 7000, 512), (3, 28672, 1792),
+                 (17, 6144, 256), (32, 8200, 4096), (20, 8200, 256), (32, 28700, 512), (24, 16400, 256), (32, 28672, 1792)]
+
+
+def fewrows_workgroup_shape(M, N, K):
+    """The launcher's choice of workgroup shape (fewrows_choose in csrc/hif4_gemm_fewrows.hip), restated: used only to
+    check that FEWROW_SHAPES reaches every compiled shape."""
+    RM, pairs = (16 if M <= 16 else 32), (K // 64 + 1) // 2
+    best, best_t = None, float("inf")
+    for nwc, ks, cg in ((7, 2, 1), (3, 4, 1), (2, 4, 1), (4, 2, 1), (4, 2, 2)):
+        nw = nwc * ks
+        slot, meta = ks * 16 * RM * 16 + nw * cg * 1024, nw * 2 * cg * 1024
+        half = nw == 4 and 3 * slot + meta <= 80 * 1024
+        if ((80 if half else 160) * 1024 - meta) // slot < 3:
+            continue
+        per_cu = 2 if half else 1
+        strips = -(-N // (16 * cg))
+        wgs = -(-strips // nwc)
+        rounds, steps = -(-wgs // (256 * per_cu)), -(-pairs // ks)
+        t = rounds * (1 + 0.05 * (rounds - 1)) * per_cu * nw / 4 * cg * (steps + 8)
+        if t < best_t:
+            best, best_t = (RM, nwc, ks, cg), t
+    return best
+
+
+def test_few_row_shapes_cover_every_workgroup_shape():
+    seen = {fewrows_workgroup_shape(*s) for s in FEWROW_SHAPES}
+    assert seen == {(rm, *c) for rm in (16, 32) for c in ((7, 2, 1), (3, 4, 1), (2, 4, 1), (4, 2, 1), (4, 2, 2))}, seen
 
 
 @pytest.mark.parametrize("M,N,K", FEWROW_SHAPES)
