@@ -78,10 +78,11 @@ enum { COLWAVE_BF16 = 0, COLWAVE_F32 = 1, COLWAVE_EMIT = 2 };
 // it), NB buffers of A, a ring of R steps of packed W.
 template <int NW, int KS, int NB, int R>
 struct ColwaveShape {
-    static constexpr size_t lds_bytes(int tmax)
+    // mblk: metadata in blocks of 8 units (two blocks of 32 rows per wave) instead of a word per lane and ring step
+    static constexpr size_t lds_bytes(int tmax, bool mblk)
     {
         const int rg = (32 * tmax + 63) / 64;
-        return (size_t)NB * KS * 8 * 64 * rg * 16 + (size_t)R * NW * 64 * (16 + 4);
+        return (size_t)NB * KS * 8 * 64 * rg * 16 + (size_t)R * NW * 64 * 16 + (mblk ? (size_t)NW * 2048 : (size_t)R * NW * 64 * 4);
     }
 };
 
@@ -89,7 +90,7 @@ struct ColwaveShape {
 // units [kw K/64/KS, (kw + 1) K/64/KS) - and their partial sums meet in LDS after the loop.  With few
 // rows and not many columns there are too few 32-column strips to give every SIMD its two waves,
 // and a wave alone cannot issue faster than it does; K is the only other axis to cut.
-template <int TMAX, int NW, int KS, int NB, int R, int WPS, int OUT>
+template <int TMAX, int NW, int KS, int NB, int R, int WPS, int OUT, bool MBLK>
 __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs g)
 {
     constexpr bool OUT_F32 = OUT == COLWAVE_F32, EMIT = OUT >= COLWAVE_EMIT;
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     extern __shared__ uint4 lds[];
     uint4 *lds_a = lds;                                  // [NB][KS][8][BMP]
     uint4 *lds_wc = lds + NB * KS * A_CELLS;             // [R][NW][64]
-    uint32_t *lds_wm = reinterpret_cast<uint32_t *>(lds_wc + R * NW * 64); // [R][NW][64]
+    uint32_t *lds_wm = reinterpret_cast<uint32_t *>(lds_wc + R * NW * 64); // [R][NW][64], or MBLK: [NW][2 blocks][32 rows][8 units]
 
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -148,7 +149,17 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     int wrow = col0 + cw * 32 + l32;
     wrow = wrow < g.N ? wrow : g.N - 1;
     const uint32_t wc_off = (uint32_t)wrow * (uint32_t)(g.K / 2) + 16u * half + (uint32_t)u0 * 32u;
-    const uint32_t wm_off = (uint32_t)wrow * (uint32_t)(g.K / 16) + (uint32_t)u0 * 4u;
+    // Metadata.  MBLK: blocks of 8 units of the wave's 32 rows, one load of 8 rows x 8 units (32-byte runs) per step, see
+    // issue_w; lane -> row lane / 8 of the load's 8, unit lane % 8 of the block (a K range of fewer than 8 units repeats
+    // its last one).  Rows past N - 1 take row N - 1: the byte offset is capped at that row's (it grows with the row).
+    // Otherwise the unit's word per lane and step.
+    const int mj = lane % 8 < nk ? lane % 8 : nk - 1;
+    const uint32_t wm_stride8 = (uint32_t)(g.K / 16) * 8u; // bytes between rows r and r + 8
+    const uint32_t wm_off = MBLK ? (uint32_t)(col0 + cw * 32 + lane / 8) * (uint32_t)(g.K / 16) + (uint32_t)(u0 + mj) * 4u
+                                 : (uint32_t)wrow * (uint32_t)(g.K / 16) + (uint32_t)u0 * 4u;
+    const uint32_t wm_off_cap = (uint32_t)(g.N - 1) * (uint32_t)(g.K / 16) + (uint32_t)(u0 + mj) * 4u;
+    // first unit of metadata block b of this wave's K range: the last block is moved back to end with the range
+    auto mblk_start = [&](int b) { const int s8 = 8 * b; return nk >= 8 ? (s8 < nk - 8 ? s8 : nk - 8) : 0; };
     uint32_t a_off[IA], a_dst[IA];
 #pragma unroll
     for (int i = 0; i < IA; ++i) {
@@ -163,15 +174,31 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     auto lds_byte_of = [](const void *p) { return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p; };
     const uint32_t a_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_a));
     const uint32_t wc_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_wc)) + (uint32_t)(wave * 64 * 16);
-    const uint32_t wm_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_wm)) + (uint32_t)(wave * 64 * 4);
+    const uint32_t wm_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_wm)) + (uint32_t)(wave * (MBLK ? 2048 : 64 * 4));
     const uint64_t a_step = (uint64_t)g.M * 128; // bytes of A planes per K step
     const uint64_t wc_ptr = cw_uniform((uint64_t)(uintptr_t)w_codes), wm_ptr = cw_uniform((uint64_t)(uintptr_t)w_meta);
     const uint64_t a_ptr = cw_uniform((uint64_t)(uintptr_t)g.a_planes);
     // the loads of unit u into ring slot / buffer number `at`: steps past the end of K repeat the last one (never used)
+    // MBLK: the load of 8 rows x 8 units of metadata that goes with it belongs to block b = (u - R + 9) / 8, rows
+    // 8 t .. 8 t + 7 with t = (u - R + 9) % 4: in step k = u - R of the main loop, block b is written during steps
+    // 8 b - 9 .. 8 b - 2 (each quarter twice, the same bytes), after the last read of block b - 2 in the same slot
+    // (unit 8 b - 9, read in step 8 b - 10) and complete with the load of step 8 b - 6, which every wait from step
+    // 8 b - 6 + NB on covers (NB <= 3; the block's first unit is read in step 8 b - 1).  One load per step, so the
+    // count of loads per step stays what the waits assume.
+    auto issue_meta_block = [&](int b, int t) {
+        uint32_t off = wm_off + (uint32_t)t * wm_stride8;
+        off = off < wm_off_cap ? off : wm_off_cap;
+        cw_load_to_lds_4(wm_ptr + (uint64_t)mblk_start(b) * 4, off, wm_base + (uint32_t)((b & 1) * 1024 + t * 256));
+    };
     auto issue_w = [&](int u, int at) {
         const uint64_t uc = (uint64_t)(u < nk ? u : nk - 1);
         cw_load_to_lds_16(wc_ptr + uc * 32, wc_off, wc_base + (uint32_t)(at * NW * 64 * 16));
-        cw_load_to_lds_4(wm_ptr + uc * 4, wm_off, wm_base + (uint32_t)(at * NW * 64 * 4));
+        if constexpr (MBLK) {
+            const int x = u - R + 9; // >= 9 - R > 0
+            issue_meta_block(x >> 3, x & 3);
+        } else {
+            cw_load_to_lds_4(wm_ptr + uc * 4, wm_off, wm_base + (uint32_t)(at * NW * 64 * 4));
+        }
     };
     auto issue_a = [&](int u, int at) {
         const uint64_t base = a_ptr + (uint64_t)(u < nk ? u : nk - 1) * a_step;
@@ -191,9 +218,16 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
         uint32_t m8, m16; // the unit's level-2 and level-3 bits, shifted so that bit 0 belongs to group 4 h
         uint32_t sbase;  // fp32 pattern of the unit scale
     };
-    auto read_w = [&](UnitW &uw, int slot) {
+    const uint32_t *lds_wm_lane = lds_wm + wave * 512 + l32 * 8; // MBLK: this lane's row in block slot 0
+    auto read_w = [&](UnitW &uw, int slot, int u) { // ring slot and number (in the wave's K range) of the unit
         const uint4 cw = lds_wc[(slot * NW + wave) * 64 + lane];
-        const uint32_t m = lds_wm[(slot * NW + wave) * 64 + lane];
+        uint32_t m;
+        if constexpr (MBLK) {
+            const int uc = u < nk ? u : nk - 1, b = uc >> 3;
+            m = lds_wm_lane[(b & 1) * 256 + uc - mblk_start(b)];
+        } else {
+            m = lds_wm[(slot * NW + wave) * 64 + lane];
+        }
         uw.c[0] = cw.x, uw.c[1] = cw.y, uw.c[2] = cw.z, uw.c[3] = cw.w;
         uw.m8 = m >> (8 + 4 * half);
         uw.m16 = m >> (16 + 8 * half);
@@ -213,6 +247,10 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
 
     // ---- prologue.  After the barrier of step k the loop issues the group [A(k + NB), W(k + R)]; the
     // same groups for k < 0 start the pipeline, so that the loads in flight are always the same ones.
+    if constexpr (MBLK) { // the first block of metadata, whole, before everything else
+#pragma unroll
+        for (int t = 0; t < 4; ++t) issue_meta_block(0, t);
+    }
 #pragma unroll
     for (int u = 0; u < R - NB; ++u) issue_w(u, u);
 #pragma unroll
@@ -271,7 +309,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
             bcur = bnext;
         };
 
-        read_w(uw, 0);
+        read_w(uw, 0, 0);
         cs = begin(uw, 0);
         bcur.x = chunk_pair<0>(cs);
         bcur.y = chunk_pair<1>(cs);
@@ -291,7 +329,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
             __syncthreads(); // every wave holds its last operands of buffer `buf`, which may now be refilled
             issue_a(k + NB, buf);
             issue_w(k + R, slot);
-            read_w(uw, nslot);
+            read_w(uw, nslot, k + 1);
             sub_step(1, 0, nbuf, 0);
             buf = nbuf;
             slot = nslot;
@@ -313,7 +351,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     // ---- KS > 1: the partial sums of wave groups 1 .. KS - 1 go through LDS (all loads have landed and
     // all operands are read once every wave is past the barrier) to group 0, lane for lane
     if constexpr (KS > 1) {
-        static_assert((size_t)(KS - 1) * NWC * TMAX * 4096 <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX), "partial sums fit the buffers");
+        static_assert((size_t)(KS - 1) * NWC * TMAX * 4096 <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK), "partial sums fit the buffers");
         float4 *red = reinterpret_cast<float4 *>(lds); // [kw - 1][cw][block][4][lane]
         __syncthreads();
         if (kw > 0) {
@@ -348,7 +386,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     // row-major by the waves that hold it, then every thread of the workgroup encodes units of 64 columns
     if constexpr (EMIT) {
         static_assert(BN % 64 == 0, "whole units across a tile");
-        static_assert(emit_lds_bytes<BM, BN>() <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX), "the parked tile fits the buffers");
+        static_assert(emit_lds_bytes<BM, BN>() <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK), "the parked tile fits the buffers");
         constexpr int RS = BN + 8; // row stride in BF16 elements
         uint16_t *tile = reinterpret_cast<uint16_t *>(lds);
         __syncthreads(); // all operand reads and loads are done (KS > 1: and group 0 has read the partial sums)
@@ -396,15 +434,21 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
 #ifndef HIF4_COLWAVE_NW_DENSE
 #define HIF4_COLWAVE_NW_DENSE 4
 #endif
+#ifndef HIF4_COLWAVE_MBLK
+#define HIF4_COLWAVE_MBLK 1
+#endif
 // EMIT_OK: also instantiate the kernels that write the result as HiF4
 template <int TMAX, int NW, int KS, bool EMIT_OK = false>
 static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
 {
-    // three buffers of A and four steps of W where LDS has room for them, else two and three
-    constexpr bool DEEP = ColwaveShape<NW, KS, HIF4_COLWAVE_NB, HIF4_COLWAVE_R>::lds_bytes(TMAX) <= 160 * 1024;
+    // three buffers of A and four steps of W where LDS has room for them, else two and three; metadata in blocks of 8
+    // units (a quarter of the cache lines fetched per step) where that fits as well
+    constexpr size_t LDS_MAX = 160 * 1024;
+    constexpr bool DEEP = ColwaveShape<NW, KS, HIF4_COLWAVE_NB, HIF4_COLWAVE_R>::lds_bytes(TMAX, false) <= LDS_MAX;
     constexpr int NB = DEEP ? HIF4_COLWAVE_NB : 2, R = DEEP ? HIF4_COLWAVE_R : 3, WPS = HIF4_COLWAVE_WPS;
+    constexpr bool MBLK = HIF4_COLWAVE_MBLK && ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, true) <= LDS_MAX;
     constexpr int BM = 32 * TMAX, BN = 32 * NW / KS;
-    constexpr size_t lds_bytes = ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX);
+    constexpr size_t lds_bytes = ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK);
     static_assert(lds_bytes <= 160 * 1024, "fits the LDS of one CU");
     g.tiles_n = (g.N + BN - 1) / BN;
     g.tiles_m = g.offs ? g.M / BM + g.E : (g.M + BM - 1) / BM; // grouped: upper bound of sum_e ceil(rows_e / BM)
@@ -416,11 +460,11 @@ static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
         return true;
     };
     bool ok;
-    if (out_dtype == HIF4_OUT_F32) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_F32>);
-    else if (out_dtype == HIF4_OUT_BF16) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_BF16>);
+    if (out_dtype == HIF4_OUT_F32) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_F32, MBLK>);
+    else if (out_dtype == HIF4_OUT_BF16) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_BF16, MBLK>);
     else if constexpr (EMIT_OK && BN % 64 == 0) { // 16 + rounding mode: the result as HiF4 (the launcher below picks shapes that allow it)
-        ok = out_dtype == 16 + HIF4_ROUND_RNE ? launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RNE>)
-                                              : launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RHA>);
+        ok = out_dtype == 16 + HIF4_ROUND_RNE ? launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RNE, MBLK>)
+                                              : launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RHA, MBLK>);
     } else return HIF4_ERR_UNSUPPORTED;
     if (!ok) return HIF4_ERR_DEVICE;
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
