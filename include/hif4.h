@@ -257,6 +257,17 @@ int hif4_gemm_plan(int a_kind, int experts, int64_t M_or_total_rows, int64_t N, 
 /* Static host string naming a HIF4_PLAN_* value (the kernel's name in the sources). */
 const char *hif4_gemm_plan_name(int plan);
 
+/*
+ * How a HIF4_PLAN_PLANES call of M rows and N columns is cut into launches (host function, nothing is launched).  One
+ * workgroup per 256-row tile holds a compute unit, so a last round of tiles that is mostly empty costs a full one; the
+ * library then runs whole rounds of 256-column tiles first and the remaining columns in narrower tiles that fill one
+ * more round.  Every output keeps the order of its additions over K, so results do not depend on the cut.
+ *   main_tile_columns  out: tile columns of 256 in the first launch (0: there is only one launch)
+ *   tail_tile_width    out: tile width of the launch that takes the remaining columns: 256, 192 or 128
+ * Returns HIF4_OK, HIF4_ERR_NULL or HIF4_ERR_SHAPE.
+ */
+int hif4_gemm_plan_planes_split(int64_t M, int64_t N, int *main_tile_columns, int *tail_tile_width);
+
 /* Static host string naming a status code. */
 const char *hif4_status_string(int status);
 

@@ -26,6 +26,10 @@ int launch_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_c
                       int64_t K, void *c, int64_t ldc, int out_dtype, hipStream_t stream);
 int launch_mfma_loop(int kind, int iters, float *out, hipStream_t stream);
 int gemm_plan(int a_kind, bool grouped, int E, int64_t M, int64_t N, int64_t K, int64_t lda, bool emit, bool ws_ok, size_t ws_bytes);
+struct PlanesSplit {
+    int main_tile_cols, tail_bn;
+};
+PlanesSplit planes_split(int64_t M, int64_t N);
 size_t gemm_workspace_bytes(int a_kind, int64_t M, int64_t K);
 size_t gemm_workspace_bytes_decoded_w(int a_kind, int64_t M, int64_t N, int64_t K);
 } // namespace hif4
@@ -315,6 +319,16 @@ int hif4_gemm_plan(int a_kind, int experts, int64_t M, int64_t N, int64_t K, int
     if (result_as_hif4 && N % HIF4_UNIT != 0) return HIF4_ERR_SHAPE;
     if (workspace_bytes < hif4_gemm_workspace_bytes(a_kind, M, K)) return HIF4_ERR_WORKSPACE;
     return hif4::gemm_plan(a_kind, experts > 0, experts, M, N, K, K, result_as_hif4 != 0, workspace_bytes > 0, workspace_bytes);
+}
+
+int hif4_gemm_plan_planes_split(int64_t M, int64_t N, int *main_tile_columns, int *tail_tile_width)
+{
+    if (!main_tile_columns || !tail_tile_width) return HIF4_ERR_NULL;
+    if (M < 0 || N < 0 || M >= MAX_DIM || N >= MAX_DIM) return HIF4_ERR_SHAPE;
+    const hif4::PlanesSplit sp = hif4::planes_split(M, N);
+    *main_tile_columns = sp.main_tile_cols;
+    *tail_tile_width = sp.tail_bn;
+    return HIF4_OK;
 }
 
 const char *hif4_gemm_plan_name(int plan)

@@ -99,4 +99,29 @@ __device__ __forceinline__ void store4(uint32_t *p, uint32_t v)
     else *p = v;
 }
 
+// Block -> tile of the dense tile kernels.  Workgroups are dealt to the 8 XCDs round-robin (block b runs on
+// XCD b % 8) and each XCD has its own L2, so every XCD gets one contiguous run of the tile list, and the list
+// walks the tiles_m x tiles_n grid in bands of 4 tile rows, each band in super-tiles of 4 x 8 tiles (fewer rows
+// in the last band, fewer columns in a band's last super-tile): the ~32 workgroups an XCD runs at a time then
+// share A rows 8 ways and W rows 4 ways in its L2.  The list holds the grid's tiles only, so the 8 runs are
+// equal to within one tile whatever the grid's shape; the grid is tiles_m * tiles_n rounded up to 8 blocks
+// (dense_tile_blocks), the surplus blocks get false.
+__host__ __device__ inline int64_t dense_tile_blocks(int tiles_m, int tiles_n) { return ((int64_t)tiles_m * tiles_n + 7) / 8 * 8; }
+
+__device__ __forceinline__ bool dense_tile_of_block(int tiles_m, int tiles_n, int &tile_m, int &tile_n)
+{
+    const int per_xcd = (int)(gridDim.x / 8);
+    const int t = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
+    if (t >= tiles_m * tiles_n) return false;
+    const int band = t / (4 * tiles_n), i = t - band * 4 * tiles_n;
+    const int hb = tiles_m - 4 * band < 4 ? tiles_m - 4 * band : 4; // tile rows of this band
+    const int full = tiles_n / 8;                                    // its super-tiles of 8 columns
+    int sc = i / (hb * 8), wb = 8;
+    if (sc >= full) sc = full, wb = tiles_n - 8 * full;
+    const int r = i - sc * hb * 8;
+    tile_m = 4 * band + r / wb;
+    tile_n = 8 * sc + r % wb;
+    return true;
+}
+
 } // namespace hif4

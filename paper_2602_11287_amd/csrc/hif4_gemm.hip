@@ -68,11 +68,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_kernel(GemmArgs g)
     int row0, rows_end; // this tile covers rows [row0, min(row0 + BM, rows_end)) of A and C
     const uint32_t *w_codes = g.w_codes;
     const uint32_t *w_meta = g.w_meta;
-    // Block -> tile.  Workgroups are dealt to the 8 XCDs round-robin (block b runs on XCD b % 8)
-    // and each XCD has its own L2, so every XCD gets one contiguous run of the tile list, and
-    // the list walks the tile grid in super-tiles of GM x GN tiles: the ~32 workgroups an XCD
-    // runs at a time then share A rows 8 ways and W rows 4 ways in its L2.
-    constexpr int GM = 4, GN = 8, XCDS = 8;
+    // Block -> tile: see dense_tile_of_block.
+    constexpr int XCDS = 8;
     int tile_m, tile_n;
     if (GROUPED) {
         // The tile list of a grouped GEMM ends in an unknown number of empty m-tiles (the grid
@@ -83,13 +80,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_kernel(GemmArgs g)
         tile_n = i % g.tiles_n;
         if (tile_m >= g.tiles_m) return;
     } else {
-        const int per_xcd = (int)(gridDim.x / XCDS);
-        const int t = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
-        const int sn = (g.tiles_n + GN - 1) / GN;
-        const int st = t / (GM * GN), within = t % (GM * GN);
-        tile_n = (st % sn) * GN + within % GN;
-        tile_m = (st / sn) * GM + within / GN;
-        if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return; // padding of the super-tile grid
+        if (!dense_tile_of_block(g.tiles_m, g.tiles_n, tile_m, tile_n)) return;
     }
     if (GROUPED) {
         int e;
@@ -498,9 +489,9 @@ static int launch_tiles(GemmArgs g, int out_dtype, int m_tiles, hipStream_t stre
     g.tiles_m = m_tiles;
     constexpr size_t loop_bytes = 2 * (8 * (BM + BN) + 8) * sizeof(uint4);
     constexpr size_t lds_bytes = loop_bytes;
-    // the super-tile grid (4 x 8 tiles), padded, split evenly over the 8 XCDs: see the kernel
-    const int64_t padded = GROUPED ? (int64_t)((m_tiles + 7) / 8) * 8 * g.tiles_n
-                                   : (int64_t)((m_tiles + 3) / 4) * ((g.tiles_n + 7) / 8) * 32;
+    // grouped: whole rounds of 8 m-tiles; dense: the tiles themselves, split evenly over the 8 XCDs (see the kernel)
+    const int64_t padded = GROUPED ? (int64_t)((m_tiles + 7) / 8) * 8 * g.tiles_n : dense_tile_blocks(m_tiles, g.tiles_n);
+    if (padded > 0x7FFFFFFF) return HIF4_ERR_SHAPE;
     const dim3 grid((unsigned)((padded + 7) / 8 * 8)), block(64 * WM * WN);
     hipError_t e;
     {

@@ -115,7 +115,8 @@ struct PlaneGemmArgs {
     uint32_t *c_meta; // EMIT kernels: c is the codes plane of the HiF4 result, this its metadata plane
     int64_t ldc;
     int M, N, K;
-    int tiles_m, tiles_n;
+    int tiles_m, tiles_n; // tiles of this launch
+    int col_base;         // its first column of W / of C (a launch may cover a range of columns only, see launch_planes)
 };
 
 // MX = false: BF16 cells, a K step is 64 wide and a quarter is one v_mfma_f32_32x32x16_bf16.
@@ -139,19 +140,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
     const int wave = tid / 64, lane = tid % 64;
     const int wm = wave / WN, wn = wave % WN;
 
-    // Block -> tile: every XCD (block b runs on XCD b % 8, each with its own L2) gets one
-    // contiguous run of the tile list, and the list walks the tile grid in super-tiles of
-    // GM x GN tiles, so the ~32 workgroups an XCD runs at a time share A rows 8 ways and W rows
-    // 4 ways in its L2.
-    constexpr int GM = 4, GN = 8, XCDS = 8;
-    const int per_xcd = (int)(gridDim.x / XCDS);
-    const int t = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
-    const int sn = (g.tiles_n + GN - 1) / GN;
-    const int stile = t / (GM * GN), within = t % (GM * GN);
-    const int tile_n = (stile % sn) * GN + within % GN;
-    const int tile_m = (stile / sn) * GM + within / GN;
-    if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return; // padding of the super-tile grid
-    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    int tile_m, tile_n; // see dense_tile_of_block
+    if (!dense_tile_of_block(g.tiles_m, g.tiles_n, tile_m, tile_n)) return;
+    const int row0 = tile_m * BM, col0 = g.col_base + tile_n * BN;
     const int nk = g.K / KSTEP;
 
     // ---- staging plan of this wave: load i moves cells (group j, rows rb*64 .. rb*64+63); rows
@@ -340,7 +331,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
 {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM / 16, TN = BN / WN / 16; // 16 x 16 tiles per wave
-    static_assert(TM == 8 && TN == 4, "two phases of four tile rows per half step");
+    static_assert(TM == 8 && TN >= 2 && TN <= 4, "two phases of four tile rows per half step; 32 to 64 columns per wave");
     constexpr int W_BASE = 8 * BM, CELLS = 8 * (BM + BN);
     constexpr int IA = 8 * BM / 64 / NW, IW = 8 * BN / 64 / NW;
     extern __shared__ uint4 lds[]; // 2 buffers x CELLS
@@ -349,15 +340,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
     const int wave = tid / 64, lane = tid % 64;
     const int wm = wave / WN, wn = wave % WN;
 
-    constexpr int GM = 4, GN = 8, XCDS = 8; // see gemm_planes_kernel
-    const int per_xcd = (int)(gridDim.x / XCDS);
-    const int t = (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS);
-    const int sn = (g.tiles_n + GN - 1) / GN;
-    const int stile = t / (GM * GN), within = t % (GM * GN);
-    const int tile_n = (stile % sn) * GN + within % GN;
-    const int tile_m = (stile / sn) * GM + within / GN;
-    if (tile_n >= g.tiles_n || tile_m >= g.tiles_m) return;
-    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    int tile_m, tile_n;
+    if (!dense_tile_of_block(g.tiles_m, g.tiles_n, tile_m, tile_n)) return;
+    const int row0 = tile_m * BM, col0 = g.col_base + tile_n * BN;
     const int nk = g.K / 64;
 
     const uint4 *a_src[IA], *w_src[IW];
@@ -403,15 +388,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
     const int q = lane / 16, n = lane % 16;
     // operands of two phases (4 tile rows of A each) and of two half steps (4 tile columns of W each);
     // the sets the first phase works on start as zeros
-    uint4 af[2][4], bfr[2][4];
+    uint4 af[2][4], bfr[2][TN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) af[1][i] = bfr[1][i] = make_uint4(0, 0, 0, 0);
-    auto mfma_phase = [&](int ph) { // the 16 MFMAs of phase ph = 2 hs + ab: tile rows 4 ab .. 4 ab + 3, operands of half step hs
+    for (int i = 0; i < 4; ++i) af[1][i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) bfr[1][i] = make_uint4(0, 0, 0, 0);
+    auto mfma_phase = [&](int ph) { // the 4 TN MFMAs of phase ph = 2 hs + ab: tile rows 4 ab .. 4 ab + 3, operands of half step hs
         const int hs = ph / 2, ab = ph % 2;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < TN; ++j)
                 acc[4 * ab + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, af[ph & 1][i]), __builtin_bit_cast(bf16x8_t, bfr[hs & 1][j]),
                                                                              acc[4 * ab + i][j], 0, 0, 0);
     };
@@ -425,7 +412,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
             for (int i = 0; i < 4; ++i) af[ph & 1][i] = abase[j * BM + (4 * ab + i) * 16];
             if (ab == 0) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) bfr[hs & 1][i] = bbase[j * BN + i * 16];
+                for (int i = 0; i < TN; ++i) bfr[hs & 1][i] = bbase[j * BN + i * 16];
             }
             __builtin_amdgcn_sched_barrier(0);
             mfma_phase((ph + 3) & 3);
@@ -478,6 +465,81 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
 #define HIF4_PLANES_MFMA16 1
 #endif
 
+// ---- the last, partly filled round of a launch.  A workgroup holds a CU to itself, so a launch of T tiles runs
+// in ceil(T / 256) rounds (per XCD: of its share of the tiles on its 32 CUs), and a last round that is two thirds
+// empty costs as much as a full one: 4096 x 11008 is 688 tiles, 2.69 rounds of work in 3 rounds of time.  The remedy
+// here keeps one workgroup per tile and the order of every output's additions over K (so the bits of the result do
+// not depend on it): the columns are cut in two ranges, whole rounds of 256-column tiles first, then the rest in
+// narrower tiles (192 or 128 columns, 48 or 32 per wave) that fill one more round, as a second launch behind the first.
+// 4096 x 11008: 32 tile columns of 256 (512 tiles, two rounds), then 2816 columns as 15 x 16 tiles of 192.
+struct PlanesSplit {
+    int main_tile_cols; // tile columns of 256 in the first launch (0: none)
+    int tail_bn;        // tile width of the launch that takes the other columns: 256 (one launch for all), 192 or 128
+};
+
+// Rounds a launch of `tiles` tiles runs: its blocks are dealt to the 8 XCDs in equal shares (dense_tile_of_block),
+// each XCD has 32 CUs and a workgroup holds a CU to itself.
+static int64_t planes_rounds(int64_t tiles)
+{
+    return ((tiles + 7) / 8 + 31) / 32;
+}
+
+// Time of a narrower tile's round in units of a 256-column tile's (measured on MI355X, K steps of 256 x 192 and
+// 256 x 128 tiles against 256 x 256), and of the gap between the two launches.
+#ifndef HIF4_PLANES_REL192
+#define HIF4_PLANES_REL192 0.80
+#define HIF4_PLANES_REL128 0.60
+#define HIF4_PLANES_GAP 0.04
+#endif
+
+// Which split a call of M x N takes: the cheapest by that model among no split and, for each narrower width, the
+// most whole rounds of 256-column tiles that leave a tail; a split must save at least 3 %.  Pure host function.
+PlanesSplit planes_split(int64_t M, int64_t N)
+{
+    const PlanesSplit none = { 0, 256 };
+    const int64_t tm = (M + 255) / 256, tn = (N + 255) / 256;
+    if (!HIF4_PLANES_MFMA16 || tm * tn <= 256 || tm * tn > 16 * 256 || tm > 1024) return none; // one round anyway, or a tail that is small change
+    const double t_none = (double)planes_rounds(tm * tn);
+    PlanesSplit best = none;
+    double t_best = t_none * 0.97;
+    const int widths[2] = { 192, 128 };
+    const double rel[2] = { HIF4_PLANES_REL192, HIF4_PLANES_REL128 };
+    // candidates for the first launch: the most tile columns that make the last or last but one whole number of rounds
+    const int64_t full = tm * tn / 256;
+    int64_t cand[2];
+    int nc = 0;
+    for (int64_t k = full; k >= 0 && k + 1 >= full; --k) cand[nc++] = k * 256 / tm;
+    for (int wi = 0; wi < 2; ++wi)
+        for (int ci = 0; ci < nc; ++ci) {
+            const int64_t c = cand[ci];
+            if (c >= tn) continue;
+            const int64_t tail_cols = N - 256 * c, tt = (tail_cols + widths[wi] - 1) / widths[wi];
+            const double t = (double)planes_rounds(tm * c) + rel[wi] * (double)planes_rounds(tm * tt) + (c > 0 ? HIF4_PLANES_GAP : 0.0);
+            if (t < t_best) best = { (int)c, widths[wi] }, t_best = t;
+        }
+    return best;
+}
+
+template <int BN>
+static int launch_planes16(PlaneGemmArgs g, int out_dtype, hipStream_t stream) // tiles_m, tiles_n, col_base are set
+{
+    constexpr int BM = 256, WM = 2, WN = 4;
+    constexpr size_t lds_bytes = 2 * 8 * (BM + BN) * sizeof(uint4);
+    constexpr size_t emit_bytes = emit_lds_bytes<BM, BN>() > lds_bytes ? emit_lds_bytes<BM, BN>() : lds_bytes;
+    static_assert(emit_bytes <= 160 * 1024, "fits the LDS of one CU");
+    if (dense_tile_blocks(g.tiles_m, g.tiles_n) > 0x7FFFFFFF) return HIF4_ERR_SHAPE;
+    const dim3 grid((unsigned)dense_tile_blocks(g.tiles_m, g.tiles_n)), block(64 * WM * WN);
+    auto launch = [&](auto k, size_t bytes) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return HIF4_ERR_DEVICE;
+        hipLaunchKernelGGL(k, grid, block, bytes, stream, g);
+        return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
+    };
+    if (out_dtype == 16 + HIF4_ROUND_RNE) return launch(gemm_planes16_kernel<BM, BN, WM, WN, false, HIF4_ROUND_RNE>, emit_bytes);
+    if (out_dtype == 16 + HIF4_ROUND_RHA) return launch(gemm_planes16_kernel<BM, BN, WM, WN, false, HIF4_ROUND_RHA>, emit_bytes);
+    if (out_dtype == HIF4_OUT_F32) return launch(gemm_planes16_kernel<BM, BN, WM, WN, true>, lds_bytes);
+    return launch(gemm_planes16_kernel<BM, BN, WM, WN, false>, lds_bytes);
+}
+
 template <bool MX>
 static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int out_dtype, hipStream_t stream)
 {
@@ -490,9 +552,24 @@ static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int o
     g.K = (int)K;
     g.tiles_m = (int)((M + BM - 1) / BM);
     g.tiles_n = (int)((N + BN - 1) / BN);
+    g.col_base = 0;
+    if constexpr (!MX) {
+        if (HIF4_PLANES_MFMA16) {
+            const PlanesSplit sp = planes_split(M, N);
+            if (sp.main_tile_cols > 0) {
+                g.tiles_n = sp.main_tile_cols;
+                if (int rc = launch_planes16<256>(g, out_dtype, stream)) return rc;
+                g.col_base = 256 * sp.main_tile_cols;
+            }
+            g.tiles_n = (int)((N - g.col_base + sp.tail_bn - 1) / sp.tail_bn);
+            if (sp.tail_bn == 192) return launch_planes16<192>(g, out_dtype, stream);
+            if (sp.tail_bn == 128) return launch_planes16<128>(g, out_dtype, stream);
+            return launch_planes16<256>(g, out_dtype, stream);
+        }
+    }
     constexpr size_t lds_bytes = 2 * 8 * (BM + BN) * sizeof(uint4);
-    const int64_t padded = (int64_t)((g.tiles_m + 3) / 4) * ((g.tiles_n + 7) / 8) * 32; // whole super-tiles, a multiple of 8
-    const dim3 grid((unsigned)padded), block(64 * WM * WN);
+    if (dense_tile_blocks(g.tiles_m, g.tiles_n) > 0x7FFFFFFF) return HIF4_ERR_SHAPE;
+    const dim3 grid((unsigned)dense_tile_blocks(g.tiles_m, g.tiles_n)), block(64 * WM * WN);
     hipError_t e;
     if constexpr (!MX) {
         if (out_dtype == 16 + HIF4_ROUND_RNE || out_dtype == 16 + HIF4_ROUND_RHA) { // result written as HiF4
@@ -500,28 +577,16 @@ static int launch_planes(PlaneGemmArgs g, int64_t M, int64_t N, int64_t K, int o
             static_assert(emit_bytes <= 160 * 1024, "fits the LDS of one CU");
             auto k = out_dtype == 16 + HIF4_ROUND_RNE ? gemm_planes_kernel<BM, BN, WM, WN, false, false, HIF4_ROUND_RNE>
                                                        : gemm_planes_kernel<BM, BN, WM, WN, false, false, HIF4_ROUND_RHA>;
-            if (HIF4_PLANES_MFMA16)
-                k = out_dtype == 16 + HIF4_ROUND_RNE ? gemm_planes16_kernel<BM, BN, WM, WN, false, HIF4_ROUND_RNE>
-                                                     : gemm_planes16_kernel<BM, BN, WM, WN, false, HIF4_ROUND_RHA>;
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)emit_bytes);
             if (e != hipSuccess) return HIF4_ERR_DEVICE;
             hipLaunchKernelGGL(k, grid, block, emit_bytes, stream, g);
             return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
         }
     }
-    if (out_dtype == HIF4_OUT_F32) {
-        auto k = gemm_planes_kernel<BM, BN, WM, WN, true, MX>;
-        if (!MX && HIF4_PLANES_MFMA16) k = gemm_planes16_kernel<BM, BN, WM, WN, true>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return HIF4_ERR_DEVICE;
-        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
-    } else {
-        auto k = gemm_planes_kernel<BM, BN, WM, WN, false, MX>;
-        if (!MX && HIF4_PLANES_MFMA16) k = gemm_planes16_kernel<BM, BN, WM, WN, false>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return HIF4_ERR_DEVICE;
-        hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
-    }
+    auto k = out_dtype == HIF4_OUT_F32 ? gemm_planes_kernel<BM, BN, WM, WN, true, MX> : gemm_planes_kernel<BM, BN, WM, WN, false, MX>;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return HIF4_ERR_DEVICE;
+    hipLaunchKernelGGL(k, grid, block, lds_bytes, stream, g);
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
 }
 

@@ -21,7 +21,7 @@ HIF4_OUT_BF16, HIF4_OUT_F32 = 0, 1
 HIF4_PLAN_ZERO_FILL = 0
 
 EXPORTS = ["hif4_quantize", "hif4_quantize_from", "hif4_dequantize", "hif4_gemm", "hif4_gemm_to_hif4", "hif4_grouped_gemm",
-           "hif4_gemm_noalloc", "hif4_gemm_noalloc_max_bytes", "hif4_grouped_gemm_to_hif4", "hif4_gemm_plan", "hif4_gemm_plan_name",
+           "hif4_gemm_noalloc", "hif4_gemm_noalloc_max_bytes", "hif4_grouped_gemm_to_hif4", "hif4_gemm_plan", "hif4_gemm_plan_name", "hif4_gemm_plan_planes_split",
            "hif4_gemm_workspace_bytes", "hif4_gemm_workspace_bytes_decoded_w", "hif4_status_string", "hif4_version",
            "hif4cmp_mxfp4_fake_quant", "hif4cmp_nvfp4_fake_quant", "hif4cmp_abs_max", "hif4cmp_sq_err_bf16",
            "hif4ref_mxfp4_pack", "hif4ref_mxfp4_gemm", "hif4ref_mfma_loop"]
@@ -62,6 +62,8 @@ def load():
         L.hif4_gemm_plan.argtypes = [i32, i32, i64, i64, i64, i32, sz]
         L.hif4_gemm_plan_name.restype = C.c_char_p
         L.hif4_gemm_plan_name.argtypes = [i32]
+        L.hif4_gemm_plan_planes_split.restype = i32
+        L.hif4_gemm_plan_planes_split.argtypes = [i64, i64, C.POINTER(i32), C.POINTER(i32)]
         L.hif4_gemm_noalloc.restype = i32
         L.hif4_gemm_noalloc.argtypes = [i32, vp, vp, i64, vp, vp, i64, i64, i64, vp, i64, i32, vp]
         L.hif4_gemm_noalloc_max_bytes.restype = sz
@@ -130,6 +132,13 @@ def hif4_gemm_plan(a_kind, M, N, K, experts=0, result_as_hif4=False, workspace_b
 
 def hif4_gemm_plan_name(plan):
     return load().hif4_gemm_plan_name(int(plan)).decode()
+
+
+def hif4_gemm_plan_planes_split(M, N):
+    """(tile columns of 256 in the first launch, tile width of the launch for the remaining columns) of a HIF4_PLAN_PLANES call."""
+    main, width = C.c_int(0), C.c_int(0)
+    _check(load().hif4_gemm_plan_planes_split(int(M), int(N), C.byref(main), C.byref(width)), "hif4_gemm_plan_planes_split")
+    return main.value, width.value
 
 
 def hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K):

@@ -96,3 +96,47 @@ def test_plan_rejects_what_the_calls_reject(lib):
     assert lib.hif4_gemm_plan(P, 0, 8, 64, 64, 0, 8 * 64 * 2 - 1) == h.HIF4_ERR_WORKSPACE
     assert lib.hif4_gemm_plan(P, 0, 8, 64, 0, 0, 0) == h.HIF4_PLAN_ZERO_FILL
     assert lib.hif4_gemm_plan_name(99) == b"unknown plan"
+
+
+# ---- how a call on decoded operands is cut into launches (hif4_gemm_plan_planes_split)
+
+def rounds_of_launch(tiles_m, tiles_n):
+    """Rounds of one workgroup per CU: the kernels deal the tiles of a launch to the 8 XCDs (32 CUs each) in equal shares."""
+    return -(-(-(-tiles_m * tiles_n // 8)) // 32)
+
+
+REL = {256: 1.0, 192: 0.80, 128: 0.60}   # time of a round of narrower tiles, in rounds of 256-column tiles (measured: 0.795 for 192)
+GAP = 0.04
+
+
+def test_planes_split_of_known_shapes():
+    assert h.hif4_gemm_plan_planes_split(4096, 11008) == (32, 192)    # 688 tiles: two rounds of 256 x 256, then 240 tiles of 256 x 192
+    assert h.hif4_gemm_plan_planes_split(16384, 28672) == (0, 256)    # 28 whole rounds
+    assert h.hif4_gemm_plan_planes_split(4096, 4096) == (0, 256)      # one whole round
+    assert h.hif4_gemm_plan_planes_split(2048, 2048) == (0, 256)      # less than a round: nothing to gain
+    assert h.hif4_gemm_plan_planes_split(0, 0) == (0, 256)
+    main, width = h.hif4_gemm_plan_planes_split(4096, 14336)          # 3.5 rounds
+    assert width in (192, 128) and main > 0
+
+
+def test_planes_split_covers_the_columns_and_saves_rounds():
+    for M in (1536, 1600, 2048, 3328, 4096, 5000, 8192, 16384):
+        for N in (2048, 4096, 5120, 8192, 11008, 11000, 14336, 16384, 22016, 28672):
+            main, width = h.hif4_gemm_plan_planes_split(M, N)
+            tm, tn = -(-M // 256), -(-N // 256)
+            assert width in (256, 192, 128) and 0 <= main < max(tn, 1)
+            assert width != 256 or main == 0                           # a tail of 256-column tiles is no split at all
+            if width == 256:
+                continue
+            assert 256 < tm * tn <= 16 * 256                           # never for one round or less, nor for many rounds
+            tail_tiles = -(-(N - 256 * main) // width)
+            assert tail_tiles >= 1 and 256 * main + width * tail_tiles >= N   # every column has a tile
+            t_split = rounds_of_launch(tm, main) + REL[width] * rounds_of_launch(tm, tail_tiles) + (GAP if main else 0.0)
+            assert t_split <= 0.97 * rounds_of_launch(tm, tn) + 1e-9, (M, N, main, width)
+
+
+def test_planes_split_rejects_bad_arguments(lib):
+    import ctypes as C
+    a, b = C.c_int(0), C.c_int(0)
+    assert lib.hif4_gemm_plan_planes_split(-1, 64, C.byref(a), C.byref(b)) == h.HIF4_ERR_SHAPE
+    assert lib.hif4_gemm_plan_planes_split(64, 64, None, C.byref(b)) == h.HIF4_ERR_NULL

@@ -402,6 +402,37 @@ def test_gemm_many_rows_decoded_w_workspace(h, oracle, kind):
     assert rel_fro(c_small.cpu().numpy().astype(np.float64), got) <= 1e-6
 
 
+@pytest.mark.parametrize("kind", ["hif4", "keep"])
+@pytest.mark.parametrize("M,N,K", [(1600, 11000, 128), (3336, 7000, 192), (2136, 11000, 64), (2336, 16250, 64)])
+def test_gemm_decoded_operands_columns_in_two_tile_widths(h, oracle, kind, M, N, K):
+    """Calls on decoded operands whose 256 x 256 tiles would leave the last round of workgroups mostly empty run whole
+    rounds of 256-column tiles first and the remaining columns in tiles of 192 or 128 columns (a second launch): the
+    whole result against the oracle, ragged in both directions, and bit for bit equal in BF16 and fp32 output kinds
+    (the order of an output's additions over K does not depend on the tile it falls in)."""
+    main, width = h.hif4_gemm_plan_planes_split(M, N)
+    print(f"gemm split kind={kind} M={M} N={N} K={K} main={main} width={width}", flush=True)
+    assert width in (192, 128)
+    ab, (ac, am), (wc, wm) = quantized_operands(oracle, M, N, K, 31 + M)
+    wcd, wmd = dev_packed(wc, wm)
+    if kind == "keep":
+        a_kind, a_dev, am_dev = h.HIF4_A_BF16_KEEP, synth.from_bits(ab).cuda(), None
+        want = oracle.gemm_f64(ab, oracle.dequantize(wc, wm))
+    else:
+        a_kind = h.HIF4_A_HIF4
+        a_dev, am_dev = dev_packed(ac, am)
+        want = oracle.gemm_f64(oracle.dequantize(ac, am), oracle.dequantize(wc, wm))
+    big = h.hif4_gemm_workspace_bytes_decoded_w(a_kind, M, N, K)
+    assert h.hif4_gemm_plan_name(h.hif4_gemm_plan(a_kind, M, N, K, workspace_bytes=big)) == "hif4::gemm_planes16_kernel"
+    ws = torch.empty(big, dtype=torch.uint8, device="cuda")
+    cbuf = torch.full((M, N + 5), 3.0, dtype=torch.float32, device="cuda")
+    c32 = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_F32, c=cbuf[:, :N], workspace=ws)
+    c16 = h.hif4_gemm(a_kind, a_dev, am_dev, wcd, wmd, out_dtype=h.HIF4_OUT_BF16, workspace=ws)
+    torch.cuda.synchronize()
+    assert (cbuf[:, N:] == 3.0).all()
+    assert rel_fro(c32.double().cpu().numpy(), want) <= TOL
+    assert torch.equal(c16, c32.to(torch.bfloat16))
+
+
 def test_gemm_many_rows_many_tiles_sampled(h, oracle):
     """16384 x 2048 x 8192 with the activations quantised inside the call: 512 tiles over the whole chip
     through the decoded-operand path (the launch shape of the large prefill benchmark leg, fewer
@@ -449,7 +480,9 @@ def test_gemm_equals_fake_quant_linear(h):
 
 
 @pytest.mark.parametrize("kind", ["hif4", "quantize", "keep"])
-@pytest.mark.parametrize("M,N,K,mode", [(1, 64, 64, 0), (2100, 320, 512, 0), (2305, 576, 192, 1), (300, 22016, 128, 0)])
+@pytest.mark.parametrize("M,N,K,mode", [(1, 64, 64, 0), (2100, 320, 512, 0), (2305, 576, 192, 1), (300, 22016, 128, 0),
+                                        # decoded operands, columns cut into a launch of 256-column tiles and one of narrower tiles
+                                        (3336, 7040, 128, 1)])
 def test_gemm_to_hif4_equals_gemm_then_quantize(h, oracle, kind, M, N, K, mode):
     """The HiF4-emitting epilogue gives hif4_quantize(BF16 result of hif4_gemm) bit for bit (same products,
     same summation order, same BF16 rounding, Algorithm 1 with the encoder's arithmetic); the BF16 result
