@@ -569,10 +569,13 @@ static bool few_rows_prefer_k_split(int64_t M, int64_t N, int64_t K)
 // 8192 x 28672 79.7 : 88.0; one row: 11008 x 4096 11.1 : 12.4, 28672 x 8192 40.9 : 46.8.  The other way round on fewer
 // columns, where its 16-column strips do not fill the chip with waves (16 rows: 4096 x 4096 8.8 : 7.2, 2048 x 7168
 // 12.3 : 10.3, 4096 x 11008 17.5 : 15.4; 32 rows: 14.2 : 8.4, 20.9 : 13.5, 32.1 : 20.5; 8 rows and fewer: within 5 %).
+#ifndef HIF4_FEWROWS_MIN_COLUMNS
+#define HIF4_FEWROWS_MIN_COLUMNS 6144
+#endif
 static bool fewrows_pays(int64_t M, int64_t N, int64_t K)
 {
     (void)K;
-    return M <= 32 && N >= 6144;
+    return M <= 32 && N >= HIF4_FEWROWS_MIN_COLUMNS;
 }
 
 // Rows of A per workgroup of that kernel for a dense call, 0: not its case.  Up to 192 rows: one tile.

@@ -36,6 +36,8 @@
 // the order they were issued, so s_waitcnt vmcnt((D - 2) PER) before step i leaves only loads younger than
 // those of step i in flight (the compiler never sees them, and the loop contains no other vector memory
 // instruction).  K must be a multiple of 256 (metadata rows then start on 16-byte boundaries).
+#include <type_traits>
+
 #include "hif4_common.h"
 
 namespace hif4 {
@@ -52,6 +54,18 @@ __device__ __forceinline__ uint64_t fr_uniform(uint64_t v) // a wave-uniform val
 {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v), hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
     return ((uint64_t)hi << 32) | lo;
+}
+
+// byte B of x, shifted into the exponent field of an fp32 pattern: one instruction (the operand's byte select does the
+// extraction; the shift amount has to sit in a register for this encoding)
+template <int B>
+__device__ __forceinline__ uint32_t byte_shl23(uint32_t x)
+{
+    static_assert(B == 1 || B == 2, "bytes 0 and 3 need no extraction");
+    uint32_t r;
+    if (B == 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(23u), "v"(x));
+    else asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(23u), "v"(x));
+    return r;
 }
 
 struct FewRowsArgs {
@@ -189,15 +203,26 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
 #pragma unroll
         for (int i = 0; i < RB; ++i) acc[cg][i] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
 
+    // ---- the powers of two of a unit's micro-exponents, as this lane needs them: lane (n, q) expands groups of 8 number
+    // q (half step 0) and 4 + q (half step 1), i.e. E1_8 bits q and 4 + q and E1_16 bits 2 q, 2 q + 1, 8 + 2 q, 9 + 2 q of
+    // the metadata word m.  Result: the biased exponents 127 + E1_8 + E1_16 of 2^(E1_8 + E1_16) as four bytes -
+    // byte 0: half step 0, elements 0..3 of the group; byte 1: half step 1, elements 0..3; byte 2: half step 0, elements
+    // 4..7; byte 3: half step 1, elements 4..7 - by arithmetic on all four at once (a multiplication spreads the bits).
+    const uint32_t sh16 = 16 + 2 * (lane / 16), sh8 = 8 + lane / 16, sh8b = 12 + lane / 16;
+    auto micro_exponents = [&](uint32_t m) {
+        const uint32_t t = __builtin_amdgcn_ubfe(m, sh16, 10);                       // bits 0, 1, 8, 9 are the four E1_16 bits
+        const uint32_t s16 = __umul24(t, 0x8001u) & 0x01010101u;     // bit 0 -> 0, 1 -> 16, 8 -> 8, 9 -> 24
+        const uint32_t e = __builtin_amdgcn_ubfe(m, sh8, 1) | (__builtin_amdgcn_ubfe(m, sh8b, 1) << 8); // E1_8 of the two groups
+        return s16 + __umul24(e, 0x10001u) + 0x7F7F7F7Fu;            // no carries: every byte is 127 .. 129
+    };
     // ---- one dword of codes (group of 8 number j = 4 hs + q of its unit) -> one operand of 8 BF16: S1P2
-    // magnitude times sign times 2^(E1_8 + E1_16), natural element order.  m8q, m16q: the unit's metadata word
-    // shifted so that bit 4 hs of m8q is E1_8[j] and bits 8 hs, 8 hs + 1 of m16q are E1_16[2 j], E1_16[2 j + 1]
-    // (one bit-field extract and one shift-add per power of two).
-    auto expand_dword = [&](uint32_t c, uint32_t m8q, uint32_t m16q, int hs) {
-        const uint32_t one8 = (__builtin_amdgcn_ubfe(m8q, 4 * hs, 1) << 23) + 0x3F800000u;      // 2^E1_8 as an fp32 pattern
-        const float sa = u2f((__builtin_amdgcn_ubfe(m16q, 8 * hs, 1) << 23) + one8);             // ... times 2^E1_16, elements 0..3
-        const float sb = u2f((__builtin_amdgcn_ubfe(m16q, 8 * hs + 1, 1) << 23) + one8);         // elements 4..7
-        const uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u;                         // magnitudes, one per byte
+    // magnitude times sign times 2^(E1_8 + E1_16), natural element order.  xb: micro_exponents() of the unit.  The
+    // conversion instruction reads the exponent field of its scale operand only, so whatever a shift leaves in the low
+    // 23 bits does not matter; the sign bit stays clear.
+    auto expand_dword = [&](uint32_t c, uint32_t xb, int hs) {
+        const float sa = u2f(hs == 0 ? xb << 23 : byte_shl23<1>(xb));                // elements 0..3
+        const float sb = u2f(hs == 0 ? byte_shl23<2>(xb) : xb >> 1);                 // elements 4..7
+        const uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u;             // magnitudes, one per byte
         const uint32_t f8lo = __builtin_amdgcn_perm(FP8_OF_4567, FP8_OF_0123, lo) | ((c << 4) & 0x80808080u);
         const uint32_t f8hi = __builtin_amdgcn_perm(FP8_OF_4567, FP8_OF_0123, hi) | (c & 0x80808080u);
         uint4 b;
@@ -222,13 +247,15 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
     const int wswz = (n16 >> 2) & 3; // swizzle of rows n and 16 + n alike
     const f32x4_t zero4 = { 0.f, 0.f, 0.f, 0.f };
 
-    // matrix work of the pair in slot `slot`.  Every LDS read of the step is requested up front, so that the
-    // read latency is covered by arithmetic the wave has anyway.
-    auto compute = [&](int slot, int pair) {
-        if (pair >= np) return; // wave-uniform: a K part past the end of K
+    // matrix work of the pair in slot `slot` (a compile-time number: every LDS address of the step is then a lane
+    // constant plus an immediate offset).  Every LDS read of the step is requested up front, so that the read latency
+    // is covered by arithmetic the wave has anyway.  TWO: the pair has both units (all pairs but the last of an odd K/64).
+    auto compute = [&](auto slot_c, int pair, auto two_c) {
+        constexpr int slot = decltype(slot_c)::value;
+        constexpr bool TWO = decltype(two_c)::value;
+        constexpr int NU = TWO ? 2 : 1;
         const uint4 *sl = lds + slot * SLOT;
         const int u0 = 2 * pair; // the pair's first unit; both units lie in metadata block u0 / 16
-        const bool two = u0 + 1 < upr; // wave-uniform
         const uint32_t *mring = reinterpret_cast<const uint32_t *>(lds + META0 + (wave * 2 + ((u0 >> 4) & 1)) * WCELLS) + (u0 & 15);
         uint2 mm[CG];       // metadata of the pair's units, per column group
         uint32_t cd[CG][2][2]; // codes dword [column group][unit][half step]
@@ -237,13 +264,13 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
         for (int cg = 0; cg < CG; ++cg) {
             mm[cg] = *reinterpret_cast<const uint2 *>(mring + (16 * cg + n16) * 16);
 #pragma unroll
-            for (int uu = 0; uu < 2; ++uu)
+            for (int uu = 0; uu < NU; ++uu)
 #pragma unroll
                 for (int hs = 0; hs < 2; ++hs) cd[cg][uu][hs] = cbase[(64 * cg + 4 * n16 + ((2 * uu + hs) ^ wswz)) * 4];
         }
         uint4 av[2][2][RB]; // A operands [unit][half step][row block]
 #pragma unroll
-        for (int uu = 0; uu < 2; ++uu)
+        for (int uu = 0; uu < NU; ++uu)
 #pragma unroll
             for (int hs = 0; hs < 2; ++hs)
 #pragma unroll
@@ -251,20 +278,15 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
         __builtin_amdgcn_sched_barrier(0);
         f32x4_t part[2][CG][RB]; // the units' own sums [unit][column group][row block]
 #pragma unroll
-        for (int uu = 0; uu < 2; ++uu) {
-            if (uu == 1 && !two) break;
-            uint32_t m8q[CG], m16q[CG];
+        for (int uu = 0; uu < NU; ++uu) {
+            uint32_t xb[CG];
 #pragma unroll
-            for (int cg = 0; cg < CG; ++cg) {
-                const uint32_t m = uu == 0 ? mm[cg].x : mm[cg].y;
-                m8q[cg] = m >> (8 + q);
-                m16q[cg] = m >> (16 + 2 * q);
-            }
+            for (int cg = 0; cg < CG; ++cg) xb[cg] = micro_exponents(uu == 0 ? mm[cg].x : mm[cg].y);
 #pragma unroll
             for (int hs = 0; hs < 2; ++hs)
 #pragma unroll
                 for (int cg = 0; cg < CG; ++cg) {
-                    const uint4 b = expand_dword(cd[cg][uu][hs], m8q[cg], m16q[cg], hs);
+                    const uint4 b = expand_dword(cd[cg][uu][hs], xb[cg], hs);
 #pragma unroll
                     for (int i = 0; i < RB; ++i)
                         part[uu][cg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[uu][hs][i]), __builtin_bit_cast(bf16x8_t, b),
@@ -273,8 +295,7 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
         }
         // the units' sums times their E6M2 factors (the first unit's have long left the matrix pipeline)
 #pragma unroll
-        for (int uu = 0; uu < 2; ++uu) {
-            if (uu == 1 && !two) break;
+        for (int uu = 0; uu < NU; ++uu) {
 #pragma unroll
             for (int cg = 0; cg < CG; ++cg) {
                 const float sc = unit_scale(uu == 0 ? mm[cg].x : mm[cg].y);
@@ -287,14 +308,15 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
     };
 
     // ---- pipeline: step `it` is issued D - 1 steps ahead of its matrix work; the two metadata blocks the part
-    // starts in come first, block b + 1 follows when the part enters block b
+    // starts in come first, block b + 1 follows when the part enters block b.  The loop is unrolled over the D slots
+    // of the ring, so that a step's slot is a compile-time number.
     int blk = (2 * p0) >> 4;
     issue_meta(blk);
     issue_meta(blk + 1);
 #pragma unroll
     for (int it = 0; it < D - 1; ++it) issue(it, it);
-    int slot = 0;
-    for (int it = 0; it < ppp; ++it) {
+    auto step = [&](int it, auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
         // the loads of step `it` have landed once only younger ones (those of D - 2 steps, at least) are in flight
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"((D - 2) * PER) : "memory");
         __syncthreads(); // every wave's share of A(it) is there, and every wave is through with the slot refilled next
@@ -304,8 +326,18 @@ __global__ __launch_bounds__(64 * NWC * KS) void gemm_fewrows_kernel(FewRowsArgs
             issue_meta(blk + 1);
         }
         issue(it + D - 1, slot == 0 ? D - 1 : slot - 1);
-        compute(slot, p0 + it);
-        slot = slot + 1 == D ? 0 : slot + 1;
+        const int pair = p0 + it;
+        if (pair >= np) return;                       // wave-uniform: a K part past the end of K
+        if (2 * pair + 1 < upr) compute(slot_c, pair, std::true_type{}); // wave-uniform
+        else compute(slot_c, pair, std::false_type{});
+    };
+    for (int it0 = 0; it0 < ppp; it0 += D) {
+        step(it0, std::integral_constant<int, 0>{});
+        if (it0 + 1 < ppp) step(it0 + 1, std::integral_constant<int, 1>{});
+        if (it0 + 2 < ppp) step(it0 + 2, std::integral_constant<int, 2>{});
+        if constexpr (D > 3) { if (it0 + 3 < ppp) step(it0 + 3, std::integral_constant<int, 3>{}); }
+        if constexpr (D > 4) { if (it0 + 4 < ppp) step(it0 + 4, std::integral_constant<int, 4>{}); }
+        if constexpr (D > 5) { if (it0 + 5 < ppp) step(it0 + 5, std::integral_constant<int, 5>{}); }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // no load may outlive the workgroup's LDS
 
@@ -362,7 +394,9 @@ struct FewRowsChoice {
 
 // The shapes a workgroup can take: (column strips, K parts, column groups of 16 per strip).  Strips of 16 columns
 // give twice as many strips to spread over the chip and over K; strips of 32 share each A operand between two MFMAs.
+#ifndef HIF4_FR_SHAPES
 #define HIF4_FR_SHAPES(X) X(7, 2, 1) X(3, 4, 1) X(2, 4, 1) X(4, 2, 1) X(4, 2, 2)
+#endif
 
 // Which of them a call takes.  The kernel is bound by the vector instructions of the expansion, which a SIMD
 // issues for its waves in turn, so time is modelled as rounds of workgroups over the chip's 256 CUs times the
