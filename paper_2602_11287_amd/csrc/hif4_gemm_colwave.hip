@@ -78,11 +78,13 @@ enum { COLWAVE_BF16 = 0, COLWAVE_F32 = 1, COLWAVE_EMIT = 2 };
 // it), NB buffers of A, a ring of R steps of packed W.
 template <int NW, int KS, int NB, int R>
 struct ColwaveShape {
-    // mblk: metadata in blocks of 8 units (two blocks of 32 rows per wave) instead of a word per lane and ring step
-    static constexpr size_t lds_bytes(int tmax, bool mblk)
+    // mblk: metadata in blocks of 8 units (two blocks of 32 rows per wave) instead of a word per lane and ring step;
+    // wpair: codes in pairs of units (64-byte runs per row, see the kernel), (R + 2) / 2 pair slots of 2 KB per wave
+    static constexpr size_t lds_bytes(int tmax, bool mblk, bool wpair = false)
     {
         const int rg = (32 * tmax + 63) / 64;
-        return (size_t)NB * KS * 8 * 64 * rg * 16 + (size_t)R * NW * 64 * 16 + (mblk ? (size_t)NW * 2048 : (size_t)R * NW * 64 * 4);
+        return (size_t)NB * KS * 8 * 64 * rg * 16 + (wpair ? (size_t)((R + 2) / 2) * NW * 128 * 16 : (size_t)R * NW * 64 * 16) +
+               (mblk ? (size_t)NW * 2048 : (size_t)R * NW * 64 * 4);
     }
 };
 
@@ -90,7 +92,12 @@ struct ColwaveShape {
 // units [kw K/64/KS, (kw + 1) K/64/KS) - and their partial sums meet in LDS after the loop.  With few
 // rows and not many columns there are too few 32-column strips to give every SIMD its two waves,
 // and a wave alone cannot issue faster than it does; K is the only other axis to cut.
-template <int TMAX, int NW, int KS, int NB, int R, int WPS, int OUT, bool MBLK>
+// WPAIR: the packed codes come in pairs of units.  One load per step as before, but load j brings rows 16 (j % 2) ..
+// + 15 of the wave's 32 weight rows for both units of pair j / 2: four adjacent lanes fetch the 64 contiguous bytes of a
+// row, so a request covers half a 128-byte line instead of a quarter, and a line is fetched twice instead of four times
+// by the time its four units are used.  The 16-byte chunks of a row are stored XOR-swizzled (chunk c of row n at
+// position c ^ (n / 2 % 4) of the row's four), so that the operand reads of a wave are spread over the banks.
+template <int TMAX, int NW, int KS, int NB, int R, int WPS, int OUT, bool MBLK, bool WPAIR = false>
 __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs g)
 {
     constexpr bool OUT_F32 = OUT == COLWAVE_F32, EMIT = OUT >= COLWAVE_EMIT;
@@ -102,11 +109,14 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     constexpr int IA = (KS * 8 * RG + NW - 1) / NW; // A loads per wave and step
     constexpr int PER_STEP = IA + 2;         // LDS-writing loads per wave and step
     static_assert(R > NB && NB >= 2, "W(k + 1) must be older than A(k + 1)");
+    static_assert(!WPAIR || R >= NB + 2, "both loads of the pair of unit k + 1 must be older than A(k + 1)");
+    constexpr int RP = (R + 2) / 2;          // WPAIR: pair slots of the codes ring
+    constexpr int WC_CELLS = WPAIR ? RP * NW * 128 : R * NW * 64;
     static_assert(NW % KS == 0, "whole wave groups");
     extern __shared__ uint4 lds[];
     uint4 *lds_a = lds;                                  // [NB][KS][8][BMP]
-    uint4 *lds_wc = lds + NB * KS * A_CELLS;             // [R][NW][64]
-    uint32_t *lds_wm = reinterpret_cast<uint32_t *>(lds_wc + R * NW * 64); // [R][NW][64], or MBLK: [NW][2 blocks][32 rows][8 units]
+    uint4 *lds_wc = lds + NB * KS * A_CELLS;             // [R][NW][64], or WPAIR: [RP][NW][2 halves][16 rows][4 chunks]
+    uint32_t *lds_wm = reinterpret_cast<uint32_t *>(lds_wc + WC_CELLS); // [R][NW][64], or MBLK: [NW][2 blocks][32 rows][8 units]
 
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
@@ -149,6 +159,20 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     int wrow = col0 + cw * 32 + l32;
     wrow = wrow < g.N ? wrow : g.N - 1;
     const uint32_t wc_off = (uint32_t)wrow * (uint32_t)(g.K / 2) + 16u * half + (uint32_t)u0 * 32u;
+    // WPAIR, load half t: lane -> weight row 16 t + lane / 4 of the wave's 32, position lane % 4 of the row's four 16-byte
+    // chunks, which holds chunk position ^ swizzle(row); chunk c = half c % 2 of unit c / 2 of the pair.  The last pair
+    // of an odd number of units has its first unit only: its chunks 2 and 3 repeat chunks 0 and 1 (never used, in bounds).
+    // (plain values combined by masks, no arrays indexed by the load's parity: those would live in scratch memory)
+    uint32_t wp_off0, wp_delta, wp_tail_adj;
+    {
+        const int r16 = lane / 4, c = (lane % 4) ^ ((r16 >> 1) & 3);
+        int row0w = col0 + cw * 32 + r16, row1w = row0w + 16;
+        row0w = row0w < g.N ? row0w : g.N - 1;
+        row1w = row1w < g.N ? row1w : g.N - 1;
+        wp_off0 = (uint32_t)row0w * (uint32_t)(g.K / 2) + 16u * c + (uint32_t)u0 * 32u;
+        wp_delta = (uint32_t)(row1w - row0w) * (uint32_t)(g.K / 2); // half 1 of a load pair: 16 rows further on
+        wp_tail_adj = 16u * (c & 2);                                // back to chunk c % 2
+    }
     // Metadata.  MBLK: blocks of 8 units of the wave's 32 rows, one load of 8 rows x 8 units (32-byte runs) per step, see
     // issue_w; lane -> row lane / 8 of the load's 8, unit lane % 8 of the block (a K range of fewer than 8 units repeats
     // its last one).  Rows past N - 1 take row N - 1: the byte offset is capped at that row's (it grows with the row).
@@ -173,7 +197,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     }
     auto lds_byte_of = [](const void *p) { return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p; };
     const uint32_t a_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_a));
-    const uint32_t wc_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_wc)) + (uint32_t)(wave * 64 * 16);
+    const uint32_t wc_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_wc)) + (uint32_t)(wave * (WPAIR ? 128 : 64) * 16);
     const uint32_t wm_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte_of(lds_wm)) + (uint32_t)(wave * (MBLK ? 2048 : 64 * 4));
     const uint64_t a_step = (uint64_t)g.M * 128; // bytes of A planes per K step
     const uint64_t wc_ptr = cw_uniform((uint64_t)(uintptr_t)w_codes), wm_ptr = cw_uniform((uint64_t)(uintptr_t)w_meta);
@@ -192,7 +216,13 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     };
     auto issue_w = [&](int u, int at) {
         const uint64_t uc = (uint64_t)(u < nk ? u : nk - 1);
-        cw_load_to_lds_16(wc_ptr + uc * 32, wc_off, wc_base + (uint32_t)(at * NW * 64 * 16));
+        if constexpr (WPAIR) { // load number u: half u % 2 of pair u / 2 (`at` is not used: the pair slot follows from u)
+            const int last = (nk - 1) / 2, p = u / 2 < last ? u / 2 : last, t = u & 1;
+            const bool tail = 2 * p + 1 >= nk; // wave-uniform
+            cw_load_to_lds_16(wc_ptr + (uint64_t)p * 64, wp_off0 + (wp_delta & (0u - (uint32_t)t)) - (wp_tail_adj & (0u - (uint32_t)tail)), wc_base + (uint32_t)(((u / 2) % RP * NW * 128 + t * 64) * 16));
+        } else {
+            cw_load_to_lds_16(wc_ptr + uc * 32, wc_off, wc_base + (uint32_t)(at * NW * 64 * 16));
+        }
         if constexpr (MBLK) {
             const int x = u - R + 9; // >= 9 - R > 0
             issue_meta_block(x >> 3, x & 3);
@@ -219,8 +249,13 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
         uint32_t sbase;  // fp32 pattern of the unit scale
     };
     const uint32_t *lds_wm_lane = lds_wm + wave * 512 + l32 * 8; // MBLK: this lane's row in block slot 0
+    // WPAIR: this lane's cell of a pair slot, for the first and the second unit of the pair
+    const int wp_sw = (l32 >> 1) & 3;
+    const int wp_cell0 = (l32 / 16) * 64 + 4 * (l32 % 16) + (half ^ wp_sw), wp_cell_delta = ((2 + half) ^ wp_sw) - (half ^ wp_sw);
     auto read_w = [&](UnitW &uw, int slot, int u) { // ring slot and number (in the wave's K range) of the unit
-        const uint4 cw = lds_wc[(slot * NW + wave) * 64 + lane];
+        uint4 cw;
+        if constexpr (WPAIR) cw = lds_wc[((u / 2) % RP * NW + wave) * 128 + wp_cell0 + (wp_cell_delta & (0 - (u & 1)))];
+        else cw = lds_wc[(slot * NW + wave) * 64 + lane];
         uint32_t m;
         if constexpr (MBLK) {
             const int uc = u < nk ? u : nk - 1, b = uc >> 3;
@@ -351,7 +386,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     // ---- KS > 1: the partial sums of wave groups 1 .. KS - 1 go through LDS (all loads have landed and
     // all operands are read once every wave is past the barrier) to group 0, lane for lane
     if constexpr (KS > 1) {
-        static_assert((size_t)(KS - 1) * NWC * TMAX * 4096 <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK), "partial sums fit the buffers");
+        static_assert((size_t)(KS - 1) * NWC * TMAX * 4096 <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK, WPAIR), "partial sums fit the buffers");
         float4 *red = reinterpret_cast<float4 *>(lds); // [kw - 1][cw][block][4][lane]
         __syncthreads();
         if (kw > 0) {
@@ -386,7 +421,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     // row-major by the waves that hold it, then every thread of the workgroup encodes units of 64 columns
     if constexpr (EMIT) {
         static_assert(BN % 64 == 0, "whole units across a tile");
-        static_assert(emit_lds_bytes<BM, BN>() <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK), "the parked tile fits the buffers");
+        static_assert(emit_lds_bytes<BM, BN>() <= ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK, WPAIR), "the parked tile fits the buffers");
         constexpr int RS = BN + 8; // row stride in BF16 elements
         uint16_t *tile = reinterpret_cast<uint16_t *>(lds);
         __syncthreads(); // all operand reads and loads are done (KS > 1: and group 0 has read the partial sums)
@@ -437,18 +472,26 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
 #ifndef HIF4_COLWAVE_MBLK
 #define HIF4_COLWAVE_MBLK 1
 #endif
+#ifndef HIF4_COLWAVE_WPAIR
+#define HIF4_COLWAVE_WPAIR 1
+#endif
 // EMIT_OK: also instantiate the kernels that write the result as HiF4
 template <int TMAX, int NW, int KS, bool EMIT_OK = false>
 static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
 {
-    // three buffers of A and four steps of W where LDS has room for them, else two and three; metadata in blocks of 8
+    // three buffers of A where LDS has room for them, else two; the codes of W in pairs of units (64-byte runs per row,
+    // a ring of NB + 2 steps) where that fits as well, else one unit per step (a ring of NB + 1); metadata in blocks of 8
     // units (a quarter of the cache lines fetched per step) where that fits as well
     constexpr size_t LDS_MAX = 160 * 1024;
+    constexpr bool PAIR3 = HIF4_COLWAVE_WPAIR && ColwaveShape<NW, KS, 3, 5>::lds_bytes(TMAX, false, true) <= LDS_MAX;
+    constexpr bool PAIR2 = HIF4_COLWAVE_WPAIR && !PAIR3 && ColwaveShape<NW, KS, 2, 4>::lds_bytes(TMAX, false, true) <= LDS_MAX &&
+                           ColwaveShape<NW, KS, HIF4_COLWAVE_NB, HIF4_COLWAVE_R>::lds_bytes(TMAX, false) > LDS_MAX;
+    constexpr bool WPAIR = PAIR3 || PAIR2;
     constexpr bool DEEP = ColwaveShape<NW, KS, HIF4_COLWAVE_NB, HIF4_COLWAVE_R>::lds_bytes(TMAX, false) <= LDS_MAX;
-    constexpr int NB = DEEP ? HIF4_COLWAVE_NB : 2, R = DEEP ? HIF4_COLWAVE_R : 3, WPS = HIF4_COLWAVE_WPS;
-    constexpr bool MBLK = HIF4_COLWAVE_MBLK && ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, true) <= LDS_MAX;
+    constexpr int NB = PAIR3 ? 3 : PAIR2 ? 2 : DEEP ? HIF4_COLWAVE_NB : 2, R = WPAIR ? NB + 2 : DEEP ? HIF4_COLWAVE_R : 3, WPS = HIF4_COLWAVE_WPS;
+    constexpr bool MBLK = HIF4_COLWAVE_MBLK && ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, true, WPAIR) <= LDS_MAX;
     constexpr int BM = 32 * TMAX, BN = 32 * NW / KS;
-    constexpr size_t lds_bytes = ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK);
+    constexpr size_t lds_bytes = ColwaveShape<NW, KS, NB, R>::lds_bytes(TMAX, MBLK, WPAIR);
     static_assert(lds_bytes <= 160 * 1024, "fits the LDS of one CU");
     g.tiles_n = (g.N + BN - 1) / BN;
     g.tiles_m = g.offs ? g.M / BM + g.E : (g.M + BM - 1) / BM; // grouped: upper bound of sum_e ceil(rows_e / BM)
@@ -460,11 +503,11 @@ static int launch_colwave_t(ColwaveArgs g, int out_dtype, hipStream_t stream)
         return true;
     };
     bool ok;
-    if (out_dtype == HIF4_OUT_F32) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_F32, MBLK>);
-    else if (out_dtype == HIF4_OUT_BF16) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_BF16, MBLK>);
+    if (out_dtype == HIF4_OUT_F32) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_F32, MBLK, WPAIR>);
+    else if (out_dtype == HIF4_OUT_BF16) ok = launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_BF16, MBLK, WPAIR>);
     else if constexpr (EMIT_OK && BN % 64 == 0) { // 16 + rounding mode: the result as HiF4 (the launcher below picks shapes that allow it)
-        ok = out_dtype == 16 + HIF4_ROUND_RNE ? launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RNE, MBLK>)
-                                              : launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RHA, MBLK>);
+        ok = out_dtype == 16 + HIF4_ROUND_RNE ? launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RNE, MBLK, WPAIR>)
+                                              : launch(gemm_colwave_kernel<TMAX, NW, KS, NB, R, WPS, COLWAVE_EMIT + HIF4_ROUND_RHA, MBLK, WPAIR>);
     } else return HIF4_ERR_UNSUPPORTED;
     if (!ok) return HIF4_ERR_DEVICE;
     return hipGetLastError() == hipSuccess ? HIF4_OK : HIF4_ERR_DEVICE;
