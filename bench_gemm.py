@@ -8,18 +8,19 @@ import torch
 
 # HBM bytes per launch of the GEMM kernel itself (pre-passes not included), from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE in KiB per dispatch (FETCH_SIZE x 1.99988, WRITE_SIZE x 1.0, the factors of a plain device copy):
-# profiles/gemm_kernels_configs2-5.md, profiles/gemm_fewrows_skinny_colwave_decode_and_grouped.md
+# profiles/gemm_kernels_configs2-5.md, profiles/gemm_fewrows_skinny_colwave_decode_and_grouped.md,
+# profiles/gemm_planes16_column_split_prefill_4096x11008x4096.md
 def _kib(fetch, write):
     return int((fetch * 1.99988 + write) * 1024)
 
 
 _TRAFFIC = {
     "gemm_weight_only_M16_N4096_K4096": _kib(5151.5, 128.0),
-    "gemm_weight_only_M16_N28672_K8192": _kib(79110.9, 896.0),
-    "gemm_w4a4_quantize_inside_M4096_N11008_K4096": _kib(274558.5, 88143.1),
-    "gemm_w4a4_prepacked_M4096_N11008_K4096": _kib(274558.5, 88143.1),
+    "gemm_weight_only_M16_N28672_K8192": _kib(78072.5, 896.0),
+    "gemm_w4a4_quantize_inside_M4096_N11008_K4096": _kib(196736.0 + 84068.7, 65598.1 + 22528.8),  # the two launches of the call
+    "gemm_w4a4_prepacked_M4096_N11008_K4096": _kib(196736.0 + 84068.7, 65598.1 + 22528.8),
     "gemm_w4a4_quantize_inside_small_workspace_M4096_N11008_K4096": _kib(147985.0, 89805.7),
-    "grouped_gemm_w4a4_E64_rows8192_N2048_K7168": _kib(356800.0, 32768.0),
+    "grouped_gemm_w4a4_E64_rows8192_N2048_K7168": _kib(370768.1, 32768.0),
     "gemm_w4a4_quantize_inside_M16384_N28672_K8192": _kib(5505218.2, 918472.8),
     "gemm_w4a4_quantize_inside_small_workspace_M16384_N28672_K8192": _kib(2867346.8, 930189.2),
     "gemm_w4a4_to_hif4_M16384_N28672_K8192": _kib(5512239.6, 258048.0),
@@ -183,7 +184,9 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
         ws = torch.empty(hif4.hif4_gemm_workspace_bytes_decoded_w(hif4.HIF4_A_BF16_QUANTIZE, M, N, K), dtype=torch.uint8, device=dev)
         ws_small = torch.empty(hif4.hif4_gemm_workspace_bytes(hif4.HIF4_A_BF16_QUANTIZE, M, K), dtype=torch.uint8, device=dev)
         QK = hif4.HIF4_A_BF16_QUANTIZE
-        planes = plan(QK, M, N, K, ws=ws.numel()) + " (+ pre-passes: encode_to_planes, decode_planes)"
+        main_cols, tail_width = hif4.hif4_gemm_plan_planes_split(M, N)   # how the library cuts this call's columns into launches
+        cut = f", columns in {main_cols} tile columns of 256 + the rest in tiles of {tail_width}" if tail_width != 256 else ""
+        planes = plan(QK, M, N, K, ws=ws.numel()) + cut + " (+ pre-passes: encode_to_planes, decode_planes)"
         tiles = plan(QK, M, N, K, ws=ws_small.numel()) + " (+ pre-pass: encode_to_cells)"
         mfma_leg("gemm_w4a4_quantize_inside_M4096_N11008_K4096", M, N, K,
                  lambda: hif4.hif4_gemm(hif4.HIF4_A_BF16_QUANTIZE, a, None, wc, wm, out_dtype=hif4.HIF4_OUT_BF16, c=c, workspace=ws),
