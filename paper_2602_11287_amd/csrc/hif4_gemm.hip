@@ -23,6 +23,7 @@
 #include "hif4_emit.h"
 #include "hif4_expand.h"
 #include "hif4_grouped.h"
+#include "hif4_store.h"
 
 #ifndef HIF4_GEMM_SCHED
 #define HIF4_GEMM_SCHED 1
@@ -248,25 +249,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void gemm_kernel(GemmArgs g)
         return;
     }
     // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*half + r%4
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int jn = 0; jn < TN; ++jn) {
-            const int col = col0 + wn * (BN / WN) + jn * 32 + l32;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm * (BM / WM) + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                if (row < rows_end && col < g.N) {
-                    const float v = acc[i][jn][r];
-                    if (OUT_F32) {
-                        static_cast<float *>(g.c)[(int64_t)row * g.ldc + col] = v;
-                    } else {
-                        static_cast<uint16_t *>(g.c)[(int64_t)row * g.ldc + col] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
-                    }
-                }
-            }
-        }
-    }
+    store_acc_32x32<OUT_F32>(acc, g.c, g.ldc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), rows_end, g.N);
 }
 
 // ------------------------------------------------------------------ skinny weight-only GEMM

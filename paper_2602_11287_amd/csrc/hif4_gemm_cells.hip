@@ -17,6 +17,7 @@
 // no ds_write is issued, and the staging needs no VALU work at all.
 #include "hif4_emit.h"
 #include "hif4_expand.h"
+#include "hif4_store.h"
 
 namespace hif4 {
 
@@ -295,25 +296,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes_kernel(PlaneGemmArgs
     }
 
     // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*half + r%4
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int jn = 0; jn < TN; ++jn) {
-            const int col = col0 + wn * (BN / WN) + jn * 32 + l32;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm * (BM / WM) + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                if (row < g.M && col < g.N) {
-                    const float v = acc[i][jn][r];
-                    if (OUT_F32) {
-                        static_cast<float *>(g.c)[(int64_t)row * g.ldc + col] = v;
-                    } else {
-                        static_cast<uint16_t *>(g.c)[(int64_t)row * g.ldc + col] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
-                    }
-                }
-            }
-        }
-    }
+    store_acc_32x32<OUT_F32>(acc, g.c, g.ldc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), g.M, g.N);
 }
 
 
@@ -440,25 +423,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
         return;
     }
     // ---- epilogue: lane holds column n of each 16 x 16 tile, rows 4 q + r
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int jn = 0; jn < TN; ++jn) {
-            const int col = col0 + wn * (BN / WN) + jn * 16 + n;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = row0 + wm * (BM / WM) + i * 16 + 4 * q + r;
-                if (row < g.M && col < g.N) {
-                    const float v = acc[i][jn][r];
-                    if (OUT_F32) {
-                        static_cast<float *>(g.c)[(int64_t)row * g.ldc + col] = v;
-                    } else {
-                        static_cast<uint16_t *>(g.c)[(int64_t)row * g.ldc + col] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
-                    }
-                }
-            }
-        }
-    }
+    store_acc_16x16<OUT_F32>(acc, g.c, g.ldc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), g.M, g.N);
 }
 
 #ifndef HIF4_PLANES_MFMA16

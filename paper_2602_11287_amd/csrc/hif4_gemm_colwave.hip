@@ -39,6 +39,7 @@
 #include "hif4_emit.h"
 #include "hif4_expand.h"
 #include "hif4_grouped.h"
+#include "hif4_store.h"
 
 namespace hif4 {
 
@@ -442,20 +443,7 @@ __global__ __launch_bounds__(64 * NW, WPS) void gemm_colwave_kernel(ColwaveArgs 
     }
 
     // ---- epilogue: lane holds column l32 of each 32 x 32 block, rows 8 (r / 4) + 4 half + r % 4
-    const int col = col0 + cw * 32 + l32;
-#pragma unroll
-    for (int i = 0; i < TMAX; ++i) {
-        if (i >= live) continue;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = row0 + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            if (row < rows_end && col < g.N) {
-                const float v = acc[i][r];
-                if (OUT_F32) static_cast<float *>(g.c)[(int64_t)row * g.ldc + col] = v;
-                else static_cast<uint16_t *>(g.c)[(int64_t)row * g.ldc + col] = (uint16_t)((f2u(v) + 0x7FFFu + ((f2u(v) >> 16) & 1u)) >> 16);
-            }
-        }
-    }
+    store_acc_32x32<OUT_F32>(acc, g.c, g.ldc, row0, col0 + cw * 32, rows_end, g.N);
 }
 
 #ifndef HIF4_COLWAVE_NW
