@@ -108,11 +108,9 @@ __device__ __forceinline__ void store4(uint32_t *p, uint32_t v)
 // (dense_tile_blocks), the surplus blocks get false.
 __host__ __device__ inline int64_t dense_tile_blocks(int tiles_m, int tiles_n) { return ((int64_t)tiles_m * tiles_n + 7) / 8 * 8; }
 
-__device__ __forceinline__ bool dense_tile_of_block(int tiles_m, int tiles_n, int &tile_m, int &tile_n)
+// tile number t of that list (t < tiles_m * tiles_n)
+__device__ __forceinline__ void dense_tile_of_index(int t, int tiles_m, int tiles_n, int &tile_m, int &tile_n)
 {
-    const int per_xcd = (int)(gridDim.x / 8);
-    const int t = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
-    if (t >= tiles_m * tiles_n) return false;
     const int band = t / (4 * tiles_n), i = t - band * 4 * tiles_n;
     const int hb = tiles_m - 4 * band < 4 ? tiles_m - 4 * band : 4; // tile rows of this band
     const int full = tiles_n / 8;                                    // its super-tiles of 8 columns
@@ -121,6 +119,33 @@ __device__ __forceinline__ bool dense_tile_of_block(int tiles_m, int tiles_n, in
     const int r = i - sc * hb * 8;
     tile_m = 4 * band + r / wb;
     tile_n = 8 * sc + r % wb;
+}
+
+__device__ __forceinline__ bool dense_tile_of_block(int tiles_m, int tiles_n, int &tile_m, int &tile_n)
+{
+    const int per_xcd = (int)(gridDim.x / 8);
+    const int t = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
+    if (t >= tiles_m * tiles_n) return false;
+    dense_tile_of_index(t, tiles_m, tiles_n, tile_m, tile_n);
+    return true;
+}
+
+// The same list for a kernel whose workgroups stay and take tile after tile: the grid is 8 x `slots` blocks (slots =
+// workgroups an XCD runs at a time, at most its share of the tiles), block b is slot b / 8 of XCD b % 8 and takes the
+// tiles slot, slot + slots, ... of its XCD's run.  persistent_tile(k, ...) gives its k-th tile, false past the end.
+__host__ __device__ inline int persistent_slots(int tiles_m, int tiles_n, int cus_per_xcd)
+{
+    const int64_t per_xcd = ((int64_t)tiles_m * tiles_n + 7) / 8;
+    return (int)(per_xcd < cus_per_xcd ? per_xcd : cus_per_xcd);
+}
+
+__device__ __forceinline__ bool persistent_tile(int k, int tiles_m, int tiles_n, int &tile_m, int &tile_n)
+{
+    const int total = tiles_m * tiles_n, per_xcd = (total + 7) / 8, slots = (int)(gridDim.x / 8);
+    const int in_run = (int)(blockIdx.x / 8) + k * slots;
+    const int t = (int)(blockIdx.x % 8) * per_xcd + in_run;
+    if (in_run >= per_xcd || t >= total) return false;
+    dense_tile_of_index(t, tiles_m, tiles_n, tile_m, tile_n);
     return true;
 }
 

@@ -323,29 +323,37 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
     const int wave = tid / 64, lane = tid % 64;
     const int wm = wave / WN, wn = wave % WN;
 
-    int tile_m, tile_n;
-    if (!dense_tile_of_block(g.tiles_m, g.tiles_n, tile_m, tile_n)) return;
-    const int row0 = tile_m * BM, col0 = g.col_base + tile_n * BN;
+    // The workgroups stay: a compute unit runs one of them at a time, and a new one per tile would spend about 12 us
+    // outside its K loop (start of the waves, first loads from memory, draining of its stores) for 64 to 128 K steps of
+    // 1.4 us.  So a workgroup takes tile after tile (persistent_tile), and the first K step of its next tile is on its
+    // way into LDS while it stores the results of this one.
     const int nk = g.K / 64;
+    int tile_m, tile_n;
+    if (!persistent_tile(0, g.tiles_m, g.tiles_n, tile_m, tile_n)) return;
 
     const uint4 *a_src[IA], *w_src[IW];
     int a_dst[IA], w_dst[IW];
 #pragma unroll
-    for (int i = 0; i < IA; ++i) {
-        const int id = wave * IA + i, j = id / (BM / 64), rb = id % (BM / 64);
-        int row = row0 + rb * 64 + lane;
-        row = row < g.M ? row : g.M - 1;
-        a_src[i] = g.a + (int64_t)j * g.M + row;
-        a_dst[i] = j * BM + rb * 64;
-    }
+    for (int i = 0; i < IA; ++i) a_dst[i] = (wave * IA + i) / (BM / 64) * BM + (wave * IA + i) % (BM / 64) * 64;
 #pragma unroll
-    for (int i = 0; i < IW; ++i) {
-        const int id = wave * IW + i, j = id / (BN / 64), rb = id % (BN / 64);
-        int row = col0 + rb * 64 + lane;
-        row = row < g.N ? row : g.N - 1;
-        w_src[i] = g.w + (int64_t)j * g.N + row;
-        w_dst[i] = W_BASE + j * BN + rb * 64;
-    }
+    for (int i = 0; i < IW; ++i) w_dst[i] = W_BASE + (wave * IW + i) / (BN / 64) * BN + (wave * IW + i) % (BN / 64) * 64;
+    // where the loads of the first K step of the tile at (row0, col0) start; rows past the edge of a matrix repeat its last row
+    auto aim = [&](int row0, int col0) {
+#pragma unroll
+        for (int i = 0; i < IA; ++i) {
+            const int id = wave * IA + i, j = id / (BM / 64), rb = id % (BM / 64);
+            int row = row0 + rb * 64 + lane;
+            row = row < g.M ? row : g.M - 1;
+            a_src[i] = g.a + (int64_t)j * g.M + row;
+        }
+#pragma unroll
+        for (int i = 0; i < IW; ++i) {
+            const int id = wave * IW + i, j = id / (BN / 64), rb = id % (BN / 64);
+            int row = col0 + rb * 64 + lane;
+            row = row < g.N ? row : g.N - 1;
+            w_src[i] = g.w + (int64_t)j * g.N + row;
+        }
+    };
     const int64_t a_step = (int64_t)8 * g.M, w_step = (int64_t)8 * g.N;
     auto stage = [&](uint4 *buf) {
         const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_offset(buf));
@@ -363,19 +371,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
     auto staged_wait = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     f32x4_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
-
     const int q = lane / 16, n = lane % 16;
-    // operands of two phases (4 tile rows of A each) and of two half steps (4 tile columns of W each);
-    // the sets the first phase works on start as zeros
+    // operands of two phases (4 tile rows of A each) and of two half steps (4 tile columns of W each)
     uint4 af[2][4], bfr[2][TN];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) af[1][i] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int i = 0; i < TN; ++i) bfr[1][i] = make_uint4(0, 0, 0, 0);
     auto mfma_phase = [&](int ph) { // the 4 TN MFMAs of phase ph = 2 hs + ab: tile rows 4 ab .. 4 ab + 3, operands of half step hs
         const int hs = ph / 2, ab = ph % 2;
 #pragma unroll
@@ -404,26 +402,51 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_planes16_kernel(PlaneGemmAr
     };
 
     int cur = 0, nxt = CELLS;
+    aim(tile_m * BM, g.col_base + tile_n * BN);
     stage(lds);
-    staged_wait();
-    __syncthreads();
-    for (int ks = 0; ks < nk; ++ks) {
-        if (ks + 1 < nk) stage(lds + nxt); // every wave is past its reads of that buffer (the barrier above)
-        k_step(lds + cur);
-        staged_wait();
+    for (int k = 0;; ++k) {
+        const int row0 = tile_m * BM, col0 = g.col_base + tile_n * BN;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
+        // the sets the first phase works on start as zeros
+#pragma unroll
+        for (int i = 0; i < 4; ++i) af[1][i] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < TN; ++i) bfr[1][i] = make_uint4(0, 0, 0, 0);
+        staged_wait(); // the tile's first K step (requested before the loop, or before the last tile's stores) is in LDS
         __syncthreads();
-        const int t2 = cur;
-        cur = nxt;
-        nxt = t2;
-    }
-    mfma_phase(3); // the last phase of the last step
+        for (int ks = 0; ks < nk; ++ks) {
+            if (ks + 1 < nk) stage(lds + nxt); // every wave is past its reads of that buffer (the barrier above)
+            k_step(lds + cur);
+            staged_wait();
+            __syncthreads();
+            const int t2 = cur;
+            cur = nxt;
+            nxt = t2;
+        }
+        mfma_phase(3); // the last phase of the last step
+        const bool more = persistent_tile(k + 1, g.tiles_m, g.tiles_n, tile_m, tile_n);
 
-    if constexpr (EMIT >= 0) {
-        emit_hif4_tile16<BM, BN, WM, WN, EMIT>(acc, lds, row0, g.M, col0, g.N, static_cast<uint32_t *>(g.c), g.c_meta);
-        return;
+        if constexpr (EMIT >= 0) {
+            emit_hif4_tile16<BM, BN, WM, WN, EMIT>(acc, lds, row0, g.M, col0, g.N, static_cast<uint32_t *>(g.c), g.c_meta);
+            if (!more) return;
+            __syncthreads(); // the parked tile is read: LDS may take the next tile's first K step
+            aim(tile_m * BM, g.col_base + tile_n * BN);
+            stage(lds + cur);
+        } else {
+            // both buffers are free (the barrier that ended the K loop): the next tile's first K step goes into `cur`
+            // while the results leave from registers
+            if (more) {
+                aim(tile_m * BM, g.col_base + tile_n * BN);
+                stage(lds + cur);
+            }
+            // ---- epilogue: lane holds column n of each 16 x 16 tile, rows 4 q + r
+            store_acc_16x16<OUT_F32>(acc, g.c, g.ldc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), g.M, g.N);
+            if (!more) return;
+        }
     }
-    // ---- epilogue: lane holds column n of each 16 x 16 tile, rows 4 q + r
-    store_acc_16x16<OUT_F32>(acc, g.c, g.ldc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), g.M, g.N);
 }
 
 #ifndef HIF4_PLANES_MFMA16
@@ -492,8 +515,9 @@ static int launch_planes16(PlaneGemmArgs g, int out_dtype, hipStream_t stream) /
     constexpr size_t lds_bytes = 2 * 8 * (BM + BN) * sizeof(uint4);
     constexpr size_t emit_bytes = emit_lds_bytes<BM, BN>() > lds_bytes ? emit_lds_bytes<BM, BN>() : lds_bytes;
     static_assert(emit_bytes <= 160 * 1024, "fits the LDS of one CU");
-    if (dense_tile_blocks(g.tiles_m, g.tiles_n) > 0x7FFFFFFF) return HIF4_ERR_SHAPE;
-    const dim3 grid((unsigned)dense_tile_blocks(g.tiles_m, g.tiles_n)), block(64 * WM * WN);
+    if ((int64_t)g.tiles_m * g.tiles_n > 0x7FFFFFF0) return HIF4_ERR_SHAPE;
+    // workgroups that stay (see the kernel): 32 per XCD, one per compute unit, or fewer if the tiles are fewer
+    const dim3 grid((unsigned)(8 * persistent_slots(g.tiles_m, g.tiles_n, 32))), block(64 * WM * WN);
     auto launch = [&](auto k, size_t bytes) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return HIF4_ERR_DEVICE;
         hipLaunchKernelGGL(k, grid, block, bytes, stream, g);
