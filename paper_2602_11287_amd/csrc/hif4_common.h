@@ -67,8 +67,14 @@ __device__ __forceinline__ uint32_t pk_fma_f16(uint32_t a, uint32_t b, uint32_t 
     return __builtin_bit_cast(uint32_t, r);
 }
 
-// Bit-field insert: bits of a where mask is set, bits of b elsewhere (v_bfi_b32).
-__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
+// Three-input bit operations through v_bitop3_b32 (truth table: 0xF0 = first, 0xCC = second, 0xAA = third operand).
+// On this chip it issues at the rate of a plain AND (1.3 ns per wave-instruction and SIMD with two or more waves on
+// the SIMD), where v_bfi_b32 and v_and_or_b32 take 2.3 - 2.9 ns like shifts to the left, byte permutes, conversions
+// and every other three-operand integer instruction (measured with loops of independent instructions).
+// Bit-field insert: bits of a where mask is set, bits of b elsewhere.
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return __builtin_amdgcn_bitop3_b32(a, b, mask, 0xE4); }
+// x | (y & mask)
+__device__ __forceinline__ uint32_t or_and(uint32_t x, uint32_t y, uint32_t mask) { return __builtin_amdgcn_bitop3_b32(x, y, mask, 0xF8); }
 
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 __device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }

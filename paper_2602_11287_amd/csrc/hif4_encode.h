@@ -147,8 +147,8 @@ __device__ __forceinline__ uint32_t encode_share(const uint4 (&w)[8 / LPU], int 
         }
         const uint32_t ww[4] = { w[c].x, w[c].y, w[c].z, w[c].w };
         // sign bits: top bit of each BF16 -> bit 3 of the element's byte
-        const uint32_t b0 = ((__builtin_amdgcn_perm(ww[1], ww[0], 0x07050301u) >> 4) & 0x08080808u) | mag0;
-        const uint32_t b1 = ((__builtin_amdgcn_perm(ww[3], ww[2], 0x07050301u) >> 4) & 0x08080808u) | mag1;
+        const uint32_t b0 = or_and(mag0, __builtin_amdgcn_perm(ww[1], ww[0], 0x07050301u) >> 4, 0x08080808u);
+        const uint32_t b1 = or_and(mag1, __builtin_amdgcn_perm(ww[3], ww[2], 0x07050301u) >> 4, 0x08080808u);
         // byte t of the chunk: element t in the low nibble, element 4 + t in the high nibble
         out[c] = special ? 0u : (b0 | (b1 << 4));
     }

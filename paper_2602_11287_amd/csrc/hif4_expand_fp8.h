@@ -53,8 +53,8 @@ __device__ __forceinline__ uint4 expand_dword_fp8(uint32_t c, uint32_t xb, int h
     const float sa = u2f(hs == 0 ? xb << 23 : byte_shl23<1>(xb));    // elements 0..3
     const float sb = u2f(hs == 0 ? byte_shl23<2>(xb) : xb >> 1);     // elements 4..7
     const uint32_t lo = c & 0x07070707u, hi = (c >> 4) & 0x07070707u; // magnitudes, one per byte
-    const uint32_t f8lo = __builtin_amdgcn_perm(FP8_OF_4567, FP8_OF_0123, lo) | ((c << 4) & 0x80808080u);
-    const uint32_t f8hi = __builtin_amdgcn_perm(FP8_OF_4567, FP8_OF_0123, hi) | (c & 0x80808080u);
+    const uint32_t f8lo = or_and(__builtin_amdgcn_perm(FP8_OF_4567, FP8_OF_0123, lo), c << 4, 0x80808080u);
+    const uint32_t f8hi = or_and(__builtin_amdgcn_perm(FP8_OF_4567, FP8_OF_0123, hi), c, 0x80808080u);
     uint4 b;
     b.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(f8lo, sa, false));
     b.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(f8lo, sa, true));
