@@ -71,12 +71,14 @@ def run(hif4, synth, dev, steps, warmup, mfma_peak_tflops, hbm_peak_gbps, large=
         # ---- what the matrix pipeline sustains by itself on operands with random bits (power-limited clock):
         # the ceiling next to which the GEMM rates below are read; the nominal peak stays the roofline's `peak`
         scratch = torch.empty(131072, dtype=torch.float32, device=dev)
-        ceiling = {}
+        ceiling, clock = {}, {}
         for kind, name in ((0, "bf16_32x32x16"), (2, "bf16_16x16x32"), (1, "fp4_scaled_32x32x64")):
             flop = hif4.hif4ref_mfma_loop(kind, 512, scratch)
             ms = _timed(lambda: hif4.hif4ref_mfma_loop(kind, 512, scratch), 50)
             ceiling[name] = round(flop / ms / 1e9, 1)
+            clock[name] = round(float(scratch[0]))   # shader clock of the last launch (its first wave), MHz
         legs["mfma_only_loop_random_operands_TFLOPs"] = ceiling
+        legs["mfma_only_loop_shader_clock_MHz"] = dict(clock, nominal=2400)
         state["bf16_ceiling"] = max(ceiling["bf16_32x32x16"], ceiling["bf16_16x16x32"])  # the 16 x 16 x 32 form sustains more
         state["fp4_ceiling"] = ceiling["fp4_scaled_32x32x64"]
 

@@ -72,7 +72,9 @@ int hif4ref_mxfp4_gemm(const void *a_cells, const void *a_scales, const void *w_
  * v_mfma_scale_f32_32x32x64_f8f6f4); kind 2 runs 16 v_mfma_f32_16x16x32_bf16 per round, the same
  * flops as kind 0.  Timed by the benchmark, it gives the rate the matrix pipeline sustains under
  * its power limit, the ceiling next to which GEMM rates are read.
- *   out  device, 131072 floats, receives checksums nobody needs
+ *   out  device, 131072 floats, receives checksums nobody needs; out[0] instead receives the shader clock, in MHz, that
+ *        the first wave of the launch ran at (its cycle counter over the fixed 100 MHz counter): under a power
+ *        limit the clock falls with the work done per cycle
  */
 int hif4ref_mfma_loop(int kind, int iters, float *out, void *stream);
 

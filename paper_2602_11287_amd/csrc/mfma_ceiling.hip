@@ -12,12 +12,25 @@ __device__ __forceinline__ uint32_t lcg(uint32_t &s)
     return s;
 }
 
+// The first thread of the launch replaces its sum in out[0] by the shader clock it ran at, in MHz: cycles of the
+// shader clock over ticks of the fixed 100 MHz counter, both read before the loop and after the sums (`t` keeps the
+// second reading behind the last MFMA).  Under a power limit the clock falls with the work per cycle, so this is the
+// clock a matrix-bound kernel on real data can expect, not the nominal one.
+__device__ __forceinline__ void store_loop_clock(float *out, long long c0, long long w0, float t)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    asm volatile("" : : "v"(t)); // the sums are complete before the clocks are read again
+    const long long c1 = clock64(), w1 = wall_clock64();
+    out[0] = w1 > w0 ? (float)(c1 - c0) * 100.0f / (float)(w1 - w0) : 0.0f;
+}
+
 // KIND 0: v_mfma_f32_32x32x16_bf16.  KIND 1: v_mfma_scale_f32_32x32x64_f8f6f4 with both
 // operands FP4 (E2M1) and unit scales.  Eight accumulators per wave (the GEMM kernels' shape:
 // 4 x 2 tiles), 8 waves per workgroup, one workgroup per CU-sized slot.
 template <int KIND>
 __global__ __launch_bounds__(512) void mfma_loop_kernel(float *out, int iters, uint32_t seed)
 {
+    const long long c0 = clock64(), w0 = wall_clock64(); // shader clock cycles; a fixed 100 MHz counter
     f32x16_t acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -52,12 +65,14 @@ __global__ __launch_bounds__(512) void mfma_loop_kernel(float *out, int iters, u
 #pragma unroll
         for (int r = 0; r < 16; ++r) t += acc[i][r];
     out[blockIdx.x * 512 + threadIdx.x] = t;
+    store_loop_clock(out, c0, w0, t);
 }
 
 // KIND 2 of the MFMA-only loop: v_mfma_f32_16x16x32_bf16, sixteen accumulators of 16 x 16 per wave and
 // iteration (the same flops per iteration as the eight 32 x 32 x 16 of KIND 0).
 __global__ __launch_bounds__(512) void mfma_loop16_kernel(float *out, int iters, uint32_t seed)
 {
+    const long long c0 = clock64(), w0 = wall_clock64();
     f32x4_t acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = f32x4_t{ 0.f, 0.f, 0.f, 0.f };
@@ -80,6 +95,7 @@ __global__ __launch_bounds__(512) void mfma_loop16_kernel(float *out, int iters,
 #pragma unroll
         for (int r = 0; r < 4; ++r) t += acc[i][r];
     out[blockIdx.x * 512 + threadIdx.x] = t;
+    store_loop_clock(out, c0, w0, t);
 }
 
 int launch_mfma_loop(int kind, int iters, float *out, hipStream_t stream)

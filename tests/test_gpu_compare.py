@@ -135,3 +135,7 @@ def test_mfma_only_loops_run(h):
     assert h.hif4ref_mfma_loop(2, 4, scratch) == 2048 * 4 * 8 * 32768
     assert h.hif4ref_mfma_loop(1, 4, scratch) == 2048 * 4 * 8 * 131072
     torch.cuda.synchronize()
+    for kind in (0, 1, 2):          # out[0]: the shader clock of the launch in MHz (nominal 2400, lower under load)
+        h.hif4ref_mfma_loop(kind, 256, scratch)
+        mhz = float(scratch[0])
+        assert 300.0 < mhz < 3000.0, (kind, mhz)
